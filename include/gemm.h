@@ -1,0 +1,180 @@
+/*
+ * gemm.h -- C ABI of the MI355X (gfx950) GEMM library.
+ *
+ * Computes C = alpha * A * B (the paper's Section II-A definition with beta = 0):
+ *   A  M x K, row-major, leading dimension lda (elements), bf16 or fp8 e4m3 (OCP "e4m3fn")
+ *   B  K x N, row-major, leading dimension ldb
+ *   C  M x N, row-major, leading dimension ldc, bf16, rounded to nearest even from an
+ *      fp32 accumulator.
+ * A, B, C and the split-K workspace are DEVICE pointers owned by the caller; the library
+ * never allocates, frees or copies them.  Per-tensor fp8 scales enter as
+ * cfg.alpha = scale_a * scale_b.
+ *
+ * The kernel that runs is picked by gemm_select(): a deterministic analytical model of
+ * the tiling hierarchy (Section IV of the paper: Algorithms 3-9) evaluated for every
+ * compiled kernel variant -- no timing, no GPU call, no allocation.
+ *
+ * All functions return 0 on success or a negative gemm_status; nothing is launched when
+ * an error is returned.  No function throws or aborts.
+ */
+#ifndef GEMM355_GEMM_H
+#define GEMM355_GEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GEMM_ABI_VERSION 1u
+
+typedef enum gemm_dtype {
+    GEMM_BF16 = 0,     /* A, B bf16 */
+    GEMM_FP8_E4M3 = 1  /* A, B one byte per element, OCP e4m3fn (max finite 448) */
+} gemm_dtype;
+
+typedef enum gemm_status {
+    GEMM_OK = 0,
+    GEMM_ERR_NULL = -1,        /* a required pointer is NULL */
+    GEMM_ERR_SHAPE = -2,       /* M, N or K < 1, or beyond the 32-bit tile arithmetic */
+    GEMM_ERR_DTYPE = -3,       /* dtype is not a gemm_dtype */
+    GEMM_ERR_CFG_ILLEGAL = -4, /* cfg fields do not describe a compiled kernel legal for the shape */
+    GEMM_ERR_ALIGN = -5,       /* pointer not 16-byte aligned, or ld/N/K not a multiple of 16 bytes */
+    GEMM_ERR_WORKSPACE = -6,   /* split_k > 1 and the registered workspace is missing or too small */
+    GEMM_ERR_ABI = -7,         /* cfg.abi_version differs from GEMM_ABI_VERSION */
+    GEMM_ERR_HIP = -8,         /* the HIP runtime refused the launch */
+    GEMM_ERR_INDEX = -9        /* gemm_cfg_at: index outside [0, gemm_cfg_count) */
+} gemm_status;
+
+/* Bottleneck label of a prediction (Section IV-D's taxonomy). */
+typedef enum gemm_bottleneck {
+    GEMM_BOUND_COMPUTE_FULL = 0, /* all CUs busy, matrix cores limit */
+    GEMM_BOUND_COMPUTE_UNDER = 1,/* matrix cores limit, but fewer tiles than CUs in the last wave */
+    GEMM_BOUND_LS_ISSUE = 2,     /* per-CU vector-memory issue rate */
+    GEMM_BOUND_LDS = 3,          /* LDS read bandwidth */
+    GEMM_BOUND_L2 = 4,           /* L2 bandwidth */
+    GEMM_BOUND_MALL = 5,         /* Infinity Cache (MALL) bandwidth */
+    GEMM_BOUND_HBM = 6,          /* HBM bandwidth + latency */
+    GEMM_BOUND_LAUNCH = 7        /* fixed launch / prologue / epilogue cost dominates */
+} gemm_bottleneck;
+
+/*
+ * Hardware descriptor H of the model (Section IV: CU count, cache scopes, bandwidths,
+ * memory latency, matrix-instruction issue intervals).  Bandwidths are bytes per
+ * compute clock; the defaults describe one MI355X and are compiled in.
+ */
+typedef struct gemm_hw {
+    int32_t n_cu;              /* compute units on the device (256) */
+    int32_t n_xcd;             /* L2 scopes; CUs per L2 = n_cu / n_xcd (8 -> 32) */
+    int32_t simd_per_cu;       /* 4 */
+    int32_t reserved0;
+    double lds_bytes;          /* per CU (163840) */
+    double l2_bytes;           /* per XCD (4 MiB) */
+    double mall_bytes;         /* device (256 MiB) */
+    double clk_ghz;            /* sustained compute clock used to convert clocks to time */
+    double hbm_bytes_per_clk;  /* device total */
+    double mall_bytes_per_clk; /* device total */
+    double l2_bytes_per_clk;   /* per XCD */
+    double lds_bytes_per_clk;  /* per CU */
+    double vmem_bytes_per_clk; /* per CU vector-memory (L1) rate */
+    double mem_latency_clk;    /* L_lat of Algorithm 7 */
+    double cache_eff_frac;     /* fraction of a cache's capacity that holds reusable tiles */
+    double launch_clk;         /* fixed cost per kernel launch, clocks */
+    double wg_overhead_clk;    /* fixed cost per workgroup (dispatch, address setup, drain) */
+    double l_mi_clk[2][2];     /* issue interval L_MI of one MFMA: [dtype][0: 32x32, 1: 16x16] */
+} gemm_hw;
+
+/*
+ * A kernel configuration: plain data, no hidden pointers, so it can be copied and cached.
+ * gemm_select / gemm_cfg_at fill every field; gemm_run validates them again.
+ */
+typedef struct gemm_cfg {
+    uint32_t abi_version;
+    int32_t dtype;            /* gemm_dtype */
+    int64_t M, N, K;
+    int64_t lda, ldb, ldc;    /* elements; gemm_select sets K, N, N */
+    int32_t kernel_id;        /* index into the compiled variant table */
+    uint16_t block_m, block_n, block_k; /* workgroup tile M_T x N_T x K_T */
+    uint8_t waves_m, waves_n; /* wave grid inside the workgroup */
+    uint8_t mfma;             /* 32: 32x32xk MFMA, 16: 16x16xk MFMA */
+    uint8_t k_unroll;         /* MFMA k-steps unrolled per K_T slab (block_k / MI_K) */
+    uint16_t split_k;         /* spatial K unroll: K slices computed by different workgroups */
+    uint16_t group_m;         /* cache-tile height in tiles (Algorithm 6's f_m); tiles run column-major inside a band of group_m tile rows */
+    uint16_t group_n;         /* cache-tile width f_n = CUs per L2 / f_m (informational) */
+    uint8_t xcd_remap;        /* 1: workgroup ids are renumbered so that each XCD owns a contiguous id range */
+    uint8_t reserved[3];
+    float alpha;              /* default 1; the caller may overwrite it before gemm_run */
+    int32_t bottleneck;       /* gemm_bottleneck of the prediction */
+    double predicted_us;      /* model's total latency for this cfg */
+} gemm_cfg;
+
+/* Terms of the model for one cfg (clocks unless said otherwise), for tests and reports. */
+typedef struct gemm_prediction {
+    double n_mi;          /* Algorithm 3: matrix instructions per workgroup tile and K slab */
+    double l_compute;     /* Algorithm 3 spread over the SIMDs, clocks per K slab */
+    double tiles;         /* Algorithm 4: output tiles x split_k */
+    double waves;         /* Algorithm 4: omega */
+    double active_cu;     /* Algorithm 4: CUs busy in the last wave */
+    double f_m, f_n;      /* Algorithm 6 pair chosen for the L2 scope */
+    double h_l2, h_mall;  /* Algorithm 5 hit rates after the capacity derate */
+    double l_issue, l_lds, l_l2, l_mall, l_hbm; /* Algorithm 7 terms, full wave */
+    double l_mem;         /* Algorithm 7: max of the terms above, full wave */
+    double l_mem_tail;    /* same with C = active_cu */
+    double l_prologue, l_epilogue, l_iter; /* Algorithm 8, full wave */
+    double iters;         /* Algorithm 8: I */
+    double l_tile;        /* Algorithm 8, full wave */
+    double l_tile_tail;   /* Algorithm 8 with C = active_cu */
+    double l_reduce;      /* split-K reduction pass, clocks (0 when split_k = 1) */
+    double l_total;       /* Algorithm 9 with the tail reading, clocks */
+    double total_us;
+    int32_t bottleneck;
+    int32_t reserved;
+} gemm_prediction;
+
+uint32_t gemm_abi_version(void);
+const char *gemm_strerror(int status);
+
+/*
+ * Analytical selection (Algorithms 3-9 over every compiled variant, arg-min of predicted
+ * latency, deterministic tie-break).  Pure host code: works with no GPU present.
+ * out: caller-owned.  Requires M, N, K >= 1; N and K must be multiples of 8 (bf16) or
+ * 16 (fp8) elements (else GEMM_ERR_ALIGN).
+ */
+int gemm_select(int64_t M, int64_t N, int64_t K, int dtype, gemm_cfg *out);
+
+/*
+ * Enqueue C = alpha * A * B on hip_stream (a hipStream_t; NULL = the default stream) with
+ * the kernel cfg names; returns without synchronising.  A, B, C: device pointers,
+ * 16-byte aligned.  When cfg->split_k > 1 a workspace of gemm_workspace_bytes(cfg) must
+ * have been registered with gemm_set_workspace for the current device.
+ */
+int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void *C, void *hip_stream);
+
+/* fp32 partial-sum slabs: split_k * M * N * 4 bytes when split_k > 1, else 0. */
+size_t gemm_workspace_bytes(const gemm_cfg *cfg);
+
+/* Register (or, with NULL/0, drop) a caller-owned device buffer used by split-K runs.
+ * The buffer must outlive every gemm_run that uses it; runs that share it must be
+ * stream-ordered. */
+int gemm_set_workspace(void *dev_ptr, size_t bytes);
+
+/* Enumeration of the compiled configuration space, for the offline sweep only:
+ * idx in [0, gemm_cfg_count(dtype)).  gemm_cfg_at returns GEMM_ERR_CFG_ILLEGAL when
+ * variant idx cannot run the shape (e.g. more K slices than K slabs). */
+int gemm_cfg_count(int dtype);
+int gemm_cfg_at(int idx, int64_t M, int64_t N, int64_t K, int dtype, gemm_cfg *out);
+
+/* Model terms for a cfg (Algorithms 3-9), host only. */
+int gemm_predict(const gemm_cfg *cfg, gemm_prediction *out);
+
+/* Hardware descriptor: get a copy / replace it (process-wide; not thread-safe against
+ * concurrent gemm_select).  gemm_hw_reset restores the MI355X defaults. */
+int gemm_hw_get(gemm_hw *out);
+int gemm_hw_set(const gemm_hw *in);
+int gemm_hw_reset(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GEMM355_GEMM_H */

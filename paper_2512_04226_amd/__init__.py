@@ -1,0 +1,4 @@
+"""MI355X-native GEMM with an analytical kernel selector (arXiv 2512.04226's method).
+
+`binding` mirrors the C ABI of include/gemm.h; `workloads` generates the seeded inputs.
+"""

@@ -1,0 +1,183 @@
+"""ctypes binding of include/gemm.h: same names, argument marshalling only.
+
+Tensors are torch CUDA (ROCm) tensors used purely as device buffers: bf16 operands as
+torch.bfloat16 (or int16/uint16 bit patterns), fp8 operands as torch.uint8 or
+torch.float8_e4m3fn.  Every computation happens inside libgemm355.so; if the library is
+missing this module raises at import.
+"""
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libgemm355.so")
+
+GEMM_BF16 = 0
+GEMM_FP8_E4M3 = 1
+GEMM_ABI_VERSION = 1
+
+STATUS = {0: "GEMM_OK", -1: "GEMM_ERR_NULL", -2: "GEMM_ERR_SHAPE", -3: "GEMM_ERR_DTYPE", -4: "GEMM_ERR_CFG_ILLEGAL",
+          -5: "GEMM_ERR_ALIGN", -6: "GEMM_ERR_WORKSPACE", -7: "GEMM_ERR_ABI", -8: "GEMM_ERR_HIP", -9: "GEMM_ERR_INDEX"}
+BOTTLENECKS = ("compute_full", "compute_under_occupied", "ls_issue", "lds", "l2", "mall", "hbm", "launch")
+
+
+class GemmError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        RuntimeError.__init__(self, "%s: %s (%d: %s)" % (where, STATUS.get(status, "?"), status,
+                                                         gemm_strerror(status)))
+
+
+class gemm_hw(ctypes.Structure):
+    _fields_ = [("n_cu", ctypes.c_int32), ("n_xcd", ctypes.c_int32), ("simd_per_cu", ctypes.c_int32),
+                ("reserved0", ctypes.c_int32), ("lds_bytes", ctypes.c_double), ("l2_bytes", ctypes.c_double),
+                ("mall_bytes", ctypes.c_double), ("clk_ghz", ctypes.c_double),
+                ("hbm_bytes_per_clk", ctypes.c_double), ("mall_bytes_per_clk", ctypes.c_double),
+                ("l2_bytes_per_clk", ctypes.c_double), ("lds_bytes_per_clk", ctypes.c_double),
+                ("vmem_bytes_per_clk", ctypes.c_double), ("mem_latency_clk", ctypes.c_double),
+                ("cache_eff_frac", ctypes.c_double), ("launch_clk", ctypes.c_double),
+                ("wg_overhead_clk", ctypes.c_double), ("l_mi_clk", (ctypes.c_double * 2) * 2)]
+
+
+class gemm_cfg(ctypes.Structure):
+    _fields_ = [("abi_version", ctypes.c_uint32), ("dtype", ctypes.c_int32), ("M", ctypes.c_int64),
+                ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("lda", ctypes.c_int64), ("ldb", ctypes.c_int64),
+                ("ldc", ctypes.c_int64), ("kernel_id", ctypes.c_int32), ("block_m", ctypes.c_uint16),
+                ("block_n", ctypes.c_uint16), ("block_k", ctypes.c_uint16), ("waves_m", ctypes.c_uint8),
+                ("waves_n", ctypes.c_uint8), ("mfma", ctypes.c_uint8), ("k_unroll", ctypes.c_uint8),
+                ("split_k", ctypes.c_uint16), ("group_m", ctypes.c_uint16), ("group_n", ctypes.c_uint16),
+                ("xcd_remap", ctypes.c_uint8), ("reserved", ctypes.c_uint8 * 3), ("alpha", ctypes.c_float),
+                ("bottleneck", ctypes.c_int32), ("predicted_us", ctypes.c_double)]
+
+    def describe(self):
+        return ("%dx%dx%d w%dx%d mfma%d split%d g%d%s" % (self.block_m, self.block_n, self.block_k, self.waves_m,
+                                                          self.waves_n, self.mfma, self.split_k, self.group_m,
+                                                          "" if self.xcd_remap else " noxcd"))
+
+    def copy(self):
+        c = gemm_cfg()
+        ctypes.memmove(ctypes.byref(c), ctypes.byref(self), ctypes.sizeof(gemm_cfg))
+        return c
+
+
+class gemm_prediction(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_double) for n in (
+        "n_mi", "l_compute", "tiles", "waves", "active_cu", "f_m", "f_n", "h_l2", "h_mall", "l_issue", "l_lds",
+        "l_l2", "l_mall", "l_hbm", "l_mem", "l_mem_tail", "l_prologue", "l_epilogue", "l_iter", "iters", "l_tile",
+        "l_tile_tail", "l_reduce", "l_total", "total_us")] + [("bottleneck", ctypes.c_int32),
+                                                              ("reserved", ctypes.c_int32)]
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError("libgemm355.so is not built: run `python -m paper_2512_04226_amd.build` "
+                      "(there is no fallback path)")
+_lib = ctypes.CDLL(LIB_PATH)
+
+_i64, _int, _vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+_lib.gemm_abi_version.restype = ctypes.c_uint32
+_lib.gemm_abi_version.argtypes = []
+_lib.gemm_strerror.restype = ctypes.c_char_p
+_lib.gemm_strerror.argtypes = [_int]
+_lib.gemm_select.restype = _int
+_lib.gemm_select.argtypes = [_i64, _i64, _i64, _int, ctypes.POINTER(gemm_cfg)]
+_lib.gemm_run.restype = _int
+_lib.gemm_run.argtypes = [ctypes.POINTER(gemm_cfg), _vp, _vp, _vp, _vp]
+_lib.gemm_workspace_bytes.restype = ctypes.c_size_t
+_lib.gemm_workspace_bytes.argtypes = [ctypes.POINTER(gemm_cfg)]
+_lib.gemm_set_workspace.restype = _int
+_lib.gemm_set_workspace.argtypes = [_vp, ctypes.c_size_t]
+_lib.gemm_cfg_count.restype = _int
+_lib.gemm_cfg_count.argtypes = [_int]
+_lib.gemm_cfg_at.restype = _int
+_lib.gemm_cfg_at.argtypes = [_int, _i64, _i64, _i64, _int, ctypes.POINTER(gemm_cfg)]
+_lib.gemm_predict.restype = _int
+_lib.gemm_predict.argtypes = [ctypes.POINTER(gemm_cfg), ctypes.POINTER(gemm_prediction)]
+_lib.gemm_hw_get.restype = _int
+_lib.gemm_hw_get.argtypes = [ctypes.POINTER(gemm_hw)]
+_lib.gemm_hw_set.restype = _int
+_lib.gemm_hw_set.argtypes = [ctypes.POINTER(gemm_hw)]
+_lib.gemm_hw_reset.restype = _int
+_lib.gemm_hw_reset.argtypes = []
+
+
+def gemm_abi_version():
+    return int(_lib.gemm_abi_version())
+
+
+def gemm_strerror(status):
+    return _lib.gemm_strerror(int(status)).decode()
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise GemmError(rc, where)
+
+
+def gemm_select(M, N, K, dtype):
+    cfg = gemm_cfg()
+    _check(_lib.gemm_select(M, N, K, dtype, ctypes.byref(cfg)), "gemm_select")
+    return cfg
+
+
+def gemm_cfg_count(dtype):
+    n = _lib.gemm_cfg_count(dtype)
+    if n < 0:
+        raise GemmError(n, "gemm_cfg_count")
+    return n
+
+
+def gemm_cfg_at(idx, M, N, K, dtype):
+    """Returns the cfg, or None when variant idx is not legal for the shape."""
+    cfg = gemm_cfg()
+    rc = _lib.gemm_cfg_at(idx, M, N, K, dtype, ctypes.byref(cfg))
+    if rc == -4:
+        return None
+    _check(rc, "gemm_cfg_at")
+    return cfg
+
+
+def gemm_predict(cfg):
+    p = gemm_prediction()
+    _check(_lib.gemm_predict(ctypes.byref(cfg), ctypes.byref(p)), "gemm_predict")
+    return p
+
+
+def gemm_hw_get():
+    h = gemm_hw()
+    _check(_lib.gemm_hw_get(ctypes.byref(h)), "gemm_hw_get")
+    return h
+
+
+def gemm_hw_set(h):
+    _check(_lib.gemm_hw_set(ctypes.byref(h)), "gemm_hw_set")
+
+
+def gemm_hw_reset():
+    _check(_lib.gemm_hw_reset(), "gemm_hw_reset")
+
+
+def gemm_workspace_bytes(cfg):
+    return int(_lib.gemm_workspace_bytes(ctypes.byref(cfg)))
+
+
+def gemm_set_workspace(tensor):
+    """Register a caller-owned device tensor (or None) as the split-K workspace."""
+    if tensor is None:
+        _check(_lib.gemm_set_workspace(None, 0), "gemm_set_workspace")
+    else:
+        _check(_lib.gemm_set_workspace(tensor.data_ptr(), tensor.numel() * tensor.element_size()),
+               "gemm_set_workspace")
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def gemm_run(cfg, A, B, C, stream=None):
+    """Enqueue C = alpha * A * B.  stream: a torch.cuda.Stream, a raw hipStream_t int, or
+    None for torch's current stream."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    _check(_lib.gemm_run(ctypes.byref(cfg), _ptr(A), _ptr(B), _ptr(C), ctypes.c_void_p(stream)), "gemm_run")

@@ -1,0 +1,357 @@
+// Analytical latency model and selector (host only; no HIP call anywhere in this file).
+//
+// Follows Section IV of the paper: Algorithm 3 (compute latency of a workgroup tile),
+// Algorithm 4 (waves and active CUs of the last wave), Algorithms 5/6 (cache-tile
+// factorisations and hit rate) with the capacity derate of Section IV-C, Algorithm 7
+// (memory latency of one K iteration), Algorithm 8 (output-tile latency) and Algorithm 9
+// (total latency).  Quantities are bytes and compute clocks.  Where the paper leaves a step
+// open the choice made here is stated next to the code.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+#include "../../include/gemm.h"
+#include "model.hpp"
+#include "variants.hpp"
+
+namespace g355 {
+
+#define G355_X(bm, bn, bk, wm, wn, mi) {bm, bn, bk, wm, wn, mi},
+static const Variant kVariantsBf16[] = {G355_VARIANTS_BF16(G355_X)};
+static const Variant kVariantsFp8[] = {G355_VARIANTS_FP8(G355_X)};
+#undef G355_X
+
+int variant_count(int dtype)
+{
+    return dtype == GEMM_BF16 ? (int)(sizeof(kVariantsBf16) / sizeof(Variant))
+                              : (int)(sizeof(kVariantsFp8) / sizeof(Variant));
+}
+const Variant &variant_at(int dtype, int id)
+{
+    return dtype == GEMM_BF16 ? kVariantsBf16[id] : kVariantsFp8[id];
+}
+
+// One MI355X.  Matrix-instruction issue intervals and the HBM rate come from
+// register-resident MFMA loops and a streaming read on the device, expressed in 2.4 GHz
+// clocks; cache rates are the public per-channel figures.
+static gemm_hw make_default_hw()
+{
+    gemm_hw h;
+    std::memset(&h, 0, sizeof(h));
+    h.n_cu = 256;
+    h.n_xcd = 8;
+    h.simd_per_cu = 4;
+    h.lds_bytes = 160.0 * 1024;
+    h.l2_bytes = 4.0 * 1024 * 1024;
+    h.mall_bytes = 256.0 * 1024 * 1024;
+    h.clk_ghz = 2.4;
+    h.hbm_bytes_per_clk = 2600.0;   // ~6.2 TB/s sustained of the 8 TB/s pins
+    h.mall_bytes_per_clk = 5800.0;  // ~14 TB/s
+    h.l2_bytes_per_clk = 2048.0;    // 16 channels x 128 B per XCD
+    h.lds_bytes_per_clk = 128.0;
+    h.vmem_bytes_per_clk = 64.0;
+    h.mem_latency_clk = 2000.0;
+    h.cache_eff_frac = 0.5;
+    h.launch_clk = 6000.0;
+    h.wg_overhead_clk = 1500.0;
+    h.l_mi_clk[GEMM_BF16][0] = 39.7;      // v_mfma_f32_32x32x16_bf16  (2030 TFLOP/s device-wide)
+    h.l_mi_clk[GEMM_BF16][1] = 31.8;      // v_mfma_f32_16x16x32_bf16  (1267 TFLOP/s)
+    h.l_mi_clk[GEMM_FP8_E4M3][0] = 69.4;  // v_mfma_f32_32x32x64_f8f6f4 (4642 TFLOP/s)
+    h.l_mi_clk[GEMM_FP8_E4M3][1] = 65.7;  // v_mfma_f32_16x16x128_f8f6f4 (4904 TFLOP/s)
+    return h;
+}
+
+static gemm_hw g_hw = make_default_hw();
+
+const gemm_hw &hw_current() { return g_hw; }
+void hw_replace(const gemm_hw &h) { g_hw = h; }
+void hw_reset() { g_hw = make_default_hw(); }
+
+static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+int elem_bytes(int dtype) { return dtype == GEMM_BF16 ? 2 : 1; }
+
+int mfma_k(int dtype, int mfma)
+{
+    if (dtype == GEMM_BF16)
+        return mfma == 32 ? 16 : 32;
+    return mfma == 32 ? 64 : 128;
+}
+
+int64_t k_per_split(const Variant &v, int64_t K, int split_k)
+{
+    return cdiv(cdiv(K, v.block_k), split_k) * v.block_k;
+}
+
+bool variant_legal(const gemm_hw &hw, const Variant &v, int dtype, int64_t M, int64_t N, int64_t K, int split_k)
+{
+    (void)M;
+    (void)N;
+    const int es = elem_bytes(dtype);
+    const double lds = 2.0 * (v.block_m + v.block_n) * v.block_k * es;
+    if (lds > hw.lds_bytes)
+        return false;
+    if (split_k < 1)
+        return false;
+    if (split_k > 1) {
+        // every K slice must own at least one slab
+        const int64_t kps = k_per_split(v, K, split_k);
+        if ((int64_t)(split_k - 1) * kps >= K)
+            return false;
+    }
+    return true;
+}
+
+// Workgroups of this variant that fit one CU at a time (LDS, registers, wave slots).
+static int occupancy(const gemm_hw &hw, const Variant &v, int dtype)
+{
+    const int es = elem_bytes(dtype);
+    const double lds = 2.0 * (v.block_m + v.block_n) * v.block_k * es;
+    const int waves = v.waves_m * v.waves_n;
+    const int nt = waves * 64;
+    // registers per lane: fp32 accumulators + staged slab + fragments and addresses
+    const double acc = (double)v.block_m * v.block_n / nt;
+    const double stage = (double)(v.block_m + v.block_n) * v.block_k * es / 4.0 / nt;
+    const double vgpr = acc + stage + 48.0;
+    int waves_per_simd = (int)std::floor(512.0 / vgpr);
+    waves_per_simd = std::max(1, std::min(8, waves_per_simd));
+    const int by_regs = std::max(1, waves_per_simd * hw.simd_per_cu / waves);
+    const int by_lds = std::max(1, (int)std::floor(hw.lds_bytes / lds));
+    return std::max(1, std::min(std::min(by_regs, by_lds), 8));
+}
+
+// Algorithm 5 with the cache tile clipped to the tile grid.
+static double hit_rate(double f_m, double f_n, double bm, double bn)
+{
+    const double u = f_m * bm + f_n * bn;
+    const double r = f_m * f_n * (bm + bn);
+    if (r <= 0)
+        return 0.0;
+    const double h = 1.0 - u / r;
+    return std::min(1.0, std::max(0.0, h));
+}
+
+// Algorithm 6 + the choice of the pair: among all (f_m, f_n) with f_m * f_n = scope, clipped
+// to the tile grid, take the one with the highest Algorithm-5 hit rate; ties go to the pair
+// whose cache tile is closest to square in elements, then to the wider one.
+static void best_factor_pair(int scope, const Variant &v, int64_t tiles_m, int64_t tiles_n, double *fm_out,
+                             double *fn_out, int *fm_raw_out)
+{
+    double best_h = -1.0, best_fm = 1, best_fn = 1, best_skew = 0;
+    int best_raw = 1;
+    for (int i = 1; i <= scope; ++i) {
+        if (scope % i)
+            continue;
+        const int j = scope / i;
+        const double fm = (double)std::min<int64_t>(i, tiles_m);
+        const double fn = (double)std::min<int64_t>(j, tiles_n);
+        const double h = hit_rate(fm, fn, v.block_m, v.block_n);
+        const double skew = std::fabs(fm * v.block_m - fn * v.block_n);
+        bool better = false;
+        if (h > best_h + 1e-12)
+            better = true;
+        else if (std::fabs(h - best_h) <= 1e-12) {
+            if (skew < best_skew - 1e-9)
+                better = true;
+            else if (std::fabs(skew - best_skew) <= 1e-9 && fn > best_fn)
+                better = true;
+        }
+        if (better) {
+            best_h = h;
+            best_fm = fm;
+            best_fn = fn;
+            best_skew = skew;
+            best_raw = i;
+        }
+    }
+    *fm_out = best_fm;
+    *fn_out = best_fn;
+    *fm_raw_out = best_raw;
+}
+
+struct MemTerms {
+    double l_issue, l_lds, l_l2, l_mall, l_hbm, l_mem;
+};
+
+// Algorithm 7 for one K iteration.  `per_cu` = tiles a CU works on at once, `active` = CUs
+// busy.  Terms: per-CU vector-memory issue, LDS fragment reads (the software-managed-memory
+// bound of Section IV-D, which the printed algorithm leaves out), L2 (per XCD), MALL and HBM.
+static MemTerms memory_latency(const gemm_hw &hw, const Variant &v, int es, double per_cu, double active, double h1,
+                               double h2)
+{
+    MemTerms t;
+    const double ld_cu = (double)(v.block_m + v.block_n) * v.block_k * es * per_cu;  // bytes per CU per iteration
+    t.l_issue = ld_cu / hw.vmem_bytes_per_clk;
+    // every wave reads its A rows and B columns of the slab from LDS
+    const double lds_rd = ((double)v.block_m * v.waves_n + (double)v.block_n * v.waves_m) * v.block_k * es * per_cu;
+    t.l_lds = lds_rd / hw.lds_bytes_per_clk;
+    const double cus_per_l2 = (double)hw.n_cu / hw.n_xcd;
+    const double xcds_busy = std::min<double>(hw.n_xcd, std::max(1.0, active));       // round-robin dispatch
+    const double total = ld_cu * active;
+    t.l_l2 = (total / xcds_busy) / hw.l2_bytes_per_clk;
+    (void)cus_per_l2;
+    const double t2 = (1.0 - h1) * total;
+    t.l_mall = t2 / hw.mall_bytes_per_clk;
+    const double tm = (1.0 - h2) * t2;
+    t.l_hbm = tm / hw.hbm_bytes_per_clk + hw.mem_latency_clk / std::max(1.0, per_cu);
+    t.l_mem = std::max(std::max(t.l_issue, t.l_lds), std::max(std::max(t.l_l2, t.l_mall), t.l_hbm));
+    return t;
+}
+
+static int label_of(const MemTerms &t, double l_comp, bool under, double fixed, double loop)
+{
+    if (fixed > loop)
+        return GEMM_BOUND_LAUNCH;
+    if (l_comp >= t.l_mem)
+        return under ? GEMM_BOUND_COMPUTE_UNDER : GEMM_BOUND_COMPUTE_FULL;
+    if (t.l_mem == t.l_hbm)
+        return GEMM_BOUND_HBM;
+    if (t.l_mem == t.l_mall)
+        return GEMM_BOUND_MALL;
+    if (t.l_mem == t.l_l2)
+        return GEMM_BOUND_L2;
+    if (t.l_mem == t.l_lds)
+        return GEMM_BOUND_LDS;
+    return GEMM_BOUND_LS_ISSUE;
+}
+
+void predict(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, const Variant &v, int split_k,
+             gemm_prediction *p, int *group_m, int *group_n)
+{
+    std::memset(p, 0, sizeof(*p));
+    const int es = elem_bytes(dtype);
+    const int waves_wg = v.waves_m * v.waves_n;
+    const int mi_k = mfma_k(dtype, v.mfma);
+
+    // Algorithm 3, spread over the SIMDs that the workgroups resident on a CU occupy.
+    const double n_mi = (double)cdiv(v.block_m, v.mfma) * cdiv(v.block_n, v.mfma) * cdiv(v.block_k, mi_k);
+    const double l_mi = hw.l_mi_clk[dtype][v.mfma == 32 ? 0 : 1];
+    p->n_mi = n_mi;
+
+    // Algorithm 4, with K slices counted as tiles and `occ` workgroups per CU as slots.
+    const int64_t tiles_m = cdiv(M, v.block_m), tiles_n = cdiv(N, v.block_n);
+    const double tiles = (double)tiles_m * tiles_n * split_k;
+    const int occ = occupancy(hw, v, dtype);
+    const double slots = (double)hw.n_cu * occ;
+    const double waves = std::ceil(tiles / slots);
+    const double tail_tiles = tiles - (waves - 1) * slots;            // in (0, slots]
+    const double active = std::min<double>(tail_tiles, hw.n_cu);      // T_out % N_CU, with 0 read as N_CU
+    const double tail_per_cu = std::ceil(tail_tiles / hw.n_cu);
+    p->tiles = tiles;
+    p->waves = waves;
+    p->active_cu = active;
+
+    // Algorithms 5/6: L2 scope = CUs of one XCD (times resident workgroups), MALL scope = device.
+    const int l2_scope = hw.n_cu / hw.n_xcd * occ;
+    double fm, fn, fm2, fn2;
+    int fm_raw, fm2_raw;
+    best_factor_pair(l2_scope, v, tiles_m, tiles_n, &fm, &fn, &fm_raw);
+    best_factor_pair(hw.n_cu * occ, v, tiles_m, tiles_n, &fm2, &fn2, &fm2_raw);
+    double h1 = hit_rate(fm, fn, v.block_m, v.block_n);
+    double h2 = hit_rate(fm2, fn2, v.block_m, v.block_n);
+    // Capacity derate: the working set of one K step of the cache tile (both LDS stages in
+    // flight) against the usable share of the cache; beyond it the hit rate shrinks in
+    // proportion.
+    const double fp1 = (fm * v.block_m + fn * v.block_n) * v.block_k * es * 2.0;
+    const double fp2 = (fm2 * v.block_m + fn2 * v.block_n) * v.block_k * es * 2.0;
+    h1 *= std::min(1.0, hw.cache_eff_frac * hw.l2_bytes / fp1);
+    h2 *= std::min(1.0, hw.cache_eff_frac * hw.mall_bytes / fp2);
+    p->f_m = fm;
+    p->f_n = fn;
+    p->h_l2 = h1;
+    p->h_mall = h2;
+    *group_m = (int)std::max<int64_t>(1, std::min<int64_t>(fm_raw, tiles_m));
+    *group_n = std::max(1, l2_scope / fm_raw);
+
+    // K slabs per tile (Algorithm 8's I + 1), with the reduction split over split_k slices.
+    const double slabs = (double)(k_per_split(v, K, split_k) / v.block_k);
+    p->iters = slabs - 1.0;
+    const double out_bytes = (split_k > 1) ? 4.0 : 2.0;
+
+    auto tile_latency = [&](double per_cu, double act, MemTerms *mt_out, double *l_comp_out, double *pro, double *epi,
+                            double *iter) {
+        const double simds = std::min<double>(hw.simd_per_cu, per_cu * waves_wg);
+        const double l_comp = n_mi * l_mi * per_cu / simds;
+        const MemTerms mt = memory_latency(hw, v, es, per_cu, act, h1, h2);
+        const double l_pro = mt.l_mem + hw.wg_overhead_clk;
+        // the store stage scales with the output tile only; results leave through HBM
+        const double l_epi = act * per_cu * v.block_m * v.block_n * out_bytes / hw.hbm_bytes_per_clk;
+        const double l_iter = std::max(l_comp, mt.l_mem);
+        *mt_out = mt;
+        *l_comp_out = l_comp;
+        *pro = l_pro;
+        *epi = l_epi;
+        *iter = l_iter;
+        // I iterations overlap load and compute; the last slab's compute is exposed
+        return l_pro + l_epi + l_iter * (slabs - 1.0) + l_comp;
+    };
+
+    MemTerms mt_full, mt_tail;
+    double lc_full, lc_tail, pro, epi, iter, pro_t, epi_t, iter_t;
+    const double l_tile_full = tile_latency((double)occ, (double)hw.n_cu, &mt_full, &lc_full, &pro, &epi, &iter);
+    const double l_tile_tail = tile_latency(tail_per_cu, active, &mt_tail, &lc_tail, &pro_t, &epi_t, &iter_t);
+    const bool has_full = waves > 1.0;
+    const MemTerms &mt = has_full ? mt_full : mt_tail;
+    p->l_compute = has_full ? lc_full : lc_tail;
+    p->l_issue = mt.l_issue;
+    p->l_lds = mt.l_lds;
+    p->l_l2 = mt.l_l2;
+    p->l_mall = mt.l_mall;
+    p->l_hbm = mt.l_hbm;
+    p->l_mem = mt.l_mem;
+    p->l_mem_tail = mt_tail.l_mem;
+    p->l_prologue = has_full ? pro : pro_t;
+    p->l_epilogue = has_full ? epi : epi_t;
+    p->l_iter = has_full ? iter : iter_t;
+    p->l_tile = has_full ? l_tile_full : l_tile_tail;
+    p->l_tile_tail = l_tile_tail;
+
+    // Split-K: a second pass sums the fp32 slabs (read split_k * M * N * 4, write M * N * 2).
+    double l_reduce = 0.0;
+    if (split_k > 1) {
+        const double bytes = (double)M * N * (4.0 * split_k + 2.0);
+        const double rate = (bytes <= hw.cache_eff_frac * hw.mall_bytes) ? hw.mall_bytes_per_clk : hw.hbm_bytes_per_clk;
+        l_reduce = hw.launch_clk + hw.mem_latency_clk + bytes / rate;
+    }
+    p->l_reduce = l_reduce;
+
+    // Algorithm 9, with full waves and the under-occupied last wave priced separately.
+    p->l_total = hw.launch_clk + (waves - 1.0) * l_tile_full + l_tile_tail + l_reduce;
+    p->total_us = p->l_total / (hw.clk_ghz * 1e3);
+    const double fixed = hw.launch_clk + l_reduce + waves * (p->l_prologue + p->l_epilogue);
+    p->bottleneck = label_of(mt, p->l_compute, active < hw.n_cu && waves == 1.0, fixed, p->l_total - fixed);
+}
+
+void fill_cfg(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, int kernel_id, int split_k, gemm_cfg *c)
+{
+    const Variant &v = variant_at(dtype, kernel_id);
+    gemm_prediction p;
+    int gm, gn;
+    predict(hw, dtype, M, N, K, v, split_k, &p, &gm, &gn);
+    std::memset(c, 0, sizeof(*c));
+    c->abi_version = GEMM_ABI_VERSION;
+    c->dtype = dtype;
+    c->M = M;
+    c->N = N;
+    c->K = K;
+    c->lda = K;
+    c->ldb = N;
+    c->ldc = N;
+    c->kernel_id = kernel_id;
+    c->block_m = (uint16_t)v.block_m;
+    c->block_n = (uint16_t)v.block_n;
+    c->block_k = (uint16_t)v.block_k;
+    c->waves_m = (uint8_t)v.waves_m;
+    c->waves_n = (uint8_t)v.waves_n;
+    c->mfma = (uint8_t)v.mfma;
+    c->k_unroll = (uint8_t)(v.block_k / mfma_k(dtype, v.mfma));
+    c->split_k = (uint16_t)split_k;
+    c->group_m = (uint16_t)gm;
+    c->group_n = (uint16_t)gn;
+    c->xcd_remap = 1;
+    c->alpha = 1.0f;
+    c->bottleneck = p.bottleneck;
+    c->predicted_us = p.total_us;
+}
+
+}  // namespace g355

@@ -1,0 +1,165 @@
+// gemm_run and the split-K workspace: the only entry points that touch the GPU.
+#include <hip/hip_runtime.h>
+
+#include "../../include/gemm.h"
+#include "gemm_kernel.hpp"
+#include "launch.hpp"
+#include "model.hpp"
+
+using namespace g355;
+
+namespace g355 {
+// Sum the split-K slabs in slice order (deterministic), scale, round to bf16.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ ws, __bf16 *__restrict__ C, int M,
+                                                            int N, int ldc, int split_k, float alpha)
+{
+    const size_t quads = (size_t)M * (N / 4);
+    const size_t slab = (size_t)M * N;
+    for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += (size_t)gridDim.x * blockDim.x) {
+        const size_t m = q / (N / 4), n = (q % (N / 4)) * 4;
+        const float *p = ws + m * N + n;
+        f32x4 s = *(const f32x4 *)p;
+        for (int k = 1; k < split_k; ++k) {
+            f32x4 t = *(const f32x4 *)(p + k * slab);
+            s += t;
+        }
+        bf16x4 o;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            o[r] = (__bf16)(s[r] * alpha);
+        *(bf16x4 *)(C + m * ldc + n) = o;
+    }
+}
+
+}  // namespace g355
+
+namespace {
+constexpr int kMaxDevices = 16;
+struct Workspace {
+    void *ptr;
+    size_t bytes;
+};
+Workspace g_ws[kMaxDevices];
+
+LaunchFn launcher_of(int dtype, int id)
+{
+#define G355_COUNT(...) +1
+    constexpr int n_b0 = 0 G355_VARIANTS_BF16_0(G355_COUNT);
+    constexpr int n_b1 = 0 G355_VARIANTS_BF16_1(G355_COUNT);
+    constexpr int n_f0 = 0 G355_VARIANTS_FP8_0(G355_COUNT);
+#undef G355_COUNT
+    if (dtype == GEMM_BF16) {
+        if (id < n_b0)
+            return kLaunchBf16_0(id);
+        if (id < n_b0 + n_b1)
+            return kLaunchBf16_1(id - n_b0);
+        return kLaunchBf16_2(id - n_b0 - n_b1);
+    }
+    if (id < n_f0)
+        return kLaunchFp8_0(id);
+    return kLaunchFp8_1(id - n_f0);
+}
+
+inline int64_t cdiv64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+}  // namespace
+
+extern "C" int gemm_set_workspace(void *dev_ptr, size_t bytes)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return GEMM_ERR_HIP;
+    }
+    if (dev < 0 || dev >= kMaxDevices)
+        return GEMM_ERR_HIP;
+    if (dev_ptr && ((uintptr_t)dev_ptr & 15))
+        return GEMM_ERR_ALIGN;
+    g_ws[dev].ptr = dev_ptr;
+    g_ws[dev].bytes = dev_ptr ? bytes : 0;
+    return GEMM_OK;
+}
+
+extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void *C, void *hip_stream)
+{
+    if (!cfg || !A || !B || !C)
+        return GEMM_ERR_NULL;
+    if (cfg->abi_version != GEMM_ABI_VERSION)
+        return GEMM_ERR_ABI;
+    int rc = check_problem(cfg->M, cfg->N, cfg->K, cfg->dtype);
+    if (rc)
+        return rc;
+    const int dtype = cfg->dtype;
+    const int es = elem_bytes(dtype);
+    if (cfg->kernel_id < 0 || cfg->kernel_id >= variant_count(dtype))
+        return GEMM_ERR_CFG_ILLEGAL;
+    const Variant &v = variant_at(dtype, cfg->kernel_id);
+    const gemm_hw &hw = hw_current();
+    // the descriptive fields must agree with the variant the id names
+    if (cfg->block_m != v.block_m || cfg->block_n != v.block_n || cfg->block_k != v.block_k ||
+        cfg->waves_m != v.waves_m || cfg->waves_n != v.waves_n || cfg->mfma != v.mfma)
+        return GEMM_ERR_CFG_ILLEGAL;
+    if (cfg->split_k < 1 || cfg->group_m < 1 || !variant_legal(hw, v, dtype, cfg->M, cfg->N, cfg->K, cfg->split_k))
+        return GEMM_ERR_CFG_ILLEGAL;
+    if (cfg->lda < cfg->K || cfg->ldb < cfg->N || cfg->ldc < cfg->N)
+        return GEMM_ERR_SHAPE;
+    const int per16 = 16 / es;
+    if (((uintptr_t)A & 15) || ((uintptr_t)B & 15) || ((uintptr_t)C & 15) || cfg->lda % per16 || cfg->ldb % per16 ||
+        cfg->ldc % 8)
+        return GEMM_ERR_ALIGN;
+    const int64_t kps = k_per_split(v, cfg->K, cfg->split_k);
+    const int64_t tiles_m = cdiv64(cfg->M, v.block_m), tiles_n = cdiv64(cfg->N, v.block_n);
+    // the kernel addresses a tile's operands with 32-bit byte offsets below 2 GiB
+    const int64_t lim = (int64_t)1 << 31;
+    if ((int64_t)v.block_m * cfg->lda * es >= lim || (kps + v.block_k) * cfg->ldb * es >= lim ||
+        tiles_m * tiles_n * cfg->split_k >= lim || cfg->M * cfg->N >= ((int64_t)1 << 40))
+        return GEMM_ERR_SHAPE;
+
+    float *ws = nullptr;
+    if (cfg->split_k > 1) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+            (void)hipGetLastError();
+            return GEMM_ERR_HIP;
+        }
+        if (!g_ws[dev].ptr || g_ws[dev].bytes < gemm_workspace_bytes(cfg))
+            return GEMM_ERR_WORKSPACE;
+        ws = (float *)g_ws[dev].ptr;
+    }
+
+    KernelArgs a;
+    a.A = A;
+    a.B = B;
+    a.C = C;
+    a.ws = ws;
+    a.M = (int)cfg->M;
+    a.N = (int)cfg->N;
+    a.K = (int)cfg->K;
+    a.lda = (int)cfg->lda;
+    a.ldb = (int)cfg->ldb;
+    a.ldc = (int)cfg->ldc;
+    a.alpha = cfg->alpha;
+    a.tiles_m = (int)tiles_m;
+    a.tiles_n = (int)tiles_n;
+    a.split_k = cfg->split_k;
+    a.k_per_split = (int)kps;
+    a.group_m = cfg->group_m;
+    a.xcd_remap = cfg->xcd_remap ? 1 : 0;
+    a.n_xcd = hw.n_xcd;
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (launcher_of(dtype, cfg->kernel_id)(a, stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return GEMM_ERR_HIP;
+    }
+    if (cfg->split_k > 1) {
+        const size_t quads = (size_t)cfg->M * (size_t)(cfg->N / 4);
+        size_t blocks = (quads + 255) / 256;
+        if (blocks > 256 * 8)
+            blocks = 256 * 8;
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, ws, (__bf16 *)C, a.M,
+                           a.N, a.ldc, a.split_k, a.alpha);
+        if (hipGetLastError() != hipSuccess)
+            return GEMM_ERR_HIP;
+    }
+    return GEMM_OK;
+}
