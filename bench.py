@@ -1,0 +1,143 @@
+"""Benchmark of the GEMM hot path on one MI355X.
+
+One step = one pass of the whole path over the square bf16 workload: for M=N=K=4096 and
+M=N=K=8192 (N(0,1) inputs from seed 1, fp32 accumulate, bf16 output), gemm_select (the
+analytical model, host) followed by gemm_run (rasterisation, prologue, K loop, epilogue
+on the GPU).  Inputs are resident in HBM before the timed region.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0}   # MI355X dense MFMA, published
+PEAK_HBM_GBPS = 8000.0
+
+
+def read_traffic(name):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary
+    (profiles/<name>: a line `traffic_bytes_per_launch: <number>`), or None."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except (OSError, ValueError):
+        pass
+    return None
+
+
+def cpu_baseline(A, B, rows):
+    """The CPU oracle as it stands, timed on a row sample of the 8192^3 workload."""
+    import numpy as np
+    from oracle import gemm_oracle as oracle
+
+    K, N = B.shape
+    sel = np.linspace(0, A.shape[0] - 1, rows).astype(np.int64)
+    t0 = time.perf_counter()
+    oracle.gemm_rows(A, B, sel, oracle.BF16)
+    dt = time.perf_counter() - t0
+    flops = 2.0 * rows * N * K
+    threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
+    return {"value": flops / dt * 1e-12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": "%d evenly spaced rows of the 8192^3 product (%.1f s)" % (rows, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=1024)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build is single-GPU by design (the paper's method excludes multi-GPU); "
+                 "run with --gpus 1")
+
+    import numpy as np
+    import torch
+
+    from paper_2512_04226_amd import binding as g
+    from paper_2512_04226_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    sizes = (4096, 8192)
+    host = {n: wl.config2(n) for n in sizes}
+    dev = {}
+    for n in sizes:
+        A, B = host[n]
+        dev[n] = (torch.from_numpy(A.view(np.int16)).cuda(), torch.from_numpy(B.view(np.int16)).cuda(),
+                  torch.empty((n, n), dtype=torch.int16, device="cuda"))
+    ws = None
+    for n in sizes:
+        need = g.gemm_workspace_bytes(g.gemm_select(n, n, n, g.GEMM_BF16))
+        if need and (ws is None or ws.numel() * 4 < need):
+            ws = torch.empty(need // 4, dtype=torch.float32, device="cuda")
+            g.gemm_set_workspace(ws)
+
+    def step(events=None):
+        for n in sizes:
+            cfg = g.gemm_select(n, n, n, g.GEMM_BF16)
+            dA, dB, dC = dev[n]
+            if events is not None and n == sizes[-1]:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                g.gemm_run(cfg, dA, dB, dC)
+                e1.record()
+                events.append((e0, e1))
+            else:
+                g.gemm_run(cfg, dA, dB, dC)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    flops_step = sum(2.0 * n ** 3 for n in sizes)
+    value = flops_step * args.steps / dt * 1e-12
+    big = sizes[-1]
+    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))
+    achieved = 2.0 * big ** 3 / (kern_ms * 1e-3) * 1e-12
+    cfg_big = g.gemm_select(big, big, big, g.GEMM_BF16)
+    cfg_small = g.gemm_select(sizes[0], sizes[0], sizes[0], g.GEMM_BF16)
+
+    # selector cost (host only), cf. the paper's Table II
+    t1 = time.perf_counter()
+    for _ in range(200):
+        g.gemm_select(big, big, big, g.GEMM_BF16)
+    select_us = (time.perf_counter() - t1) / 200 * 1e6
+
+    out = {
+        "metric": "GEMM TFLOP/s (bf16 in, fp32 accumulate, bf16 out; analytic kernel selection included)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "square bf16 GEMM M=N=K=4096 then 8192, row-major A and B, N(0,1) seed 1",
+                   "picked_4096": cfg_small.describe(), "picked_8192": cfg_big.describe(),
+                   "select_us": select_us},
+        "frac_of_mfma_peak": value / PEAK_TFLOPS["bf16"],
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_TFLOPS["bf16"], "kernel": "gemm_kernel<%s> on 8192^3" % cfg_big.describe(),
+                     "avg_launch_ms": kern_ms, "traffic": read_traffic("gemm_bf16_8192_counters.txt")},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(host[big][0], host[big][1], args.cpu_rows)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -103,7 +103,8 @@ typedef struct gemm_cfg {
     uint16_t group_m;         /* cache-tile height in tiles (Algorithm 6's f_m); tiles run column-major inside a band of group_m tile rows */
     uint16_t group_n;         /* cache-tile width f_n = CUs per L2 / f_m (informational) */
     uint8_t xcd_remap;        /* 1: workgroup ids are renumbered so that each XCD owns a contiguous id range */
-    uint8_t reserved[3];
+    uint8_t stages;           /* LDS ring depth: K_T slabs resident or in flight per workgroup */
+    uint8_t reserved[2];
     float alpha;              /* default 1; the caller may overwrite it before gemm_run */
     int32_t bottleneck;       /* gemm_bottleneck of the prediction */
     double predicted_us;      /* model's total latency for this cfg */

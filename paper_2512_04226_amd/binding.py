@@ -45,13 +45,14 @@ class gemm_cfg(ctypes.Structure):
                 ("block_n", ctypes.c_uint16), ("block_k", ctypes.c_uint16), ("waves_m", ctypes.c_uint8),
                 ("waves_n", ctypes.c_uint8), ("mfma", ctypes.c_uint8), ("k_unroll", ctypes.c_uint8),
                 ("split_k", ctypes.c_uint16), ("group_m", ctypes.c_uint16), ("group_n", ctypes.c_uint16),
-                ("xcd_remap", ctypes.c_uint8), ("reserved", ctypes.c_uint8 * 3), ("alpha", ctypes.c_float),
+                ("xcd_remap", ctypes.c_uint8), ("stages", ctypes.c_uint8),
+                ("reserved", ctypes.c_uint8 * 2), ("alpha", ctypes.c_float),
                 ("bottleneck", ctypes.c_int32), ("predicted_us", ctypes.c_double)]
 
     def describe(self):
-        return ("%dx%dx%d w%dx%d mfma%d split%d g%d%s" % (self.block_m, self.block_n, self.block_k, self.waves_m,
-                                                          self.waves_n, self.mfma, self.split_k, self.group_m,
-                                                          "" if self.xcd_remap else " noxcd"))
+        return ("%dx%dx%d w%dx%d mfma%d s%d split%d g%d%s" % (
+            self.block_m, self.block_n, self.block_k, self.waves_m, self.waves_n, self.mfma, self.stages,
+            self.split_k, self.group_m, "" if self.xcd_remap else " noxcd"))
 
     def copy(self):
         c = gemm_cfg()

@@ -5,9 +5,10 @@
 //   A  M x K row-major, B  K x N row-major, C  M x N row-major bf16 (or fp32 partial slabs
 //   when the reduction is split across workgroups).
 //
-// Data path per K slab: 128-bit buffer loads (A along K, B along N, out-of-range chunks
-// read as zero) -> registers -> swizzled LDS (two stages) -> MFMA fragments.  A is read
-// from LDS with ds_read_b128 (K-contiguous); B is N-contiguous in LDS and is read with the
+// Data path per K slab: 128-bit buffer loads straight into LDS (A along K, B along N,
+// out-of-range chunks arrive as zero; no register staging) -> swizzled LDS ring of NS
+// stages -> MFMA fragments.  A is read from LDS with ds_read_b128 (K-contiguous); B is
+// N-contiguous in LDS and is read with the
 // gfx950 transpose loads (ds_read_b64_tr_b16 / _tr_b8) so that each lane receives
 // K-contiguous values.  The MFMA's row operand is fed from B and its column operand from
 // A, so that a lane ends up with 4 consecutive n of one output row (8- or 16-byte stores).
@@ -45,9 +46,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define G355_LDS __attribute__((address_space(3)))
 
-template <int ES_, int BM_, int BN_, int BK_, int WM_, int WN_, int MI_>
+template <int ES_, int BM_, int BN_, int BK_, int WM_, int WN_, int MI_, int NS_>
 struct Tile {
-    static constexpr int ES = ES_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MI = MI_;
+    static constexpr int ES = ES_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MI = MI_, NS = NS_;
+    static constexpr int NW = WM * WN;
     static constexpr int NT = WM * WN * 64;
     static constexpr int WTM = BM / WM, WTN = BN / WN;      // wave tile
     static constexpr int TM = WTM / MI, TN = WTN / MI;      // MFMA tiles per wave
@@ -61,22 +63,35 @@ struct Tile {
     static constexpr int STAGE = A_BYTES + B_BYTES;
     static constexpr int ACH = A_BYTES / 16, BCH = B_BYTES / 16;  // 16-byte chunks per slab
     static constexpr int CA = RA / 16, CB = RB / 16;              // chunks per row
-    static constexpr int A_LOADS = (ACH + NT - 1) / NT, B_LOADS = (BCH + NT - 1) / NT;
+    // a direct-to-LDS load instruction of one wave fills one 1 KB unit (64 lanes x 16 bytes)
+    static constexpr int A_UNITS = ACH / 64, B_UNITS = BCH / 64;
+    static constexpr int A_LOADS = (A_UNITS + NW - 1) / NW, B_LOADS = (B_UNITS + NW - 1) / NW;
+    static_assert(ACH % 64 == 0 && BCH % 64 == 0, "slabs must be whole 1 KB units");
+    // does every wave of the workgroup issue load instruction l of a slab request?
+    static constexpr bool every_wave_issues(int l) {
+        return (l < A_LOADS) ? (A_UNITS % NW == 0 || (l * NW + NW - 1) < A_UNITS)
+                             : (B_UNITS % NW == 0 || ((l - A_LOADS) * NW + NW - 1) < B_UNITS);
+    }
+    static constexpr int allowance() {
+        int full = 0;
+        for (int l = 0; l < A_LOADS + B_LOADS; ++l)
+            if (every_wave_issues(l))
+                ++full;
+        return (NS - 2) * full;
+    }
     static constexpr int ACC = (MI == 32) ? 16 : 4;               // fp32 accumulators per MFMA tile
     static_assert(WTM % MI == 0 && WTN % MI == 0, "wave tile must be a multiple of the MFMA tile");
     static_assert(BK % KI == 0, "BLOCK_K must be a multiple of MI_K");
     static_assert(RA % 16 == 0 && RB % 16 == 0, "rows must be whole 16-byte chunks");
-    static_assert(2 * STAGE <= 160 * 1024, "two stages must fit the 160 KB LDS");
+    static_assert(NS >= 2 && NS * STAGE <= 160 * 1024, "the stage ring must fit the 160 KB LDS");
 
     // A rows are K-contiguous; lanes of an MFMA operand read the same chunk column of
     // consecutive rows, so the chunk index is XORed with a row key that makes 8 consecutive
     // rows land on 8 different 16-byte bank groups.
     static constexpr int A_ROWS_PER_128 = (RA >= 128) ? 1 : 128 / RA;
     static constexpr int A_KEY_MASK = ((CA < 8) ? CA : 8) - 1;
-    __device__ static inline int a_off(int row, int chunk) {
-        int key = (row / A_ROWS_PER_128) & A_KEY_MASK;
-        return row * RA + ((chunk ^ key) << 4);
-    }
+    __device__ static inline int a_key(int row) { return (row / A_ROWS_PER_128) & A_KEY_MASK; }
+    __device__ static inline int a_off(int row, int chunk) { return row * RA + ((chunk ^ a_key(row)) << 4); }
     // B rows are N-contiguous; a transpose read touches SEG bytes of each of several
     // consecutive k rows, so the SEG-sized block index inside a row is XORed with a key of k
     // that spreads consecutive rows over 256 bytes of banks.
@@ -85,10 +100,8 @@ struct Tile {
     static constexpr int B_SPREAD = 256 / SEG;
     static constexpr int B_ROW_DIV = (RB >= 256) ? 1 : 256 / RB;
     static constexpr int B_KEY_MASK = (((RB / SEG) < B_SPREAD) ? ((RB / SEG) > 0 ? (RB / SEG) : 1) : B_SPREAD) - 1;
-    __device__ static inline int b_off(int krow, int nbyte) {
-        int key = (krow / B_ROW_DIV) & B_KEY_MASK;
-        return krow * RB + (nbyte ^ (key << SEG_BITS));
-    }
+    __device__ static inline int b_key(int krow) { return (krow / B_ROW_DIV) & B_KEY_MASK; }
+    __device__ static inline int b_off(int krow, int nbyte) { return krow * RB + (nbyte ^ (b_key(krow) << SEG_BITS)); }
 };
 
 // Workgroup id -> (tile_m, tile_n, k_slice).  Hardware deals consecutive workgroup ids
@@ -126,11 +139,23 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned by
 // beyond every window (windows are validated to stay below 2 GiB); small advances keep it there
 constexpr unsigned OOB_OFFSET = 0x80000000u;
 
+// The same descriptor as four dwords, for inline assembly.
+__device__ inline i32x4 make_rsrc_words(const void *base, unsigned bytes)
+{
+    const uint64_t p = (uint64_t)base;
+    i32x4 w;
+    w[0] = (int)(uint32_t)p;
+    w[1] = (int)(uint32_t)((p >> 32) & 0xFFFFu);
+    w[2] = (int)bytes;
+    w[3] = 0x00020000;
+    return w;
+}
+
 template <class T>
 __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
 {
     constexpr int ES = T::ES, BM = T::BM, BN = T::BN, BK = T::BK, MI = T::MI, NT = T::NT;
-    __shared__ __attribute__((aligned(128))) uint8_t smem[2 * T::STAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[T::NS * T::STAGE];
 
     int tm, tn, ks;
     tile_coords(args, blockIdx.x, tm, tn, ks);
@@ -143,17 +168,16 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept scalar
     const int wm = wave / T::WN, wn = wave % T::WN;
 
-    // ---- global load bookkeeping ----
-    // Chunk c (16 bytes) of a slab belongs to thread c % NT; NT is a multiple of the chunks
-    // per row, so a thread keeps one chunk column and steps down the rows.  Rows past the
-    // edge of the matrix (A: m >= M, B: k >= k_len) fall outside the buffer window and read
-    // as zero; chunk columns past the edge (A: k >= k_len, B: n >= N) are sent there by
-    // replacing the offset.
-    static_assert(NT % T::CA == 0 && NT % T::CB == 0, "a thread must keep one chunk column");
-    constexpr int A_RSTEP = NT / T::CA, B_RSTEP = NT / T::CB;
+    // ---- global -> LDS bookkeeping ----
+    // Load instruction i of wave w fills LDS unit u = i*NW + w of the stage: lane l writes the
+    // 16-byte slot c = u*64 + l (row c / chunks-per-row, physical chunk c % chunks-per-row).
+    // The swizzle is applied on the global side: the lane fetches the logical chunk that
+    // belongs in its slot.  Rows past the edge of the matrix (A: m >= M, B: k >= k_len) fall
+    // outside the buffer window and arrive as zero; chunk columns past the edge (A: k >= k_len,
+    // B: n >= N) are sent outside the window by replacing the offset.
     const uint8_t *Abase = (const uint8_t *)args.A + ((size_t)m0 * args.lda + k_begin) * ES;
     const uint8_t *Bbase = (const uint8_t *)args.B + ((size_t)k_begin * args.ldb + n0) * ES;
     const int a_rows_valid = (args.M - m0 < BM) ? (args.M - m0) : BM;
@@ -161,41 +185,44 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         make_rsrc(Abase, (unsigned)((a_rows_valid - 1) * args.lda + k_len) * ES);
     const __amdgpu_buffer_rsrc_t rsB = make_rsrc(Bbase, (unsigned)(k_len * args.ldb) * ES);
 
-    const int a_row0 = tid / T::CA, a_ch = tid % T::CA;
-    const int b_row0 = tid / T::CB, b_ch = tid % T::CB;
-    const int a_kcol = a_ch * (16 / ES);
-    const bool a_active = a_row0 < BM;
-    const bool b_active = (b_row0 < BK) && (n0 + b_ch * (16 / ES) < args.N);
-    const unsigned a_voff0 = a_active ? (unsigned)(a_row0 * args.lda * ES + a_ch * 16) : OOB_OFFSET;
-    const unsigned b_voff0 = b_active ? (unsigned)(b_row0 * args.ldb * ES + b_ch * 16) : OOB_OFFSET;
-    const unsigned a_rstep = (unsigned)(A_RSTEP * args.lda * ES);
-    const unsigned b_rstep = (unsigned)(B_RSTEP * args.ldb * ES);
-
-    i32x4 a_reg[T::A_LOADS], b_reg[T::B_LOADS];
-    auto load_slab = [&](int kt) {
-        const int kk = kt * BK;
-        const unsigned a_base = (a_kcol + kk < k_len) ? a_voff0 + (unsigned)(kk * ES) : OOB_OFFSET;
-        const unsigned b_base = b_voff0 + (unsigned)kk * (unsigned)(args.ldb * ES);
+    unsigned a_voff[T::A_LOADS], b_voff[T::B_LOADS];
+    int a_kcol[T::A_LOADS];
 #pragma unroll
-        for (int i = 0; i < T::A_LOADS; ++i)
-            a_reg[i] = __builtin_bit_cast(
-                i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsA, a_base + i * a_rstep, 0, 0));
+    for (int i = 0; i < T::A_LOADS; ++i) {
+        const int c = (i * T::NW + wave) * 64 + lane;
+        const int row = c / T::CA, lch = (c % T::CA) ^ T::a_key(row);
+        a_kcol[i] = lch * (16 / ES);
+        a_voff[i] = (unsigned)(row * args.lda * ES + lch * 16);
+    }
 #pragma unroll
-        for (int i = 0; i < T::B_LOADS; ++i)
-            b_reg[i] = __builtin_bit_cast(
-                i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsB, b_base + i * b_rstep, 0, 0));
+    for (int i = 0; i < T::B_LOADS; ++i) {
+        const int c = (i * T::NW + wave) * 64 + lane;
+        const int row = c / T::CB;
+        const int lbyte = ((c % T::CB) * 16) ^ (T::b_key(row) << T::SEG_BITS);
+        const bool ok = n0 + lbyte / ES < args.N;
+        b_voff[i] = ok ? (unsigned)(row * args.ldb * ES + lbyte) : OOB_OFFSET;
+    }
+    // Load instruction l of a slab request (A units first, then B units): asynchronous,
+    // completion is counted by vmcnt.
+    auto issue_one = [&](int l, int slab, int stage) {
+        const int kk = slab * BK;
+        G355_LDS uint8_t *sbase = (G355_LDS uint8_t *)smem + stage * T::STAGE;
+        if (l < T::A_LOADS) {
+            const int i = l, u = i * T::NW + wave;
+            if (T::A_UNITS % T::NW == 0 || u < T::A_UNITS) {
+                const unsigned off = (a_kcol[i] + kk < k_len) ? a_voff[i] + (unsigned)(kk * ES) : OOB_OFFSET;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (G355_LDS void *)(sbase + u * 1024), 16, off, 0, 0, 0);
+            }
+        } else {
+            const int i = l - T::A_LOADS, u = i * T::NW + wave;
+            if (T::B_UNITS % T::NW == 0 || u < T::B_UNITS) {
+                const unsigned off = b_voff[i] + (unsigned)kk * (unsigned)(args.ldb * ES);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (G355_LDS void *)(sbase + T::A_BYTES + u * 1024), 16, off,
+                                                         0, 0, 0);
+            }
+        }
     };
-    auto store_slab = [&](int stage) {
-        uint8_t *s = smem + stage * T::STAGE;
-#pragma unroll
-        for (int i = 0; i < T::A_LOADS; ++i)
-            if (T::ACH >= NT || a_row0 < BM)
-                *(i32x4 *)(s + T::a_off(a_row0 + i * A_RSTEP, a_ch)) = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < T::B_LOADS; ++i)
-            if (T::BCH >= NT || b_row0 < BK)
-                *(i32x4 *)(s + T::A_BYTES + T::b_off(b_row0 + i * B_RSTEP, b_ch * 16)) = b_reg[i];
-    };
+    constexpr int NL = T::A_LOADS + T::B_LOADS;   // load instructions per wave and slab
 
     // ---- fragment addressing (per lane, constant over the K loop) ----
     // column operand (from A): lane holds row m = lane % MI, k in [kg*KL, kg*KL + KL)
@@ -221,87 +248,118 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             for (int r = 0; r < T::ACC; ++r)
                 acc[j][i][r] = 0.f;
 
-    auto compute = [&](int stage) {
+    // Fragments of one MFMA k-step, double buffered in registers: while the MFMAs of k-step s
+    // run, the LDS reads of k-step s+1 are in flight.
+    typedef typename std::conditional<ES == 2, bf16x8, i32x8>::type frag_t;
+    frag_t af[2][T::TM], bfr[2][T::TN];
+
+    // Fragment `u` of k-step `kstep` of LDS stage `stage` into register buffer `buf`:
+    // u < TM is the A fragment of MFMA tile row u, otherwise the B fragment of tile column u-TM.
+    auto load_frag = [&](int stage, int kstep, int buf, int u) {
         const uint8_t *sA = smem + stage * T::STAGE;
         const uint8_t *sB = sA + T::A_BYTES;
-#pragma unroll
-        for (int kstep = 0; kstep < T::KSTEPS; ++kstep) {
-            const int k0 = kstep * T::KI;
+        const int k0 = kstep * T::KI;
+        if (u < T::TM) {
+            const int i = u;
             if constexpr (ES == 2) {
-                bf16x8 af[T::TM], bfr[T::TN];
-#pragma unroll
-                for (int i = 0; i < T::TM; ++i) {
-                    const int chunk = (k0 + a_kg * T::KL) / 8;
-                    af[i] = *(const bf16x8 *)(sA + T::a_off(a_row + i * MI, chunk));
-                }
-#pragma unroll
-                for (int j = 0; j < T::TN; ++j) {
-                    short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (G355_LDS short4_t *)(sB + T::b_off(k0 + b_krow_l, (b_ncol + j * MI) * 2)));
-                    short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (G355_LDS short4_t *)(sB + T::b_off(k0 + b_krow_l + TRK, (b_ncol + j * MI) * 2)));
-                    typedef short short8_t __attribute__((ext_vector_type(8)));
-                    short8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    bfr[j] = __builtin_bit_cast(bf16x8, v);
-                }
-#pragma unroll
-                for (int j = 0; j < T::TN; ++j)
-#pragma unroll
-                    for (int i = 0; i < T::TM; ++i) {
-                        if constexpr (MI == 32)
-                            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[j][i], 0, 0, 0);
-                        else
-                            acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[j], af[i], acc[j][i], 0, 0, 0);
-                    }
+                const int chunk = (k0 + a_kg * T::KL) / 8;
+                af[buf][i] = *(const bf16x8 *)(sA + T::a_off(a_row + i * MI, chunk));
             } else {
-                i32x8 af[T::TM], bfr[T::TN];
+                const int chunk = (k0 + a_kg * T::KL) / 16;
+                i32x4 lo = *(const i32x4 *)(sA + T::a_off(a_row + i * MI, chunk));
+                i32x4 hi = *(const i32x4 *)(sA + T::a_off(a_row + i * MI, chunk + 1));
+                af[buf][i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+        } else {
+            const int j = u - T::TM;
+            if constexpr (ES == 2) {
+                short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (G355_LDS short4_t *)(sB + T::b_off(k0 + b_krow_l, (b_ncol + j * MI) * 2)));
+                short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (G355_LDS short4_t *)(sB + T::b_off(k0 + b_krow_l + TRK, (b_ncol + j * MI) * 2)));
+                typedef short short8_t __attribute__((ext_vector_type(8)));
+                short8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                bfr[buf][j] = __builtin_bit_cast(bf16x8, v);
+            } else {
+                int2_t q[4];
 #pragma unroll
-                for (int i = 0; i < T::TM; ++i) {
-                    const int chunk = (k0 + a_kg * T::KL) / 16;
-                    i32x4 lo = *(const i32x4 *)(sA + T::a_off(a_row + i * MI, chunk));
-                    i32x4 hi = *(const i32x4 *)(sA + T::a_off(a_row + i * MI, chunk + 1));
-                    af[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
-#pragma unroll
-                for (int j = 0; j < T::TN; ++j) {
-                    int2_t q[4];
-#pragma unroll
-                    for (int h = 0; h < 4; ++h)
-                        q[h] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
-                            (G355_LDS int2_t *)(sB + T::b_off(k0 + b_krow_l + h * TRK, b_ncol + j * MI)));
-                    i32x4 lo = __builtin_shufflevector(q[0], q[1], 0, 1, 2, 3);
-                    i32x4 hi = __builtin_shufflevector(q[2], q[3], 0, 1, 2, 3);
-                    bfr[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
-#pragma unroll
-                for (int j = 0; j < T::TN; ++j)
-#pragma unroll
-                    for (int i = 0; i < T::TM; ++i) {
-                        if constexpr (MI == 32)
-                            acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bfr[j], af[i], acc[j][i], 0, 0, 0, 0, 0, 0);
-                        else
-                            acc[j][i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[j], af[i], acc[j][i], 0, 0, 0, 0, 0, 0);
-                    }
+                for (int h = 0; h < 4; ++h)
+                    q[h] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+                        (G355_LDS int2_t *)(sB + T::b_off(k0 + b_krow_l + h * TRK, b_ncol + j * MI)));
+                i32x4 lo = __builtin_shufflevector(q[0], q[1], 0, 1, 2, 3);
+                i32x4 hi = __builtin_shufflevector(q[2], q[3], 0, 1, 2, 3);
+                bfr[buf][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
         }
     };
+    constexpr int NF = T::TM + T::TN;     // fragments per k-step
+    auto mma_one = [&](int buf, int j, int i) {
+        if constexpr (ES == 2 && MI == 32)
+            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[buf][j], af[buf][i], acc[j][i], 0, 0, 0);
+        else if constexpr (ES == 2)
+            acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[buf][j], af[buf][i], acc[j][i], 0, 0, 0);
+        else if constexpr (MI == 32)
+            acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bfr[buf][j], af[buf][i], acc[j][i], 0, 0, 0, 0, 0, 0);
+        else
+            acc[j][i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[buf][j], af[buf][i], acc[j][i], 0, 0, 0, 0, 0, 0);
+    };
 
     // ---- pipeline: prologue, main K loop, epilogue (Algorithm 8's three phases) ----
+    // Ring of NS LDS stages: while slab kt is consumed, slabs kt+1 .. kt+NS-2 are landed or in
+    // flight and the request for slab kt+NS-1 goes into the stage that iteration kt-1 read.
+    // Before the barrier a wave waits until its own loads of slab kt+1 have landed (all but
+    // the newest NS-2 slabs' worth) and its LDS reads are done; the barrier sits before the
+    // last k-step's MFMAs, whose fragments are already in registers, so the first fragments of
+    // the next stage are fetched under those MFMAs.  Requests past the last slab are
+    // out-of-window loads: they move no data and keep the loop body branch-free.
+    //
+    static_assert(T::KSTEPS % 2 == 0, "fragment double buffering needs an even number of k-steps");
+    // vmcnt allowance at the barrier of iteration kt: everything requested after slab kt+1 may
+    // still be in flight, i.e. slabs kt+2 .. kt+NS-1.  Only instructions that every wave issues
+    // are counted (ragged unit counts), so a wave never waits for less than it must.
+    constexpr int ALLOW = T::allowance();
+    static_assert(ALLOW <= 63, "vmcnt is a 6-bit counter");
+    auto publish = [&]() { asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(ALLOW) : "memory"); };
+
     if (kt_count > 0) {
-        load_slab(0);
-        store_slab(0);
+#pragma unroll
+        for (int s = 0; s < T::NS - 1; ++s)
+#pragma unroll
+            for (int l = 0; l < NL; ++l)
+                issue_one(l, s, s);
+        publish();
+#pragma unroll
+        for (int u = 0; u < NF; ++u)
+            load_frag(0, 0, 0, u);
     }
-    __syncthreads();
+    int stage = 0;                         // stage of slab kt
+    int fill = T::NS - 1;                  // stage that receives slab kt+NS-1
     for (int kt = 0; kt < kt_count; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < kt_count;
-        if (more)
-            load_slab(kt + 1);
-        compute(cur);
-        if (more)
-            store_slab(cur ^ 1);
-        __syncthreads();
+        const int next = (stage + 1 == T::NS) ? 0 : stage + 1;
+#pragma unroll
+        for (int l = 0; l < NL; ++l)
+            issue_one(l, kt + T::NS - 1, fill);
+#pragma unroll
+        for (int kstep = 0; kstep < T::KSTEPS - 1; ++kstep) {
+#pragma unroll
+            for (int u = 0; u < NF; ++u)
+                load_frag(stage, kstep + 1, (kstep + 1) & 1, u);
+#pragma unroll
+            for (int m = 0; m < T::TM * T::TN; ++m)
+                mma_one(kstep & 1, m / T::TM, m % T::TM);
+        }
+        publish();
+#pragma unroll
+        for (int u = 0; u < NF; ++u)
+            load_frag(next, 0, 0, u);
+#pragma unroll
+        for (int m = 0; m < T::TM * T::TN; ++m)
+            mma_one((T::KSTEPS - 1) & 1, m / T::TM, m % T::TM);
+        fill = stage;
+        stage = next;
     }
+    // nothing may still be in flight towards LDS when the workgroup ends
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- epilogue: lane holds, per MFMA tile, output row m = lane % MI and
     //      n = 8*(r/4) + 4*(lane/32) + r%4 (32x32) or n = 4*(lane/16) + r (16x16) ----

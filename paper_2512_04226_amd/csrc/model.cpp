@@ -16,7 +16,7 @@
 
 namespace g355 {
 
-#define G355_X(bm, bn, bk, wm, wn, mi) {bm, bn, bk, wm, wn, mi},
+#define G355_X(bm, bn, bk, wm, wn, mi, ns) {bm, bn, bk, wm, wn, mi, ns},
 static const Variant kVariantsBf16[] = {G355_VARIANTS_BF16(G355_X)};
 static const Variant kVariantsFp8[] = {G355_VARIANTS_FP8(G355_X)};
 #undef G355_X
@@ -88,7 +88,7 @@ bool variant_legal(const gemm_hw &hw, const Variant &v, int dtype, int64_t M, in
     (void)M;
     (void)N;
     const int es = elem_bytes(dtype);
-    const double lds = 2.0 * (v.block_m + v.block_n) * v.block_k * es;
+    const double lds = (double)v.stages * (v.block_m + v.block_n) * v.block_k * es;
     if (lds > hw.lds_bytes)
         return false;
     if (split_k < 1)
@@ -106,13 +106,12 @@ bool variant_legal(const gemm_hw &hw, const Variant &v, int dtype, int64_t M, in
 static int occupancy(const gemm_hw &hw, const Variant &v, int dtype)
 {
     const int es = elem_bytes(dtype);
-    const double lds = 2.0 * (v.block_m + v.block_n) * v.block_k * es;
+    const double lds = (double)v.stages * (v.block_m + v.block_n) * v.block_k * es;
     const int waves = v.waves_m * v.waves_n;
     const int nt = waves * 64;
     // registers per lane: fp32 accumulators + staged slab + fragments and addresses
     const double acc = (double)v.block_m * v.block_n / nt;
-    const double stage = (double)(v.block_m + v.block_n) * v.block_k * es / 4.0 / nt;
-    const double vgpr = acc + stage + 48.0;
+    const double vgpr = acc + 64.0;
     int waves_per_simd = (int)std::floor(512.0 / vgpr);
     waves_per_simd = std::max(1, std::min(8, waves_per_simd));
     const int by_regs = std::max(1, waves_per_simd * hw.simd_per_cu / waves);
@@ -349,6 +348,7 @@ void fill_cfg(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, int
     c->group_m = (uint16_t)gm;
     c->group_n = (uint16_t)gn;
     c->xcd_remap = 1;
+    c->stages = (uint8_t)v.stages;
     c->alpha = 1.0f;
     c->bottleneck = p.bottleneck;
     c->predicted_us = p.total_us;

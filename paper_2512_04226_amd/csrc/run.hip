@@ -46,6 +46,7 @@ LaunchFn launcher_of(int dtype, int id)
 #define G355_COUNT(...) +1
     constexpr int n_b0 = 0 G355_VARIANTS_BF16_0(G355_COUNT);
     constexpr int n_b1 = 0 G355_VARIANTS_BF16_1(G355_COUNT);
+    constexpr int n_b2 = 0 G355_VARIANTS_BF16_2(G355_COUNT);
     constexpr int n_f0 = 0 G355_VARIANTS_FP8_0(G355_COUNT);
 #undef G355_COUNT
     if (dtype == GEMM_BF16) {
@@ -53,7 +54,9 @@ LaunchFn launcher_of(int dtype, int id)
             return kLaunchBf16_0(id);
         if (id < n_b0 + n_b1)
             return kLaunchBf16_1(id - n_b0);
-        return kLaunchBf16_2(id - n_b0 - n_b1);
+        if (id < n_b0 + n_b1 + n_b2)
+            return kLaunchBf16_2(id - n_b0 - n_b1);
+        return kLaunchBf16_3(id - n_b0 - n_b1 - n_b2);
     }
     if (id < n_f0)
         return kLaunchFp8_0(id);
@@ -96,7 +99,7 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
     const gemm_hw &hw = hw_current();
     // the descriptive fields must agree with the variant the id names
     if (cfg->block_m != v.block_m || cfg->block_n != v.block_n || cfg->block_k != v.block_k ||
-        cfg->waves_m != v.waves_m || cfg->waves_n != v.waves_n || cfg->mfma != v.mfma)
+        cfg->waves_m != v.waves_m || cfg->waves_n != v.waves_n || cfg->mfma != v.mfma || cfg->stages != v.stages)
         return GEMM_ERR_CFG_ILLEGAL;
     if (cfg->split_k < 1 || cfg->group_m < 1 || !variant_legal(hw, v, dtype, cfg->M, cfg->N, cfg->K, cfg->split_k))
         return GEMM_ERR_CFG_ILLEGAL;
@@ -110,7 +113,7 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
     const int64_t tiles_m = cdiv64(cfg->M, v.block_m), tiles_n = cdiv64(cfg->N, v.block_n);
     // the kernel addresses a tile's operands with 32-bit byte offsets below 2 GiB
     const int64_t lim = (int64_t)1 << 31;
-    if ((int64_t)v.block_m * cfg->lda * es >= lim || (kps + v.block_k) * cfg->ldb * es >= lim ||
+    if ((int64_t)v.block_m * cfg->lda * es >= lim || (kps + (int64_t)v.stages * v.block_k) * cfg->ldb * es >= lim ||
         tiles_m * tiles_n * cfg->split_k >= lim || cfg->M * cfg->N >= ((int64_t)1 << 40))
         return GEMM_ERR_SHAPE;
 

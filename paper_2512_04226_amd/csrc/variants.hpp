@@ -1,71 +1,80 @@
 // The compiled kernel variants: the candidate tile list the selector ranks (Section V-B of
 // the paper speaks of 75 searched configurations; Section V-E of 50-150 valid tiles per
 // datatype).  One line per instantiation of gemm_kernel<>:
-//   X(BLOCK_M, BLOCK_N, BLOCK_K, WAVES_M, WAVES_N, MFMA)
+//   X(BLOCK_M, BLOCK_N, BLOCK_K, WAVES_M, WAVES_N, MFMA, LDS_STAGES)
 // The order is part of the ABI of kernel_id and of the selector's tie-break (earlier wins).
 #pragma once
 
 // bf16: BLOCK_K in elements; MFMA 32 -> v_mfma_f32_32x32x16_bf16, 16 -> v_mfma_f32_16x16x32_bf16
-#define G355_VARIANTS_BF16_0(X) \
-    X(256, 256, 64, 2, 2, 32)   \
-    X(256, 256, 32, 2, 2, 32)   \
-    X(256, 128, 64, 2, 2, 32)   \
-    X(128, 256, 64, 2, 2, 32)   \
-    X(128, 128, 64, 2, 2, 32)   \
-    X(128, 128, 128, 2, 2, 32)  \
-    X(128, 128, 32, 2, 2, 32)   \
-    X(256, 64, 64, 4, 1, 32)
-#define G355_VARIANTS_BF16_1(X) \
-    X(64, 256, 64, 1, 4, 32)    \
-    X(128, 64, 64, 2, 2, 32)    \
-    X(64, 128, 64, 2, 2, 32)    \
-    X(64, 64, 64, 2, 2, 32)     \
-    X(64, 64, 128, 2, 2, 32)    \
-    X(128, 32, 64, 4, 1, 32)    \
-    X(32, 256, 64, 1, 4, 32)    \
-    X(32, 128, 64, 1, 4, 32)    \
-    X(32, 128, 128, 1, 4, 32)   \
-    X(32, 64, 128, 1, 2, 32)    \
-    X(64, 32, 128, 2, 1, 32)    \
-    X(32, 32, 128, 1, 1, 32)
-#define G355_VARIANTS_BF16_2(X) \
-    X(16, 256, 64, 1, 4, 16)    \
-    X(16, 256, 128, 1, 4, 16)   \
-    X(16, 128, 128, 1, 4, 16)   \
-    X(16, 128, 256, 1, 4, 16)   \
-    X(16, 64, 128, 1, 4, 16)    \
-    X(16, 64, 256, 1, 4, 16)    \
-    X(16, 32, 256, 1, 2, 16)    \
-    X(16, 16, 256, 1, 1, 16)
+#define G355_VARIANTS_BF16_0(X)    \
+    X(256, 256, 64, 2, 4, 32, 2)   \
+    X(256, 256, 64, 2, 2, 32, 2)   \
+    X(256, 256, 32, 2, 4, 32, 4)   \
+    X(256, 256, 32, 2, 2, 32, 4)   \
+    X(256, 256, 32, 2, 4, 32, 5)   \
+    X(256, 128, 64, 2, 4, 32, 3)   \
+    X(256, 128, 64, 2, 2, 32, 3)   \
+    X(128, 256, 64, 2, 4, 32, 3)
+#define G355_VARIANTS_BF16_1(X)    \
+    X(128, 256, 64, 2, 2, 32, 3)   \
+    X(128, 128, 64, 2, 2, 32, 2)   \
+    X(128, 128, 64, 2, 2, 32, 3)   \
+    X(128, 128, 128, 2, 2, 32, 2)  \
+    X(128, 128, 32, 2, 2, 32, 4)   \
+    X(256, 64, 64, 4, 1, 32, 2)    \
+    X(64, 256, 64, 1, 4, 32, 2)    \
+    X(128, 64, 64, 2, 2, 32, 3)    \
+    X(64, 128, 64, 2, 2, 32, 3)
+#define G355_VARIANTS_BF16_2(X)    \
+    X(64, 64, 64, 2, 2, 32, 3)     \
+    X(64, 64, 128, 2, 2, 32, 2)    \
+    X(128, 32, 64, 4, 1, 32, 3)    \
+    X(32, 256, 64, 1, 4, 32, 2)    \
+    X(32, 128, 64, 1, 4, 32, 3)    \
+    X(32, 128, 128, 1, 4, 32, 2)   \
+    X(32, 64, 128, 1, 2, 32, 3)    \
+    X(64, 32, 128, 2, 1, 32, 3)    \
+    X(32, 32, 128, 1, 1, 32, 3)
+#define G355_VARIANTS_BF16_3(X)    \
+    X(16, 256, 64, 1, 4, 16, 4)    \
+    X(16, 256, 128, 1, 4, 16, 2)   \
+    X(16, 128, 128, 1, 4, 16, 4)   \
+    X(16, 128, 256, 1, 4, 16, 2)   \
+    X(16, 64, 128, 1, 4, 16, 4)    \
+    X(16, 64, 256, 1, 4, 16, 3)    \
+    X(16, 32, 256, 1, 2, 16, 3)    \
+    X(16, 16, 256, 1, 1, 16, 3)
 
 // fp8 e4m3: MFMA 32 -> v_mfma_f32_32x32x64_f8f6f4, 16 -> v_mfma_f32_16x16x128_f8f6f4
-#define G355_VARIANTS_FP8_0(X)  \
-    X(256, 256, 128, 2, 2, 32)  \
-    X(256, 256, 64, 2, 2, 32)   \
-    X(256, 128, 128, 2, 2, 32)  \
-    X(128, 256, 128, 2, 2, 32)  \
-    X(128, 128, 128, 2, 2, 32)  \
-    X(128, 128, 256, 2, 2, 32)  \
-    X(128, 64, 128, 2, 2, 32)   \
-    X(64, 128, 128, 2, 2, 32)
-#define G355_VARIANTS_FP8_1(X)  \
-    X(64, 64, 128, 2, 2, 32)    \
-    X(64, 64, 256, 2, 2, 32)    \
-    X(64, 256, 128, 1, 4, 32)   \
-    X(32, 256, 128, 1, 4, 32)   \
-    X(32, 128, 256, 1, 4, 32)   \
-    X(32, 32, 256, 1, 1, 32)    \
-    X(16, 256, 256, 1, 4, 16)   \
-    X(16, 128, 256, 1, 4, 16)   \
-    X(16, 64, 256, 1, 4, 16)    \
-    X(16, 16, 256, 1, 1, 16)
+#define G355_VARIANTS_FP8_0(X)     \
+    X(256, 256, 128, 2, 4, 32, 2)  \
+    X(256, 256, 128, 2, 2, 32, 2)  \
+    X(256, 128, 128, 2, 4, 32, 3)  \
+    X(128, 256, 128, 2, 4, 32, 3)  \
+    X(128, 128, 128, 2, 2, 32, 2)  \
+    X(128, 128, 128, 2, 2, 32, 3)  \
+    X(128, 128, 256, 2, 2, 32, 2)  \
+    X(128, 64, 128, 2, 2, 32, 3)   \
+    X(64, 128, 128, 2, 2, 32, 3)
+#define G355_VARIANTS_FP8_1(X)     \
+    X(64, 128, 256, 2, 2, 32, 3)   \
+    X(64, 64, 128, 2, 2, 32, 3)    \
+    X(64, 64, 256, 2, 2, 32, 2)    \
+    X(64, 256, 128, 1, 4, 32, 2)   \
+    X(32, 256, 128, 1, 4, 32, 2)   \
+    X(32, 128, 256, 1, 4, 32, 2)   \
+    X(32, 32, 256, 1, 1, 32, 3)    \
+    X(16, 256, 256, 1, 4, 16, 2)   \
+    X(16, 128, 256, 1, 4, 16, 4)   \
+    X(16, 64, 256, 1, 4, 16, 4)    \
+    X(16, 16, 256, 1, 1, 16, 4)
 
-#define G355_VARIANTS_BF16(X) G355_VARIANTS_BF16_0(X) G355_VARIANTS_BF16_1(X) G355_VARIANTS_BF16_2(X)
+#define G355_VARIANTS_BF16(X) G355_VARIANTS_BF16_0(X) G355_VARIANTS_BF16_1(X) G355_VARIANTS_BF16_2(X) G355_VARIANTS_BF16_3(X)
 #define G355_VARIANTS_FP8(X) G355_VARIANTS_FP8_0(X) G355_VARIANTS_FP8_1(X)
 
 namespace g355 {
 struct Variant {
-    int block_m, block_n, block_k, waves_m, waves_n, mfma;
+    int block_m, block_n, block_k, waves_m, waves_n, mfma, stages;
 };
 // Spatial K-unroll factors offered with every variant.
 constexpr int kSplitKs[] = {1, 2, 4, 8, 16, 32};

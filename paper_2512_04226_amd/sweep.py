@@ -1,0 +1,149 @@
+"""Offline exhaustive sweep of the compiled configuration space (evaluation tool only).
+
+For each problem shape, times every legal (variant, split_k) configuration returned by
+gemm_cfg_at plus the analytical pick of gemm_select, and records the paper's selection
+efficiency (Section V-A): throughput of the pick divided by the best throughput found.
+Nothing here is used by gemm_select or gemm_run.
+
+    python -m paper_2512_04226_amd.sweep --set config5 --out gpurun_out/sweep_config5.jsonl
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+from . import binding as g
+from . import workloads as wl
+
+
+def make_operands(M, N, K, dtype, seed=0):
+    """Random device operands of the right type (values do not affect timing)."""
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    if dtype == g.GEMM_BF16:
+        A = (torch.rand((M, K), device="cuda", generator=gen) * 2 - 1).to(torch.bfloat16)
+        B = (torch.rand((K, N), device="cuda", generator=gen) * 2 - 1).to(torch.bfloat16)
+    else:
+        A = torch.randint(0, 0x78, (M, K), device="cuda", generator=gen, dtype=torch.uint8)
+        B = torch.randint(0, 0x78, (K, N), device="cuda", generator=gen, dtype=torch.uint8)
+    C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+    return A, B, C
+
+
+class Workspace:
+    def __init__(self):
+        self.t = None
+
+    def ensure(self, cfg):
+        need = g.gemm_workspace_bytes(cfg)
+        if need and (self.t is None or self.t.numel() * 4 < need):
+            self.t = torch.empty((need + 3) // 4, dtype=torch.float32, device="cuda")
+            g.gemm_set_workspace(self.t)
+
+
+def time_cfg(cfg, A, B, C, ws, min_ms=1.0, max_iters=200, repeats=3):
+    """Median-of-repeats microseconds per launch (events on torch's current stream)."""
+    ws.ensure(cfg)
+    g.gemm_run(cfg, A, B, C)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    g.gemm_run(cfg, A, B, C)
+    e1.record()
+    e1.synchronize()
+    one = max(e0.elapsed_time(e1), 1e-3)
+    iters = int(min(max_iters, max(3, min_ms / one)))
+    times = []
+    for _ in range(repeats):
+        e0.record()
+        for _ in range(iters):
+            g.gemm_run(cfg, A, B, C)
+        e1.record()
+        e1.synchronize()
+        times.append(e0.elapsed_time(e1) * 1e3 / iters)
+    return float(np.median(times))
+
+
+def sweep_shape(M, N, K, dtype, ws, quick=False):
+    A, B, C = make_operands(M, N, K, dtype)
+    flops = 2.0 * M * N * K
+    rows = []
+    for idx in range(g.gemm_cfg_count(dtype)):
+        cfg = g.gemm_cfg_at(idx, M, N, K, dtype)
+        if cfg is None:
+            continue
+        us = time_cfg(cfg, A, B, C, ws, min_ms=0.5 if quick else 1.0)
+        rows.append({"idx": idx, "cfg": cfg.describe(), "us": us, "pred_us": cfg.predicted_us})
+    pick = g.gemm_select(M, N, K, dtype)
+    pick_us = time_cfg(pick, A, B, C, ws)
+    best = min(rows, key=lambda r: r["us"])
+    # the pick is one of the swept configs; use the better of its two timings against noise
+    same = [r for r in rows if r["cfg"] == pick.describe()]
+    if same:
+        pick_us = min(pick_us, same[0]["us"])
+    rec = {"M": M, "N": N, "K": K, "dtype": dtype, "n_cfgs": len(rows), "best": best, "pick": pick.describe(),
+           "pick_us": pick_us, "pick_pred_us": pick.predicted_us, "efficiency": best["us"] / pick_us,
+           "best_tflops": flops / best["us"] * 1e-6, "pick_tflops": flops / pick_us * 1e-6,
+           "bottleneck": g.BOTTLENECKS[pick.bottleneck],
+           "top5": sorted(rows, key=lambda r: r["us"])[:5]}
+    return rec, rows
+
+
+def shape_set(name):
+    if name == "config5":
+        return [(m, n, k, g.GEMM_BF16) for (m, n, k) in wl.config5_shapes()]
+    if name == "square":
+        return [(n, n, n, g.GEMM_BF16) for n in (512, 1024, 2048, 4096, 8192)]
+    if name == "skinny":
+        return [(m, n, k, g.GEMM_BF16) for (n, k) in wl.SKINNY_NK for m in wl.SKINNY_M]
+    if name == "fp8":
+        return [(n, n, n, g.GEMM_FP8_E4M3) for n in (1024, 4096, 8192)]
+    raise SystemExit("unknown shape set " + name)
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--set", default="config5")
+    ap.add_argument("--out", default="gpurun_out/sweep.jsonl")
+    ap.add_argument("--limit", type=int, default=0)
+    ap.add_argument("--quick", action="store_true")
+    ap.add_argument("--all-rows", action="store_true", help="also write every config's timing")
+    args = ap.parse_args(argv)
+    shapes = shape_set(args.set)
+    if args.limit:
+        shapes = shapes[:args.limit]
+    done = set()
+    if os.path.exists(args.out):       # resume: skip shapes already recorded
+        for line in open(args.out):
+            try:
+                r = json.loads(line)
+                done.add((r["M"], r["N"], r["K"], r["dtype"]))
+            except ValueError:
+                pass
+    os.makedirs(os.path.dirname(args.out) or ".", exist_ok=True)
+    ws = Workspace()
+    effs = []
+    with open(args.out, "a") as f:
+        for i, (M, N, K, dt) in enumerate(shapes):
+            if (M, N, K, dt) in done:
+                continue
+            t0 = time.time()
+            rec, rows = sweep_shape(M, N, K, dt, ws, quick=args.quick)
+            if args.all_rows:
+                rec["rows"] = rows
+            f.write(json.dumps(rec) + "\n")
+            f.flush()
+            effs.append(rec["efficiency"])
+            print("[%d/%d] %dx%dx%d best %s %.1f us (%.0f TF) pick %s %.1f us eff %.3f  (%.1fs)" % (
+                i + 1, len(shapes), M, N, K, rec["best"]["cfg"], rec["best"]["us"], rec["best_tflops"], rec["pick"],
+                rec["pick_us"], rec["efficiency"], time.time() - t0), flush=True)
+    if effs:
+        print("selection efficiency: median %.3f mean %.3f min %.3f over %d shapes" % (
+            float(np.median(effs)), float(np.mean(effs)), float(np.min(effs)), len(effs)), flush=True)
+
+
+if __name__ == "__main__":
+    main()
