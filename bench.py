@@ -56,7 +56,10 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=1024)
+    ap.add_argument("--cpu-rows", type=int, default=4096)
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy, so that HBM byte counters "
+                         "collected around this command can be scaled against a transfer of known size")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build is single-GPU by design (the paper's method excludes multi-GPU); "
@@ -97,6 +100,12 @@ def main():
             else:
                 g.gemm_run(cfg, dA, dB, dC)
 
+    if args.traffic_probe:
+        src = torch.empty(1 << 28, dtype=torch.int32, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                 # 1 GiB read + 1 GiB written by one elementwise copy kernel
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -138,9 +138,21 @@ static void best_factor_pair(int scope, const Variant &v, int64_t tiles_m, int64
 {
     double best_h = -1.0, best_fm = 1, best_fn = 1, best_skew = 0;
     int best_raw = 1;
-    for (int i = 1; i <= scope; ++i) {
+    // all divisors i of scope in ascending order (trial division up to sqrt, both cofactors kept)
+    int divs[128];
+    int nd = 0, nhi = 0;
+    int hi[64];
+    for (int i = 1; (int64_t)i * i <= scope; ++i) {
         if (scope % i)
             continue;
+        divs[nd++] = i;
+        if (i != scope / i)
+            hi[nhi++] = scope / i;
+    }
+    while (nhi > 0)
+        divs[nd++] = hi[--nhi];
+    for (int d = 0; d < nd; ++d) {
+        const int i = divs[d];
         const int j = scope / i;
         const double fm = (double)std::min<int64_t>(i, tiles_m);
         const double fn = (double)std::min<int64_t>(j, tiles_n);

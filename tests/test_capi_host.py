@@ -1,0 +1,145 @@
+"""Host-side checks of the C ABI: every declared symbol is exported, argument validation
+returns the documented codes, the selector is deterministic and needs no GPU."""
+import ctypes
+import os
+import re
+import threading
+
+import pytest
+
+from paper_2512_04226_amd import binding as g
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "gemm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gemm_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_functions()
+    assert {"gemm_select", "gemm_run", "gemm_workspace_bytes", "gemm_set_workspace", "gemm_cfg_count",
+            "gemm_cfg_at", "gemm_predict", "gemm_hw_get", "gemm_hw_set", "gemm_hw_reset", "gemm_strerror",
+            "gemm_abi_version"} <= set(names)
+    lib = ctypes.CDLL(g.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert g.gemm_abi_version() == g.GEMM_ABI_VERSION
+
+
+def test_struct_sizes_match_header_layout():
+    # gemm_cfg: 4+4 + 6*8 + 4 + 3*2 + 4*1 + 3*2 + 1+1+2 + 4 + 4 (+pad) + 8
+    assert ctypes.sizeof(g.gemm_cfg) == 96
+    assert ctypes.sizeof(g.gemm_prediction) == 25 * 8 + 8
+    assert ctypes.sizeof(g.gemm_hw) == 16 + 13 * 8 + 4 * 8
+
+
+def test_select_argument_errors():
+    cfg = g.gemm_cfg()
+    f = g._lib.gemm_select
+    assert f(512, 512, 512, 0, None) == -1                     # NULL out
+    assert f(0, 512, 512, 0, ctypes.byref(cfg)) == -2          # shape
+    assert f(512, -1, 512, 0, ctypes.byref(cfg)) == -2
+    assert f(512, 512, 512, 7, ctypes.byref(cfg)) == -3        # dtype
+    assert f(512, 516, 512, 0, ctypes.byref(cfg)) == -5        # N not a multiple of 8 (bf16)
+    assert f(512, 512, 520, 1, ctypes.byref(cfg)) == -5        # K not a multiple of 16 (fp8)
+    assert f(1, 8, 8, 0, ctypes.byref(cfg)) == 0               # smallest legal problem
+    assert f(1 << 31, 512, 512, 0, ctypes.byref(cfg)) == -2
+    for code in range(0, -10, -1):
+        assert g.gemm_strerror(code) != "unknown status"
+    assert g.gemm_strerror(-99) == "unknown status"
+
+
+def test_cfg_at_enumeration_and_legality():
+    n = g.gemm_cfg_count(g.GEMM_BF16)
+    assert 75 <= n <= 400 and g.gemm_cfg_count(g.GEMM_FP8_E4M3) >= 50
+    assert g._lib.gemm_cfg_count(5) == -3
+    cfg = g.gemm_cfg()
+    assert g._lib.gemm_cfg_at(-1, 512, 512, 512, 0, ctypes.byref(cfg)) == -9
+    assert g._lib.gemm_cfg_at(n, 512, 512, 512, 0, ctypes.byref(cfg)) == -9
+    legal = [g.gemm_cfg_at(i, 512, 512, 64, 0) for i in range(n)]
+    # K = 64 has one or two slabs: no variant may split it 32 ways
+    assert all(c is None or c.split_k <= 2 for c in legal) and any(c is not None for c in legal)
+    seen = set()
+    for i in range(n):
+        c = g.gemm_cfg_at(i, 4096, 4096, 8192, 0)
+        assert c is not None and c.abi_version == 1 and c.M == 4096 and c.lda == 8192 and c.ldb == 4096
+        assert c.block_k % (16 if c.mfma == 32 else 32) == 0 and c.k_unroll == c.block_k // (16 if c.mfma == 32 else 32)
+        assert c.stages * (c.block_m + c.block_n) * c.block_k * 2 <= 160 * 1024
+        seen.add((c.kernel_id, c.split_k))
+    assert len(seen) == n
+
+
+def test_run_rejects_bad_arguments_without_launching():
+    cfg = g.gemm_select(512, 512, 512, g.GEMM_BF16)
+    run = g._lib.gemm_run
+    p = ctypes.c_void_p(0x1000)     # never dereferenced: every case fails validation first
+    assert run(None, p, p, p, None) == -1
+    assert run(ctypes.byref(cfg), None, p, p, None) == -1
+    bad = cfg.copy(); bad.abi_version = 2
+    assert run(ctypes.byref(bad), p, p, p, None) == -7
+    bad = cfg.copy(); bad.kernel_id = 10_000
+    assert run(ctypes.byref(bad), p, p, p, None) == -4
+    bad = cfg.copy(); bad.block_m = bad.block_m + 16
+    assert run(ctypes.byref(bad), p, p, p, None) == -4
+    bad = cfg.copy(); bad.split_k = 4096
+    assert run(ctypes.byref(bad), p, p, p, None) == -4
+    bad = cfg.copy(); bad.group_m = 0
+    assert run(ctypes.byref(bad), p, p, p, None) == -4
+    bad = cfg.copy(); bad.lda = 256
+    assert run(ctypes.byref(bad), p, p, p, None) == -2
+    bad = cfg.copy(); bad.ldb = 516
+    assert run(ctypes.byref(bad), p, p, p, None) == -5
+    assert run(ctypes.byref(cfg), ctypes.c_void_p(0x1008), p, p, None) == -5
+    bad = cfg.copy(); bad.dtype = 9
+    assert run(ctypes.byref(bad), p, p, p, None) == -3
+    assert g.gemm_workspace_bytes(cfg) == (0 if cfg.split_k == 1 else cfg.split_k * 512 * 512 * 4)
+
+
+def test_select_is_deterministic_and_thread_safe():
+    shapes = [(512, 512, 512), (4096, 4096, 4096), (16, 28672, 8192), (1, 8192, 28672), (1808, 7344, 272)]
+    ref = {s: bytes(g.gemm_select(*s, g.GEMM_BF16)) for s in shapes}
+    out = []
+
+    def worker():
+        for _ in range(20):
+            for s in shapes:
+                out.append(bytes(g.gemm_select(*s, g.GEMM_BF16)) == ref[s])
+
+    ts = [threading.Thread(target=worker) for _ in range(4)]
+    [t.start() for t in ts]
+    [t.join() for t in ts]
+    assert all(out) and len(out) == 4 * 20 * len(shapes)
+
+
+def test_hw_descriptor_roundtrip_and_retarget():
+    hw = g.gemm_hw_get()
+    assert hw.n_cu == 256 and hw.n_xcd == 8 and hw.lds_bytes == 160 * 1024 and hw.l2_bytes == 4 << 20
+    try:
+        small = g.gemm_hw_get()
+        small.n_cu, small.n_xcd = 64, 2          # a quarter of the chip: fewer CUs -> more waves for the same tiles
+        g.gemm_hw_set(small)
+        p_small = g.gemm_predict(g.gemm_cfg_at(0, 8192, 8192, 8192, 0))
+        g.gemm_hw_reset()
+        p_full = g.gemm_predict(g.gemm_cfg_at(0, 8192, 8192, 8192, 0))
+        assert p_small.waves == 4 * p_full.waves and p_small.total_us > 3 * p_full.total_us
+        bad = g.gemm_hw_get(); bad.n_cu = 0
+        with pytest.raises(g.GemmError):
+            g.gemm_hw_set(bad)
+    finally:
+        g.gemm_hw_reset()
+    assert bytes(g.gemm_hw_get()) == bytes(hw)
+
+
+def test_small_and_skinny_problems_do_not_get_one_giant_tile():
+    # Section II-A: a 256x256 output with one 256x256 tile would use a single CU
+    c = g.gemm_select(256, 256, 8192, g.GEMM_BF16)
+    tiles = -(-256 // c.block_m) * -(-256 // c.block_n) * c.split_k
+    assert tiles >= 32, c.describe()
+    for M in (1, 16, 64):
+        c = g.gemm_select(M, 28672, 8192, g.GEMM_BF16)
+        assert c.block_m <= 64, c.describe()
+    c = g.gemm_select(512, 512, 512, g.GEMM_BF16)
+    assert not (c.block_m == 256 and c.block_n == 256 and c.split_k == 1)

@@ -1,0 +1,104 @@
+"""Pins for the model oracle (oracle/selector_model.py): the values the paper prints and the
+closed forms its algorithms imply."""
+import math
+import os
+
+import pytest
+
+from oracle import selector_model as sm
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "paper_worked_examples.txt")
+
+
+def _gold():
+    out = {}
+    for line in open(GOLD):
+        line = line.split(";")[0].strip()
+        if not line or line.startswith("#"):
+            continue
+        k, v = line.split("=")
+        out[k.strip()] = v.strip()
+    return out
+
+
+def test_worked_tiling_example_section_2a():
+    g = _gold()
+    M, N, n_cu = int(g["example_M"]), int(g["example_N"]), int(g["example_n_cu"])
+    tm, tn, tk = (int(x) for x in g["small_tile"].split())
+    active, omega, t_out = sm.alg4_occupancy(M, N, tm, tn, n_cu)
+    assert t_out == int(g["small_tile_output_tiles"]) and omega == 1
+    assert active == 0          # the printed modulo gives 0 exactly where the text says "one tile per CU"
+    assert tm * tn * tk == int(g["small_tile_volume"])
+    tm, tn, tk = (int(x) for x in g["large_tile"].split())
+    active, omega, t_out = sm.alg4_occupancy(M, N, tm, tn, n_cu)
+    assert t_out == int(g["large_tile_output_tiles"]) and omega == 1 and active == 1
+    assert tm * tn * tk == int(g["large_tile_volume"])
+
+
+def test_factorisation_example_section_4c():
+    g = _gold()
+    want = [tuple(int(x) for x in p.split("x")) for p in g["factor_example_pairs"].split()]
+    assert sm.alg6_factorizations(int(g["factor_example_cus"])) == want
+    for n in (1, 7, 32, 38, 256, 304):
+        F = sm.alg6_factorizations(n)
+        assert all(a * b == n for a, b in F) and len(set(F)) == len(F)
+        assert len(F) == sum(1 for i in range(1, n + 1) if n % i == 0)
+
+
+def test_alg3_counts():
+    # 256x256x64 tile of 32x32x16 instructions: 8*8*4; ceilings on ragged tiles
+    assert sm.alg3_compute_latency(32, 32, 16, 256, 256, 64, 32.0) == (256, 8192.0)
+    assert sm.alg3_compute_latency(32, 32, 8, 48, 16, 20, 1.0)[0] == 2 * 1 * 3
+    n, l = sm.alg3_compute_latency(16, 16, 32, 16, 64, 128, 16.0)
+    assert n == 16 and l == 256.0
+
+
+def test_alg4_waves_and_tail():
+    assert sm.alg4_occupancy(4096, 4096, 256, 256, 256) == (0, 1, 256)
+    assert sm.alg4_occupancy(8192, 8192, 256, 256, 256) == (0, 4, 1024)
+    assert sm.alg4_occupancy(4096, 4096 + 1, 256, 256, 256) == (16, 2, 272)
+    assert sm.alg4_occupancy(1, 28672, 16, 256, 256) == (112, 1, 112)
+    assert sm.alg4_occupancy(300, 300, 128, 128, 304) == (9, 1, 9)
+
+
+def test_alg5_closed_forms():
+    # square s x s cache tile of square workgroup tiles: h = 1 - 1/s; 1 x 1 gives 0
+    for s in (1, 2, 4, 16):
+        assert sm.alg5_hit_rate(s, s, 128, 128, 64) == pytest.approx(1 - 1 / s)
+    assert sm.alg5_hit_rate(1, 1, 256, 64, 32) == 0
+    # K_T cancels; a 4 x 8 tile of 256 x 256: U = 12, R = 64
+    assert sm.alg5_hit_rate(4, 8, 256, 256, 64) == pytest.approx(1 - 12 / 64)
+    assert sm.alg5_hit_rate(4, 8, 256, 256, 64) == sm.alg5_hit_rate(4, 8, 256, 256, 16)
+    # asymmetric tiles: transposing the cache tile with the workgroup tile leaves h unchanged
+    assert sm.alg5_hit_rate(2, 8, 64, 256, 32) == pytest.approx(sm.alg5_hit_rate(8, 2, 256, 64, 32))
+    for fm, fn in sm.alg6_factorizations(32):
+        assert 0 <= sm.alg5_hit_rate(fm, fn, 128, 64, 64) <= 1
+
+
+def test_alg7_structure():
+    base = dict(ld_cu=1000.0, C=64, H1=0.5, H2=0.5, R_L1=10.0, R_1=400.0, R_2=300.0, R_MEM=100.0, L_lat=50.0)
+    v = sm.alg7_memory_latency(**base)
+    terms = [1000 / 10.0, 64000 / 400.0, 32000 / 300.0, 16000 / 100.0 + 50.0]
+    assert v == pytest.approx(max(terms)) and v == pytest.approx(210.0)
+    assert v >= base["ld_cu"] / base["R_L1"]
+    # non-increasing in either hit rate
+    for k in ("H1", "H2"):
+        prev = None
+        for h in (0.0, 0.3, 0.6, 0.9, 1.0):
+            cur = sm.alg7_memory_latency(**dict(base, **{k: h}))
+            assert prev is None or cur <= prev + 1e-12
+            prev = cur
+    # with perfect Mem1 hits only issue, Mem1 bandwidth and the bare latency remain
+    assert sm.alg7_memory_latency(**dict(base, H1=1.0)) == pytest.approx(max(100.0, 160.0, 50.0))
+
+
+def test_alg8_alg9_structure():
+    # K <= k_t: no loop iterations, only prologue + epilogue
+    assert sm.alg8_tile_latency(64, 64, 10.0, 99.0, 4, 16, 16, 8.0) == pytest.approx(10.0 + 4 * 256 / 8.0)
+    # one more K slab adds exactly max(l_compute, l_mem)
+    a = sm.alg8_tile_latency(640, 64, 10.0, 30.0, 1, 16, 16, 8.0)
+    b = sm.alg8_tile_latency(704, 64, 10.0, 30.0, 1, 16, 16, 8.0)
+    assert b - a == pytest.approx(30.0)
+    assert sm.alg9_total_latency(8192, 8192, 256, 256, 256, 7.0) == pytest.approx(4 * 7.0)
+    assert sm.alg9_total_latency(256, 256, 16, 16, 256, 7.0) == pytest.approx(7.0)
+    assert sm.alg9_total_latency(256, 272, 16, 16, 256, 7.0) == pytest.approx(2 * 7.0)
