@@ -76,12 +76,17 @@ typedef struct gemm_hw {
     double hbm_bytes_per_clk;  /* device total */
     double mall_bytes_per_clk; /* device total */
     double l2_bytes_per_clk;   /* per XCD */
-    double lds_bytes_per_clk;  /* per CU */
+    double lds_bytes_per_clk;  /* per CU, ds_read_b128 fragment reads */
+    double lds_tr_bytes_per_clk; /* per CU, transpose fragment reads (ds_read_b64_tr_*) */
     double vmem_bytes_per_clk; /* per CU vector-memory (L1) rate */
     double mem_latency_clk;    /* L_lat of Algorithm 7 */
     double cache_eff_frac;     /* fraction of a cache's capacity that holds reusable tiles */
     double launch_clk;         /* fixed cost per kernel launch, clocks */
     double wg_overhead_clk;    /* fixed cost per workgroup (dispatch, address setup, drain) */
+    double epilogue_clk;       /* fixed part of a tile's store stage */
+    double reduce_launch_clk;  /* fixed cost of the split-K reduction pass */
+    double under_occ_frac;     /* slab cost of a tile that has a CU to itself, as a fraction of its cost when the CU is full */
+    double seg_eff_lo;         /* share of the HBM rate reached with 32-byte row segments (1 from 256 bytes up) */
     double l_mi_clk[2][2];     /* issue interval L_MI of one MFMA: [dtype][0: 32x32, 1: 16x16] */
 } gemm_hw;
 
@@ -104,7 +109,7 @@ typedef struct gemm_cfg {
     uint16_t group_n;         /* cache-tile width f_n = CUs per L2 / f_m (informational) */
     uint8_t xcd_remap;        /* 1: workgroup ids are renumbered so that each XCD owns a contiguous id range */
     uint8_t stages;           /* LDS ring depth: K_T slabs resident or in flight per workgroup */
-    uint8_t reserved[2];
+    uint16_t slab_clk;        /* the variant's calibrated cost: clocks per K_T slab of one tile on a full CU */
     float alpha;              /* default 1; the caller may overwrite it before gemm_run */
     int32_t bottleneck;       /* gemm_bottleneck of the prediction */
     double predicted_us;      /* model's total latency for this cfg */
@@ -113,7 +118,8 @@ typedef struct gemm_cfg {
 /* Terms of the model for one cfg (clocks unless said otherwise), for tests and reports. */
 typedef struct gemm_prediction {
     double n_mi;          /* Algorithm 3: matrix instructions per workgroup tile and K slab */
-    double l_compute;     /* Algorithm 3 spread over the SIMDs, clocks per K slab */
+    double l_mt_ideal;    /* Algorithm 3: L_MI * N_MI spread over the workgroup's SIMDs (full utilisation) */
+    double l_compute;     /* compute latency used: the variant's measured clocks per K slab, times resident tiles */
     double tiles;         /* Algorithm 4: output tiles x split_k */
     double waves;         /* Algorithm 4: omega */
     double active_cu;     /* Algorithm 4: CUs busy in the last wave */

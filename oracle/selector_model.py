@@ -82,3 +82,153 @@ def alg9_total_latency(M, N, m_t, n_t, n_cu, l_tile):
     n_n = math.ceil(N / n_t)
     n_waves = math.ceil(n_m * n_n / n_cu)
     return n_waves * l_tile
+
+
+# ---------------------------------------------------------------- composition with readings
+
+def _ceil_div(a, b):
+    return -(-a // b)
+
+
+def occupancy(hw, v, es):
+    """READING: workgroups of variant v resident on one CU (LDS ring, register estimate, 8 at most)."""
+    lds = v["stages"] * (v["block_m"] + v["block_n"]) * v["block_k"] * es
+    waves = v["waves_m"] * v["waves_n"]
+    acc = v["block_m"] * v["block_n"] / (waves * 64.0)      # fp32 accumulators per lane
+    vgpr = acc + 64.0
+    waves_per_simd = max(1, min(8, int(512.0 // vgpr)))
+    by_regs = max(1, waves_per_simd * hw["simd_per_cu"] // waves)
+    by_lds = max(1, int(hw["lds_bytes"] // lds))
+    return max(1, min(by_regs, by_lds, 8))
+
+
+def choose_cache_tile(scope, v, tiles_m, tiles_n):
+    """READING: among Algorithm 6's pairs, clipped to the tile grid, the one with the highest
+    Algorithm-5 hit rate; ties -> cache tile closest to square in elements -> wider."""
+    best = None
+    for (i, j) in alg6_factorizations(scope):
+        fm, fn = min(i, tiles_m), min(j, tiles_n)
+        h = min(1.0, max(0.0, alg5_hit_rate(fm, fn, v["block_m"], v["block_n"], v["block_k"])))
+        skew = abs(fm * v["block_m"] - fn * v["block_n"])
+        better = False
+        if best is None or h > best["h"] + 1e-12:
+            better = True
+        elif abs(h - best["h"]) <= 1e-12:
+            if skew < best["skew"] - 1e-9:
+                better = True
+            elif abs(skew - best["skew"]) <= 1e-9 and fn > best["fn"]:
+                better = True
+        if better:
+            best = {"h": h, "skew": skew, "fm": fm, "fn": fn, "raw": i}
+    return best
+
+
+def segment_efficiency(hw, seg):
+    """READING: share of the HBM rate reached with `seg` contiguous bytes per matrix row."""
+    if seg >= 256:
+        return 1.0
+    s = max(seg, 32.0)
+    return min(1.0, hw["seg_eff_lo"] + (1.0 - hw["seg_eff_lo"]) * math.log2(s / 32.0) / 3.0)
+
+
+def predict(hw, dtype, M, N, K, v, split_k):
+    """Model terms for variant v (dict: block_m/n/k, waves_m/n, mfma, stages, slab_clk) with the
+    reduction split split_k ways; hw is a dict of the hardware descriptor's fields.  Returns a
+    dict with the names of the C ABI's gemm_prediction plus group_m."""
+    es = 2 if dtype == 0 else 1
+    mi = v["mfma"]
+    mi_k = {(0, 32): 16, (0, 16): 32, (1, 32): 64, (1, 16): 128}[(dtype, mi)]
+    waves_wg = v["waves_m"] * v["waves_n"]
+    out = {}
+
+    # Algorithm 3 (count, and latency at full utilisation spread over the workgroup's SIMDs)
+    l_mi = hw["l_mi_clk"][dtype][0 if mi == 32 else 1]
+    n_mi, l_mt = alg3_compute_latency(mi, mi, mi_k, v["block_m"], v["block_n"], v["block_k"], l_mi)
+    out["n_mi"] = n_mi
+    out["l_mt_ideal"] = l_mt / min(hw["simd_per_cu"], waves_wg)
+
+    # Algorithm 4.  READING: K slices count as tiles, a CU offers `occ` slots, a remainder of 0
+    # means a full last wave.
+    _, _, t_out = alg4_occupancy(M, N, v["block_m"], v["block_n"], hw["n_cu"])
+    tiles_m, tiles_n = _ceil_div(M, v["block_m"]), _ceil_div(N, v["block_n"])
+    tiles = t_out * split_k
+    occ = occupancy(hw, v, es)
+    slots = hw["n_cu"] * occ
+    waves = math.ceil(tiles / slots)
+    tail_tiles = tiles - (waves - 1) * slots
+    active = min(tail_tiles, hw["n_cu"])
+    tail_per_cu = math.ceil(tail_tiles / hw["n_cu"])
+    out.update(tiles=tiles, waves=waves, active_cu=active)
+
+    # Algorithms 5/6 + capacity derate (READING: h * min(1, eff * capacity / footprint))
+    l2_scope = hw["n_cu"] // hw["n_xcd"] * occ
+    c1 = choose_cache_tile(l2_scope, v, tiles_m, tiles_n)
+    c2 = choose_cache_tile(hw["n_cu"] * occ, v, tiles_m, tiles_n)
+    fp1 = (c1["fm"] * v["block_m"] + c1["fn"] * v["block_n"]) * v["block_k"] * es * 2.0
+    fp2 = (c2["fm"] * v["block_m"] + c2["fn"] * v["block_n"]) * v["block_k"] * es * 2.0
+    h1 = c1["h"] * min(1.0, hw["cache_eff_frac"] * hw["l2_bytes"] / fp1)
+    h2 = c2["h"] * min(1.0, hw["cache_eff_frac"] * hw["mall_bytes"] / fp2)
+    out.update(f_m=c1["fm"], f_n=c1["fn"], h_l2=h1, h_mall=h2)
+    out["group_m"] = max(1, min(c1["raw"], tiles_m))
+
+    k_slabs = _ceil_div(K, v["block_k"])
+    slabs = _ceil_div(k_slabs, split_k)              # slabs per K slice
+    out["iters"] = slabs - 1
+    out_bytes = 4.0 if split_k > 1 else 2.0
+
+    def memory(per_cu, act):
+        # Algorithm 7 in bytes and clocks.  READING: Ld_CU = (BM + BN) * BK bytes per tile; an LDS
+        # fragment-read term is added; the HBM term carries the row-segment efficiency and the
+        # latency is shared by the slabs in flight.
+        a_bytes = v["block_m"] * v["block_k"] * es * per_cu
+        b_bytes = v["block_n"] * v["block_k"] * es * per_cu
+        ld_cu = a_bytes + b_bytes
+        l_issue = ld_cu / hw["vmem_bytes_per_clk"]
+        l_lds = (v["block_m"] * v["waves_n"] * v["block_k"] * es / hw["lds_bytes_per_clk"]
+                 + v["block_n"] * v["waves_m"] * v["block_k"] * es / hw["lds_tr_bytes_per_clk"]) * per_cu
+        total = ld_cu * act
+        xcds = min(hw["n_xcd"], max(1.0, act))
+        l_l2 = (total / xcds) / hw["l2_bytes_per_clk"]
+        l_mall = (1.0 - h1) * total / hw["mall_bytes_per_clk"]
+        ea = segment_efficiency(hw, v["block_k"] * es)
+        eb = segment_efficiency(hw, v["block_n"] * es)
+        t_m = (1.0 - h2) * (1.0 - h1) * (a_bytes / ea + b_bytes / eb) * act
+        l_hbm = t_m / hw["hbm_bytes_per_clk"] + hw["mem_latency_clk"] / max(1.0, per_cu * (v["stages"] - 1))
+        return dict(l_issue=l_issue, l_lds=l_lds, l_l2=l_l2, l_mall=l_mall, l_hbm=l_hbm,
+                    l_mem=max(l_issue, l_lds, l_l2, l_mall, l_hbm))
+
+    def tile(per_cu, act):
+        # READING of Algorithm 3's "high utilisation" assumption: the compute latency of a slab is
+        # the variant's measured slab cost, scaled when the CU holds fewer tiles than fit.
+        l_comp = v["slab_clk"] * per_cu
+        if per_cu < occ:
+            l_comp *= hw["under_occ_frac"] + (1.0 - hw["under_occ_frac"]) * per_cu / occ
+        m = memory(per_cu, act)
+        # Algorithm 8.  READING: fixed latency and per-workgroup cost in the prologue, output bytes
+        # through the HBM rate plus a fixed cost in the epilogue, one exposed compute drain.
+        l_pro = m["l_mem"] + hw["mem_latency_clk"] + hw["wg_overhead_clk"]
+        l_epi = act * per_cu * v["block_m"] * v["block_n"] * out_bytes / hw["hbm_bytes_per_clk"] + hw["epilogue_clk"]
+        l_iter = max(l_comp, m["l_mem"])
+        l_tile = l_pro + l_epi + l_iter * (slabs - 1) + l_comp
+        return dict(m, l_compute=l_comp, l_prologue=l_pro, l_epilogue=l_epi, l_iter=l_iter, l_tile=l_tile)
+
+    full = tile(float(occ), float(hw["n_cu"]))
+    tail = tile(float(tail_per_cu), float(active))
+    shown = full if waves > 1 else tail
+    for k in ("l_compute", "l_issue", "l_lds", "l_l2", "l_mall", "l_hbm", "l_mem", "l_prologue", "l_epilogue",
+              "l_iter", "l_tile"):
+        out[k] = shown[k]
+    out["l_mem_tail"] = tail["l_mem"]
+    out["l_tile_tail"] = tail["l_tile"]
+
+    l_reduce = 0.0
+    if split_k > 1:
+        nbytes = M * N * (4.0 * split_k + 2.0)
+        rate = hw["mall_bytes_per_clk"] if nbytes <= hw["cache_eff_frac"] * hw["mall_bytes"] else hw["hbm_bytes_per_clk"]
+        l_reduce = hw["reduce_launch_clk"] + nbytes / rate
+    out["l_reduce"] = l_reduce
+    # Algorithm 9.  READING: full waves and the under-occupied last wave are priced separately,
+    # plus one launch.
+    out["l_total"] = hw["launch_clk"] + (waves - 1) * full["l_tile"] + tail["l_tile"] + l_reduce
+    out["total_us"] = out["l_total"] / (hw["clk_ghz"] * 1e3)
+    return out

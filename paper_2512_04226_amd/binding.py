@@ -33,9 +33,12 @@ class gemm_hw(ctypes.Structure):
                 ("mall_bytes", ctypes.c_double), ("clk_ghz", ctypes.c_double),
                 ("hbm_bytes_per_clk", ctypes.c_double), ("mall_bytes_per_clk", ctypes.c_double),
                 ("l2_bytes_per_clk", ctypes.c_double), ("lds_bytes_per_clk", ctypes.c_double),
+                ("lds_tr_bytes_per_clk", ctypes.c_double),
                 ("vmem_bytes_per_clk", ctypes.c_double), ("mem_latency_clk", ctypes.c_double),
                 ("cache_eff_frac", ctypes.c_double), ("launch_clk", ctypes.c_double),
-                ("wg_overhead_clk", ctypes.c_double), ("l_mi_clk", (ctypes.c_double * 2) * 2)]
+                ("wg_overhead_clk", ctypes.c_double), ("epilogue_clk", ctypes.c_double),
+                ("reduce_launch_clk", ctypes.c_double), ("under_occ_frac", ctypes.c_double),
+                ("seg_eff_lo", ctypes.c_double), ("l_mi_clk", (ctypes.c_double * 2) * 2)]
 
 
 class gemm_cfg(ctypes.Structure):
@@ -46,7 +49,7 @@ class gemm_cfg(ctypes.Structure):
                 ("waves_n", ctypes.c_uint8), ("mfma", ctypes.c_uint8), ("k_unroll", ctypes.c_uint8),
                 ("split_k", ctypes.c_uint16), ("group_m", ctypes.c_uint16), ("group_n", ctypes.c_uint16),
                 ("xcd_remap", ctypes.c_uint8), ("stages", ctypes.c_uint8),
-                ("reserved", ctypes.c_uint8 * 2), ("alpha", ctypes.c_float),
+                ("slab_clk", ctypes.c_uint16), ("alpha", ctypes.c_float),
                 ("bottleneck", ctypes.c_int32), ("predicted_us", ctypes.c_double)]
 
     def describe(self):
@@ -62,7 +65,7 @@ class gemm_cfg(ctypes.Structure):
 
 class gemm_prediction(ctypes.Structure):
     _fields_ = [(n, ctypes.c_double) for n in (
-        "n_mi", "l_compute", "tiles", "waves", "active_cu", "f_m", "f_n", "h_l2", "h_mall", "l_issue", "l_lds",
+        "n_mi", "l_mt_ideal", "l_compute", "tiles", "waves", "active_cu", "f_m", "f_n", "h_l2", "h_mall", "l_issue", "l_lds",
         "l_l2", "l_mall", "l_hbm", "l_mem", "l_mem_tail", "l_prologue", "l_epilogue", "l_iter", "iters", "l_tile",
         "l_tile_tail", "l_reduce", "l_total", "total_us")] + [("bottleneck", ctypes.c_int32),
                                                               ("reserved", ctypes.c_int32)]

@@ -16,7 +16,7 @@
 
 namespace g355 {
 
-#define G355_X(bm, bn, bk, wm, wn, mi, ns) {bm, bn, bk, wm, wn, mi, ns},
+#define G355_X(bm, bn, bk, wm, wn, mi, ns, tau) {bm, bn, bk, wm, wn, mi, ns, tau},
 static const Variant kVariantsBf16[] = {G355_VARIANTS_BF16(G355_X)};
 static const Variant kVariantsFp8[] = {G355_VARIANTS_FP8(G355_X)};
 #undef G355_X
@@ -31,9 +31,9 @@ const Variant &variant_at(int dtype, int id)
     return dtype == GEMM_BF16 ? kVariantsBf16[id] : kVariantsFp8[id];
 }
 
-// One MI355X.  Matrix-instruction issue intervals and the HBM rate come from
-// register-resident MFMA loops and a streaming read on the device, expressed in 2.4 GHz
-// clocks; cache rates are the public per-channel figures.
+// One MI355X.  Matrix-instruction issue intervals come from register-resident MFMA loops on
+// the device, expressed in 2.4 GHz clocks; the L2 rate is the public per-channel figure; the
+// remaining rates and fixed costs were fitted once against timings of this kernel family.
 static gemm_hw make_default_hw()
 {
     gemm_hw h;
@@ -45,15 +45,20 @@ static gemm_hw make_default_hw()
     h.l2_bytes = 4.0 * 1024 * 1024;
     h.mall_bytes = 256.0 * 1024 * 1024;
     h.clk_ghz = 2.4;
-    h.hbm_bytes_per_clk = 2600.0;   // ~6.2 TB/s sustained of the 8 TB/s pins
-    h.mall_bytes_per_clk = 5800.0;  // ~14 TB/s
-    h.l2_bytes_per_clk = 2048.0;    // 16 channels x 128 B per XCD
-    h.lds_bytes_per_clk = 128.0;
+    h.hbm_bytes_per_clk = 2500.0;    // 6.0 TB/s sustained of the 8 TB/s pins
+    h.mall_bytes_per_clk = 11600.0;
+    h.l2_bytes_per_clk = 2048.0;     // 16 channels x 128 B per XCD
+    h.lds_bytes_per_clk = 118.0;     // ds_read_b128 fragments
+    h.lds_tr_bytes_per_clk = 62.0;   // ds_read_b64_tr_* fragments
     h.vmem_bytes_per_clk = 64.0;
-    h.mem_latency_clk = 2000.0;
+    h.mem_latency_clk = 3060.0;
     h.cache_eff_frac = 0.5;
-    h.launch_clk = 6000.0;
-    h.wg_overhead_clk = 1500.0;
+    h.launch_clk = 1137.5;
+    h.wg_overhead_clk = 666.4;
+    h.epilogue_clk = 850.0;
+    h.reduce_launch_clk = 7200.0;
+    h.under_occ_frac = 0.72;
+    h.seg_eff_lo = 0.15;
     h.l_mi_clk[GEMM_BF16][0] = 39.7;      // v_mfma_f32_32x32x16_bf16  (2030 TFLOP/s device-wide)
     h.l_mi_clk[GEMM_BF16][1] = 31.8;      // v_mfma_f32_16x16x32_bf16  (1267 TFLOP/s)
     h.l_mi_clk[GEMM_FP8_E4M3][0] = 69.4;  // v_mfma_f32_32x32x64_f8f6f4 (4642 TFLOP/s)
@@ -184,6 +189,16 @@ struct MemTerms {
     double l_issue, l_lds, l_l2, l_mall, l_hbm, l_mem;
 };
 
+// Fraction of the HBM rate reached when a tile touches `seg` contiguous bytes of each matrix
+// row: 1 from 256 bytes up, falling linearly in log2(seg) to seg_eff_lo at 32 bytes.
+static double segment_efficiency(const gemm_hw &hw, double seg)
+{
+    if (seg >= 256.0)
+        return 1.0;
+    const double s = std::max(seg, 32.0);
+    return std::min(1.0, hw.seg_eff_lo + (1.0 - hw.seg_eff_lo) * std::log2(s / 32.0) / 3.0);
+}
+
 // Algorithm 7 for one K iteration.  `per_cu` = tiles a CU works on at once, `active` = CUs
 // busy.  Terms: per-CU vector-memory issue, LDS fragment reads (the software-managed-memory
 // bound of Section IV-D, which the printed algorithm leaves out), L2 (per XCD), MALL and HBM.
@@ -191,20 +206,23 @@ static MemTerms memory_latency(const gemm_hw &hw, const Variant &v, int es, doub
                                double h2)
 {
     MemTerms t;
-    const double ld_cu = (double)(v.block_m + v.block_n) * v.block_k * es * per_cu;  // bytes per CU per iteration
+    const double a_bytes = (double)v.block_m * v.block_k * es * per_cu;   // per CU and iteration
+    const double b_bytes = (double)v.block_n * v.block_k * es * per_cu;
+    const double ld_cu = a_bytes + b_bytes;
     t.l_issue = ld_cu / hw.vmem_bytes_per_clk;
-    // every wave reads its A rows and B columns of the slab from LDS
-    const double lds_rd = ((double)v.block_m * v.waves_n + (double)v.block_n * v.waves_m) * v.block_k * es * per_cu;
-    t.l_lds = lds_rd / hw.lds_bytes_per_clk;
-    const double cus_per_l2 = (double)hw.n_cu / hw.n_xcd;
-    const double xcds_busy = std::min<double>(hw.n_xcd, std::max(1.0, active));       // round-robin dispatch
+    // every wave reads its A rows (ds_read_b128) and its B columns (transpose reads) of the slab
+    t.l_lds = ((double)v.block_m * v.waves_n * v.block_k * es / hw.lds_bytes_per_clk +
+               (double)v.block_n * v.waves_m * v.block_k * es / hw.lds_tr_bytes_per_clk) *
+              per_cu;
+    const double xcds_busy = std::min<double>(hw.n_xcd, std::max(1.0, active));   // round-robin dispatch
     const double total = ld_cu * active;
     t.l_l2 = (total / xcds_busy) / hw.l2_bytes_per_clk;
-    (void)cus_per_l2;
-    const double t2 = (1.0 - h1) * total;
-    t.l_mall = t2 / hw.mall_bytes_per_clk;
-    const double tm = (1.0 - h2) * t2;
-    t.l_hbm = tm / hw.hbm_bytes_per_clk + hw.mem_latency_clk / std::max(1.0, per_cu);
+    t.l_mall = (1.0 - h1) * total / hw.mall_bytes_per_clk;
+    // what misses both caches, inflated by the row-segment efficiency of each operand
+    const double ea = segment_efficiency(hw, (double)v.block_k * es);
+    const double eb = segment_efficiency(hw, (double)v.block_n * es);
+    const double tm = (1.0 - h2) * (1.0 - h1) * (a_bytes / ea + b_bytes / eb) * active;
+    t.l_hbm = tm / hw.hbm_bytes_per_clk + hw.mem_latency_clk / std::max(1.0, per_cu * (v.stages - 1));
     t.l_mem = std::max(std::max(t.l_issue, t.l_lds), std::max(std::max(t.l_l2, t.l_mall), t.l_hbm));
     return t;
 }
@@ -234,10 +252,12 @@ void predict(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, cons
     const int waves_wg = v.waves_m * v.waves_n;
     const int mi_k = mfma_k(dtype, v.mfma);
 
-    // Algorithm 3, spread over the SIMDs that the workgroups resident on a CU occupy.
+    // Algorithm 3: instruction count and the latency it would have at full matrix-core
+    // utilisation (reported); the latency the model uses is the kernel's measured slab cost.
     const double n_mi = (double)cdiv(v.block_m, v.mfma) * cdiv(v.block_n, v.mfma) * cdiv(v.block_k, mi_k);
     const double l_mi = hw.l_mi_clk[dtype][v.mfma == 32 ? 0 : 1];
     p->n_mi = n_mi;
+    p->l_mt_ideal = n_mi * l_mi / std::min<double>(hw.simd_per_cu, waves_wg);
 
     // Algorithm 4, with K slices counted as tiles and `occ` workgroups per CU as slots.
     const int64_t tiles_m = cdiv(M, v.block_m), tiles_n = cdiv(N, v.block_n);
@@ -260,9 +280,8 @@ void predict(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, cons
     best_factor_pair(hw.n_cu * occ, v, tiles_m, tiles_n, &fm2, &fn2, &fm2_raw);
     double h1 = hit_rate(fm, fn, v.block_m, v.block_n);
     double h2 = hit_rate(fm2, fn2, v.block_m, v.block_n);
-    // Capacity derate: the working set of one K step of the cache tile (both LDS stages in
-    // flight) against the usable share of the cache; beyond it the hit rate shrinks in
-    // proportion.
+    // Capacity derate: the working set of one K step of the cache tile (two slabs in flight)
+    // against the usable share of the cache; beyond it the hit rate shrinks in proportion.
     const double fp1 = (fm * v.block_m + fn * v.block_n) * v.block_k * es * 2.0;
     const double fp2 = (fm2 * v.block_m + fn2 * v.block_n) * v.block_k * es * 2.0;
     h1 *= std::min(1.0, hw.cache_eff_frac * hw.l2_bytes / fp1);
@@ -281,12 +300,14 @@ void predict(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, cons
 
     auto tile_latency = [&](double per_cu, double act, MemTerms *mt_out, double *l_comp_out, double *pro, double *epi,
                             double *iter) {
-        const double simds = std::min<double>(hw.simd_per_cu, per_cu * waves_wg);
-        const double l_comp = n_mi * l_mi * per_cu / simds;
+        // per_cu tiles share the CU; fewer than fit run a little faster each, but not in proportion
+        double l_comp = (double)v.slab_clk * per_cu;
+        if (per_cu < occ)
+            l_comp *= hw.under_occ_frac + (1.0 - hw.under_occ_frac) * per_cu / occ;
         const MemTerms mt = memory_latency(hw, v, es, per_cu, act, h1, h2);
-        const double l_pro = mt.l_mem + hw.wg_overhead_clk;
+        const double l_pro = mt.l_mem + hw.mem_latency_clk + hw.wg_overhead_clk;
         // the store stage scales with the output tile only; results leave through HBM
-        const double l_epi = act * per_cu * v.block_m * v.block_n * out_bytes / hw.hbm_bytes_per_clk;
+        const double l_epi = act * per_cu * v.block_m * v.block_n * out_bytes / hw.hbm_bytes_per_clk + hw.epilogue_clk;
         const double l_iter = std::max(l_comp, mt.l_mem);
         *mt_out = mt;
         *l_comp_out = l_comp;
@@ -322,7 +343,7 @@ void predict(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, cons
     if (split_k > 1) {
         const double bytes = (double)M * N * (4.0 * split_k + 2.0);
         const double rate = (bytes <= hw.cache_eff_frac * hw.mall_bytes) ? hw.mall_bytes_per_clk : hw.hbm_bytes_per_clk;
-        l_reduce = hw.launch_clk + hw.mem_latency_clk + bytes / rate;
+        l_reduce = hw.reduce_launch_clk + bytes / rate;
     }
     p->l_reduce = l_reduce;
 
@@ -361,6 +382,7 @@ void fill_cfg(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, int
     c->group_n = (uint16_t)gn;
     c->xcd_remap = 1;
     c->stages = (uint8_t)v.stages;
+    c->slab_clk = (uint16_t)v.slab_clk;
     c->alpha = 1.0f;
     c->bottleneck = p.bottleneck;
     c->predicted_us = p.total_us;

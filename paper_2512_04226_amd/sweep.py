@@ -45,7 +45,9 @@ class Workspace:
 
 
 def time_cfg(cfg, A, B, C, ws, min_ms=1.0, max_iters=200, repeats=3):
-    """Median-of-repeats microseconds per launch (events on torch's current stream)."""
+    """Microseconds per launch: `iters` back-to-back launches captured in a HIP graph (so
+    that host launch overhead does not mask short kernels), replayed `repeats` times between
+    events on torch's current stream; the median replay is reported."""
     ws.ensure(cfg)
     g.gemm_run(cfg, A, B, C)
     torch.cuda.synchronize()
@@ -56,14 +58,20 @@ def time_cfg(cfg, A, B, C, ws, min_ms=1.0, max_iters=200, repeats=3):
     e1.synchronize()
     one = max(e0.elapsed_time(e1), 1e-3)
     iters = int(min(max_iters, max(3, min_ms / one)))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(iters):
+            g.gemm_run(cfg, A, B, C)
+    graph.replay()
+    torch.cuda.synchronize()
     times = []
     for _ in range(repeats):
         e0.record()
-        for _ in range(iters):
-            g.gemm_run(cfg, A, B, C)
+        graph.replay()
         e1.record()
         e1.synchronize()
         times.append(e0.elapsed_time(e1) * 1e3 / iters)
+    del graph
     return float(np.median(times))
 
 

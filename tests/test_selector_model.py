@@ -102,3 +102,80 @@ def test_alg8_alg9_structure():
     assert sm.alg9_total_latency(8192, 8192, 256, 256, 256, 7.0) == pytest.approx(4 * 7.0)
     assert sm.alg9_total_latency(256, 256, 16, 16, 256, 7.0) == pytest.approx(7.0)
     assert sm.alg9_total_latency(256, 272, 16, 16, 256, 7.0) == pytest.approx(2 * 7.0)
+
+
+# ---------------- the shipped selector's terms against the oracle's composition ----------------
+
+def _hw_dict(g):
+    hw = g.gemm_hw_get()
+    d = {name: getattr(hw, name) for name, _ in hw._fields_ if name not in ("l_mi_clk", "reserved0")}
+    d["l_mi_clk"] = [[hw.l_mi_clk[i][j] for j in range(2)] for i in range(2)]
+    return d
+
+
+def _variant_dict(c):
+    return dict(block_m=c.block_m, block_n=c.block_n, block_k=c.block_k, waves_m=c.waves_m, waves_n=c.waves_n,
+                mfma=c.mfma, stages=c.stages, slab_clk=c.slab_clk)
+
+
+SHAPES = [(512, 512, 512), (4096, 4096, 4096), (8192, 8192, 8192), (1, 28672, 8192), (16, 8192, 28672),
+          (256, 28672, 8192), (64, 64, 16384), (1808, 7344, 272), (11296, 64, 13504), (300, 520, 72), (16384, 16384, 64)]
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_shipped_model_terms_match_the_oracle(dtype):
+    from paper_2512_04226_amd import binding as g
+    hw = _hw_dict(g)
+    fields = ["n_mi", "l_mt_ideal", "l_compute", "tiles", "waves", "active_cu", "f_m", "f_n", "h_l2", "h_mall",
+              "l_issue", "l_lds", "l_l2", "l_mall", "l_hbm", "l_mem", "l_mem_tail", "l_prologue", "l_epilogue",
+              "l_iter", "iters", "l_tile", "l_tile_tail", "l_reduce", "l_total", "total_us"]
+    checked = 0
+    for (M, N, K) in SHAPES:
+        if dtype == 1 and (N % 16 or K % 16):
+            continue
+        for idx in range(g.gemm_cfg_count(dtype)):
+            c = g.gemm_cfg_at(idx, M, N, K, dtype)
+            if c is None:
+                continue
+            p = g.gemm_predict(c)
+            o = sm.predict(hw, dtype, M, N, K, _variant_dict(c), c.split_k)
+            for f in fields:
+                assert getattr(p, f) == pytest.approx(o[f], rel=1e-9, abs=1e-9), (M, N, K, c.describe(), f)
+            assert c.group_m == o["group_m"] and c.predicted_us == pytest.approx(o["total_us"], rel=1e-9)
+            checked += 1
+    assert checked > 500
+
+
+def test_pick_is_the_oracle_argmin():
+    """gemm_select = first minimum of the oracle's predicted latency in enumeration order."""
+    from paper_2512_04226_amd import binding as g
+    hw = _hw_dict(g)
+    for (M, N, K) in SHAPES:
+        best = None
+        for idx in range(g.gemm_cfg_count(0)):
+            c = g.gemm_cfg_at(idx, M, N, K, 0)
+            if c is None:
+                continue
+            t = sm.predict(hw, 0, M, N, K, _variant_dict(c), c.split_k)["l_total"]
+            if best is None or t < best[0] * (1 - 1e-12):
+                best = (t, c.kernel_id, c.split_k)
+        pick = g.gemm_select(M, N, K, 0)
+        assert (pick.kernel_id, pick.split_k) == best[1:], (M, N, K, pick.describe())
+
+
+def test_model_reduces_to_the_papers_form_when_extras_are_off():
+    """With one workgroup per CU, no fixed costs, perfect segments and a full last wave the
+    composition is Algorithm 8 + Algorithm 9 on the same terms (plus the drain reading)."""
+    hw = dict(n_cu=256, n_xcd=8, simd_per_cu=4, lds_bytes=160 * 1024, l2_bytes=4 << 20, mall_bytes=256 << 20,
+              clk_ghz=2.4, hbm_bytes_per_clk=2500.0, mall_bytes_per_clk=6000.0, l2_bytes_per_clk=2048.0,
+              lds_bytes_per_clk=128.0, lds_tr_bytes_per_clk=128.0, vmem_bytes_per_clk=64.0, mem_latency_clk=0.0,
+              cache_eff_frac=0.5, launch_clk=0.0, wg_overhead_clk=0.0, epilogue_clk=0.0, reduce_launch_clk=0.0,
+              under_occ_frac=1.0, seg_eff_lo=1.0, l_mi_clk=[[32.0, 16.0], [64.0, 32.0]])
+    v = dict(block_m=256, block_n=256, block_k=64, waves_m=2, waves_n=2, mfma=32, stages=2, slab_clk=2048)
+    o = sm.predict(hw, 0, 8192, 8192, 8192, v, 1)
+    assert o["waves"] == 4 and o["active_cu"] == 256 and o["l_mt_ideal"] == 256 * 32.0 / 4
+    l_epi = 256 * 256 * 256 * 2.0 / 2500.0
+    l_tile = sm.alg8_tile_latency(8192, 64, o["l_mem"], o["l_compute"], 1, 1, l_epi, 1.0) + o["l_compute"]
+    assert o["l_tile"] == pytest.approx(l_tile)
+    assert o["l_total"] == pytest.approx(sm.alg9_total_latency(8192, 8192, 256, 256, 256, l_tile))
+    assert o["h_l2"] == pytest.approx(sm.alg5_hit_rate(4, 8, 256, 256, 64))
