@@ -8,6 +8,11 @@ missing this module raises at import.
 import ctypes
 import os
 
+# PyTorch bundles its own HIP runtime.  Loading it first makes libgemm355.so resolve
+# libamdhip64 to that same copy: one runtime per process, so that streams and device
+# pointers handed over by torch belong to the runtime that launches the kernels.
+import torch  # noqa: F401
+
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libgemm355.so")
 

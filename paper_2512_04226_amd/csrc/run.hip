@@ -159,6 +159,7 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
         size_t blocks = (quads + 255) / 256;
         if (blocks > 256 * 8)
             blocks = 256 * 8;
+        (void)hipGetLastError();
         hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, ws, (__bf16 *)C, a.M,
                            a.N, a.ldc, a.split_k, a.alpha);
         if (hipGetLastError() != hipSuccess)

@@ -1,0 +1,205 @@
+"""GPU parity at the benchmark configurations' full sizes (through the C ABI, in the launch
+configuration the selector picks), on outputs the oracle can compute one by one, plus edge
+cases and error paths that need a device."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_04226_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+BF16, E4M3 = 0, 1
+
+
+@pytest.fixture(scope="module")
+def g():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2512_04226_amd import binding
+    return binding
+
+
+def _rows_to_check(M, block_m, n_random=3, seed=0):
+    """First/last rows, both sides of the first tile boundary, and a few random rows."""
+    rows = {0, M - 1, min(M - 1, block_m - 1), min(M - 1, block_m), M // 2}
+    gen = np.random.default_rng(seed)
+    rows.update(int(r) for r in gen.integers(0, M, n_random))
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+def _check_rows(g, oracle, A, B, dtype, cfg, alpha, max_a, max_b, rows=None):
+    from gpu_util import bf16_to_f64, run_cfg, to_dev
+    M, K = A.shape
+    N = B.shape[1]
+    out = run_cfg(cfg, to_dev(A), to_dev(B), M, N, alpha=alpha)
+    rows = _rows_to_check(M, cfg.block_m) if rows is None else rows
+    _, ref64 = oracle.gemm_rows(A, B, rows, dtype, alpha=alpha)
+    got = bf16_to_f64(out[rows])
+    assert np.isfinite(got).all(), "unwritten or non-finite outputs in checked rows"
+    err = float(np.max(np.abs(got - ref64)))
+    tol = oracle.tolerance(K, max_a, max_b, dtype)
+    assert err <= tol, (cfg.describe(), err, tol)
+    # every output must have been written (the buffer was poisoned with a NaN pattern)
+    assert not np.any((out & 0x7FFF) > 0x7F80), "NaN left in the output"
+    return err, tol
+
+
+@pytest.mark.parametrize("n", [4096, 8192])
+def test_config2_square_bf16(g, oracle, n):
+    A, B = wl.config2(n)
+    cfg = g.gemm_select(n, n, n, BF16)
+    max_a = float(np.abs(wl.bf16_bits_to_f32(A)).max())
+    max_b = float(np.abs(wl.bf16_bits_to_f32(B)).max())
+    err, tol = _check_rows(g, oracle, A, B, BF16, cfg, 1.0, max_a, max_b)
+    assert err <= 0.1 * tol          # in practice far inside the bound
+
+
+@pytest.mark.parametrize("N,K", wl.SKINNY_NK)
+def test_config3_skinny_bf16(g, oracle, N, K):
+    for M in wl.SKINNY_M:
+        A, B = wl.config3(M, N, K)
+        cfg = g.gemm_select(M, N, K, BF16)
+        assert cfg.block_m <= max(64, M), cfg.describe()      # the selector shrinks BLOCK_M for few tokens
+        max_a = float(np.abs(wl.bf16_bits_to_f32(A)).max())
+        max_b = float(np.abs(wl.bf16_bits_to_f32(B)).max())
+        rows = np.arange(M) if M <= 16 else _rows_to_check(M, cfg.block_m, n_random=2)
+        _check_rows(g, oracle, A, B, BF16, cfg, 1.0, max_a, max_b, rows=rows)
+        del A, B
+
+
+def test_config4_fp8_8192(g, oracle):
+    n = 8192
+    A, B, sa, sb = wl.config4(n)
+    alpha = float(sa) * float(sb)
+    cfg = g.gemm_select(n, n, n, E4M3)
+    # maxima of the real-valued (scale-applied) tensors: 448 * scale by construction
+    _check_rows(g, oracle, A, B, E4M3, cfg, alpha, 448.0 * float(sa), 448.0 * float(sb),
+                rows=_rows_to_check(n, cfg.block_m, n_random=1))
+
+
+def test_config5_irregular_shapes(g, oracle):
+    shapes = wl.config5_shapes()
+    assert len(shapes) == 64 and all(64 <= d <= 16384 and d % 16 == 0 for s in shapes for d in s)
+    for i, (M, N, K) in enumerate(shapes):
+        A, B = wl.config5(i, shapes)
+        cfg = g.gemm_select(M, N, K, BF16)
+        rows = _rows_to_check(M, cfg.block_m, n_random=1, seed=i)
+        _check_rows(g, oracle, A, B, BF16, cfg, 1.0, 1.0, 1.0, rows=rows)
+
+
+def test_fp8_random_every_variant_within_tolerance(g, oracle):
+    """Random e4m3 data (not exact in fp32): every variant against the full oracle product."""
+    from gpu_util import bf16_to_f64, run_cfg, to_dev
+    M, N, K = 272, 528, 1040
+    A, B, sa, sb = wl.normal_e4m3(M, N, K, seed=3, case=7)
+    alpha = float(sa) * float(sb)
+    _, ref64 = oracle.gemm(A, B, E4M3, alpha=alpha)
+    tol = oracle.tolerance(K, 448.0 * float(sa), 448.0 * float(sb), E4M3)
+    dA, dB = to_dev(A), to_dev(B)
+    worst = 0.0
+    for idx in range(g.gemm_cfg_count(E4M3)):
+        c = g.gemm_cfg_at(idx, M, N, K, E4M3)
+        if c is None:
+            continue
+        out = run_cfg(c, dA, dB, M, N, alpha=alpha)
+        err = float(np.max(np.abs(bf16_to_f64(out) - ref64)))
+        assert err <= tol, (c.describe(), err, tol)
+        worst = max(worst, err)
+    assert worst <= 0.05 * tol
+
+
+@pytest.mark.parametrize("shape", [(1, 8, 8), (1, 16, 8), (3, 8, 16), (17, 24, 40), (1, 4096, 64), (255, 264, 8),
+                                   (257, 8, 4104), (33, 1000, 72)])
+def test_edge_shapes_bit_exact(g, oracle, shape):
+    """Degenerate and ragged shapes, integer data, every legal variant."""
+    from gpu_util import run_cfg, to_dev
+    M, N, K = shape
+    A, B = wl.integer_bf16(M, N, K, seed=5, case=M + N + K, lo=-3, hi=3)
+    ref16, _ = oracle.gemm(A, B, BF16, alpha=0.5)
+    dA, dB = to_dev(A), to_dev(B)
+    n_run = 0
+    for idx in range(g.gemm_cfg_count(BF16)):
+        c = g.gemm_cfg_at(idx, M, N, K, BF16)
+        if c is None:
+            continue
+        out = run_cfg(c, dA, dB, M, N, alpha=0.5)
+        assert np.array_equal(out, ref16), (c.describe(), int((out != ref16).sum()))
+        n_run += 1
+    assert n_run >= 30
+
+
+def test_padded_leading_dimensions_and_alpha(g, oracle):
+    from gpu_util import to_dev, workspace_for
+    M, N, K = 200, 264, 328
+    lda, ldb, ldc = K + 24, N + 40, N + 8
+    A, B = wl.integer_bf16(M, N, K, seed=9)
+    Ap = np.full((M, lda), 0x7FC0, np.uint16); Ap[:, :K] = A      # NaN padding must never be read into results
+    Bp = np.full((K, ldb), 0x7FC0, np.uint16); Bp[:, :N] = B
+    ref16, _ = oracle.gemm(A, B, BF16, alpha=-2.0)
+    dA, dB = to_dev(Ap), to_dev(Bp)
+    for idx in (0, 5, 60, 130, 170, 200):
+        c = g.gemm_cfg_at(idx, M, N, K, BF16)
+        if c is None:
+            continue
+        c.lda, c.ldb, c.ldc, c.alpha = lda, ldb, ldc, -2.0
+        workspace_for(c)
+        dC = torch.full((M, ldc), 0x1234, dtype=torch.int16, device="cuda")
+        g.gemm_run(c, dA, dB, dC)
+        torch.cuda.synchronize()
+        out = dC.cpu().numpy().view(np.uint16)
+        assert np.array_equal(out[:, :N], ref16), c.describe()
+        assert np.all(out[:, N:] == 0x1234), "wrote outside the N columns of C"
+
+
+def test_runs_are_bit_identical_and_split_k_needs_a_workspace(g, oracle):
+    from gpu_util import run_cfg, to_dev
+    M, N, K = 320, 384, 4096
+    A, B = wl.uniform_bf16(M, N, K, seed=12)
+    dA, dB = to_dev(A), to_dev(B)
+    split = next(c for c in (g.gemm_cfg_at(i, M, N, K, BF16) for i in range(g.gemm_cfg_count(BF16)))
+                 if c is not None and c.split_k == 8 and c.block_m == 64)
+    a = run_cfg(split, dA, dB, M, N)
+    b = run_cfg(split, dA, dB, M, N)
+    assert np.array_equal(a, b)                       # slice-ordered reduction: deterministic
+    _, ref64 = oracle.gemm(A, B, BF16)
+    from gpu_util import bf16_to_f64
+    assert np.max(np.abs(bf16_to_f64(a) - ref64)) <= oracle.tolerance(K, 1.0, 1.0, BF16)
+    # error path: split-K without a registered (or with a too small) workspace launches nothing
+    import gpu_util
+    g.gemm_set_workspace(None)
+    gpu_util._ws.clear()
+    dC = torch.zeros((M, N), dtype=torch.int16, device="cuda")
+    rc = g._lib.gemm_run(ctypes.byref(split), ctypes.c_void_p(dA.data_ptr()), ctypes.c_void_p(dB.data_ptr()),
+                         ctypes.c_void_p(dC.data_ptr()), None)
+    assert rc == -6
+    small = torch.empty(16, dtype=torch.float32, device="cuda")
+    g.gemm_set_workspace(small)
+    rc = g._lib.gemm_run(ctypes.byref(split), ctypes.c_void_p(dA.data_ptr()), ctypes.c_void_p(dB.data_ptr()),
+                         ctypes.c_void_p(dC.data_ptr()), None)
+    assert rc == -6
+    torch.cuda.synchronize()
+    assert not dC.any()
+    g.gemm_set_workspace(None)
+
+
+def test_large_shape_16384(g, oracle):
+    M, N, K = 16384, 16384, 256
+    A, B = wl.uniform_bf16(M, N, K, seed=13)
+    cfg = g.gemm_select(M, N, K, BF16)
+    _check_rows(g, oracle, A, B, BF16, cfg, 1.0, 1.0, 1.0, rows=np.array([0, 8191, 8192, 16383]))
+
+
+def test_runs_on_a_side_stream(g, oracle):
+    from gpu_util import to_dev
+    A, B = wl.config1(integer=True)
+    ref16, _ = oracle.gemm(A, B, BF16)
+    dA, dB = to_dev(A), to_dev(B)
+    cfg = g.gemm_cfg_at(0, 512, 512, 512, BF16)
+    s = torch.cuda.Stream()
+    dC = torch.zeros((512, 512), dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    g.gemm_run(cfg, dA, dB, dC, stream=s)
+    s.synchronize()
+    assert np.array_equal(dC.cpu().numpy().view(np.uint16), ref16)
