@@ -181,6 +181,19 @@ int gemm_hw_get(gemm_hw *out);
 int gemm_hw_set(const gemm_hw *in);
 int gemm_hw_reset(void);
 
+/*
+ * Calibration probes (Section I: the model's hardware rates come from micro-benchmarks).
+ * Each runs two launches on hip_stream, times the second with HIP events, synchronises and
+ * writes the measured rate.  scratch4: caller-owned device memory, at least 4 bytes.
+ *   gemm_probe_mfma   register-resident MFMA loop for (dtype, mfma in {32, 16}) -> TFLOP/s on the
+ *                     whole device; L_MI in clocks = flop per instruction * n_cu * simd_per_cu *
+ *                     clk_ghz / (TFLOP/s * 1e3).
+ *   gemm_probe_stream streaming 128-bit reads of buf[0, bytes) (device memory, 16-byte aligned,
+ *                     >= 1 MiB; use more than the 256 MiB MALL to measure HBM) -> GB/s.
+ */
+int gemm_probe_mfma(int dtype, int mfma, void *scratch4, void *hip_stream, double *tflops_out);
+int gemm_probe_stream(const void *buf, size_t bytes, void *scratch4, void *hip_stream, double *gbps_out);
+
 #ifdef __cplusplus
 }
 #endif

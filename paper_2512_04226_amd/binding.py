@@ -108,6 +108,34 @@ _lib.gemm_hw_reset.restype = _int
 _lib.gemm_hw_reset.argtypes = []
 
 
+_lib.gemm_probe_mfma.restype = _int
+_lib.gemm_probe_mfma.argtypes = [_int, _int, _vp, _vp, ctypes.POINTER(ctypes.c_double)]
+_lib.gemm_probe_stream.restype = _int
+_lib.gemm_probe_stream.argtypes = [_vp, ctypes.c_size_t, _vp, _vp, ctypes.POINTER(ctypes.c_double)]
+
+
+def gemm_probe_mfma(dtype, mfma, scratch, stream=None):
+    """Device-wide TFLOP/s of a register-resident MFMA loop (scratch: any device tensor)."""
+    out = ctypes.c_double()
+    _check(_lib.gemm_probe_mfma(dtype, mfma, _ptr(scratch), ctypes.c_void_p(_stream_handle(stream)),
+                                ctypes.byref(out)), "gemm_probe_mfma")
+    return out.value
+
+
+def gemm_probe_stream(buf, scratch, stream=None):
+    """GB/s of a streaming read over the device tensor buf."""
+    out = ctypes.c_double()
+    _check(_lib.gemm_probe_stream(_ptr(buf), buf.numel() * buf.element_size(), _ptr(scratch),
+                                  ctypes.c_void_p(_stream_handle(stream)), ctypes.byref(out)), "gemm_probe_stream")
+    return out.value
+
+
+def _stream_handle(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+
+
 def gemm_abi_version():
     return int(_lib.gemm_abi_version())
 
@@ -184,9 +212,5 @@ def _ptr(t):
 def gemm_run(cfg, A, B, C, stream=None):
     """Enqueue C = alpha * A * B.  stream: a torch.cuda.Stream, a raw hipStream_t int, or
     None for torch's current stream."""
-    if stream is None:
-        import torch
-        stream = torch.cuda.current_stream().cuda_stream
-    elif hasattr(stream, "cuda_stream"):
-        stream = stream.cuda_stream
-    _check(_lib.gemm_run(ctypes.byref(cfg), _ptr(A), _ptr(B), _ptr(C), ctypes.c_void_p(stream)), "gemm_run")
+    _check(_lib.gemm_run(ctypes.byref(cfg), _ptr(A), _ptr(B), _ptr(C), ctypes.c_void_p(_stream_handle(stream))),
+           "gemm_run")

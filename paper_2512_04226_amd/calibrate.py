@@ -1,0 +1,77 @@
+"""Device calibration of the model's constants (a one-off, offline step; never run by
+gemm_select or gemm_run):
+
+  * L_MI of every matrix instruction and the HBM streaming rate, from the library's probes;
+  * SLAB_CLK of every kernel variant: steady-state clocks per K slab of one tile on a full CU,
+    from one large compute-bound problem per datatype (8192^3).
+
+Prints the hardware lines and the variants.hpp rows with the measured last column.
+
+    python -m paper_2512_04226_amd.calibrate [--n 8192]
+"""
+import argparse
+
+import torch
+
+from . import binding as g
+from .sweep import Workspace, make_operands, time_cfg
+
+
+def measure_rates():
+    scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
+    hw = g.gemm_hw_get()
+    out = {}
+    for dt, name in ((g.GEMM_BF16, "bf16"), (g.GEMM_FP8_E4M3, "fp8")):
+        for mi in (32, 16):
+            tf = g.gemm_probe_mfma(dt, mi, scratch)
+            k = {(0, 32): 16, (0, 16): 32, (1, 32): 64, (1, 16): 128}[(dt, mi)]
+            flop = 2.0 * mi * mi * k
+            l_mi = flop * hw.n_cu * hw.simd_per_cu * hw.clk_ghz / (tf * 1e3)
+            out[(name, mi)] = (tf, l_mi)
+    buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)     # 1 GiB > MALL
+    out["hbm_gbps"] = g.gemm_probe_stream(buf, scratch)
+    return out
+
+
+def measure_slab_clk(dtype, n):
+    hw = g.gemm_hw_get()
+    A, B, C = make_operands(n, n, n, dtype)
+    ws = Workspace()
+    rows = []
+    count = g.gemm_cfg_count(dtype)
+    seen = set()
+    for idx in range(count):
+        cfg = g.gemm_cfg_at(idx, n, n, n, dtype)
+        if cfg is None or cfg.split_k != 1 or cfg.kernel_id in seen:
+            continue
+        seen.add(cfg.kernel_id)
+        us = time_cfg(cfg, A, B, C, ws, min_ms=3.0)
+        tiles = -(-n // cfg.block_m) * -(-n // cfg.block_n)
+        slabs = -(-n // cfg.block_k)
+        clk = us * hw.clk_ghz * 1e3 - hw.launch_clk
+        rows.append((cfg, us, clk * hw.n_cu / (tiles * slabs)))
+    return rows
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--n", type=int, default=8192)
+    ap.add_argument("--skip-rates", action="store_true")
+    args = ap.parse_args()
+    if not args.skip_rates:
+        r = measure_rates()
+        for key, val in r.items():
+            if key == "hbm_gbps":
+                print("HBM streaming read: %.0f GB/s" % val)
+            else:
+                print("MFMA %s %dx%d: %.0f TFLOP/s device-wide -> L_MI = %.1f clk" % (key[0], key[1], key[1], val[0], val[1]))
+    for dtype, name in ((g.GEMM_BF16, "BF16"), (g.GEMM_FP8_E4M3, "FP8")):
+        print("// %s variants, SLAB_CLK measured on %d^3" % (name, args.n))
+        for cfg, us, tau in measure_slab_clk(dtype, args.n):
+            print("    X(%d, %d, %d, %d, %d, %d, %d, %d)   // %.1f us, %.0f TFLOP/s" % (
+                cfg.block_m, cfg.block_n, cfg.block_k, cfg.waves_m, cfg.waves_n, cfg.mfma, cfg.stages, round(tau), us,
+                2.0 * args.n ** 3 / us * 1e-6), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -72,12 +72,12 @@ struct Tile {
         return (l < A_LOADS) ? (A_UNITS % NW == 0 || (l * NW + NW - 1) < A_UNITS)
                              : (B_UNITS % NW == 0 || ((l - A_LOADS) * NW + NW - 1) < B_UNITS);
     }
-    static constexpr int allowance() {
+    static constexpr int common_loads() {   // load instructions of a slab request that every wave issues
         int full = 0;
         for (int l = 0; l < A_LOADS + B_LOADS; ++l)
             if (every_wave_issues(l))
                 ++full;
-        return (NS - 2) * full;
+        return full;
     }
     static constexpr int ACC = (MI == 32) ? 16 : 4;               // fp32 accumulators per MFMA tile
     static_assert(WTM % MI == 0 && WTN % MI == 0, "wave tile must be a multiple of the MFMA tile");
@@ -85,12 +85,14 @@ struct Tile {
     static_assert(RA % 16 == 0 && RB % 16 == 0, "rows must be whole 16-byte chunks");
     static_assert(NS >= 2 && NS * STAGE <= 160 * 1024, "the stage ring must fit the 160 KB LDS");
 
-    // A rows are K-contiguous; lanes of an MFMA operand read the same chunk column of
-    // consecutive rows, so the chunk index is XORed with a row key that makes 8 consecutive
-    // rows land on 8 different 16-byte bank groups.
-    static constexpr int A_ROWS_PER_128 = (RA >= 128) ? 1 : 128 / RA;
-    static constexpr int A_KEY_MASK = ((CA < 8) ? CA : 8) - 1;
-    __device__ static inline int a_key(int row) { return (row / A_ROWS_PER_128) & A_KEY_MASK; }
+    // A rows are K-contiguous; the lanes of an MFMA operand read the same chunk column of
+    // consecutive rows.  The LDS has 64 four-byte banks (256 bytes per clock) and serves a
+    // ds_read_b128 sixteen lanes at a time, so sixteen consecutive rows must land on sixteen
+    // different 16-byte slots of the 256-byte bank window: the chunk index is XORed with a key
+    // that counts 256-byte windows of rows.
+    static constexpr int A_ROWS_PER_WIN = (RA >= 256) ? 1 : 256 / RA;
+    static constexpr int A_KEY_MASK = ((CA < 16) ? CA : 16) - 1;
+    __device__ static inline int a_key(int row) { return (row / A_ROWS_PER_WIN) & A_KEY_MASK; }
     __device__ static inline int a_off(int row, int chunk) { return row * RA + ((chunk ^ a_key(row)) << 4); }
     // B rows are N-contiguous; a transpose read touches SEG bytes of each of several
     // consecutive k rows, so the SEG-sized block index inside a row is XORed with a key of k
@@ -305,40 +307,37 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     };
 
     // ---- pipeline: prologue, main K loop, epilogue (Algorithm 8's three phases) ----
-    // Ring of NS LDS stages: while slab kt is consumed, slabs kt+1 .. kt+NS-2 are landed or in
-    // flight and the request for slab kt+NS-1 goes into the stage that iteration kt-1 read.
-    // Before the barrier a wave waits until its own loads of slab kt+1 have landed (all but
-    // the newest NS-2 slabs' worth) and its LDS reads are done; the barrier sits before the
-    // last k-step's MFMAs, whose fragments are already in registers, so the first fragments of
-    // the next stage are fetched under those MFMAs.  Requests past the last slab are
-    // out-of-window loads: they move no data and keep the loop body branch-free.
-    //
+    // Ring of NS LDS stages; slab kt lives in stage kt % NS.  One barrier per slab, placed
+    // before the last k-step's MFMAs (whose fragments are already in registers).  It certifies
+    // two things at once: every wave has finished reading the current stage, and every wave's
+    // loads of slab kt+1 have landed (a wave waits for all but its newest NS-2 slab requests
+    // first).  Right after it the freed stage is refilled with slab kt+NS -- a request has NS-1
+    // whole iterations to land -- and the first fragments of the next stage are fetched under
+    // the last k-step's MFMAs.  Requests past the last slab are out-of-window loads: they move
+    // no data and keep the loop body branch-free.
     static_assert(T::KSTEPS % 2 == 0, "fragment double buffering needs an even number of k-steps");
-    // vmcnt allowance at the barrier of iteration kt: everything requested after slab kt+1 may
-    // still be in flight, i.e. slabs kt+2 .. kt+NS-1.  Only instructions that every wave issues
-    // are counted (ragged unit counts), so a wave never waits for less than it must.
-    constexpr int ALLOW = T::allowance();
-    static_assert(ALLOW <= 63, "vmcnt is a 6-bit counter");
+    // vmcnt allowance at the barrier of iteration kt: slabs kt+2 .. kt+NS-1 may still be in
+    // flight.  Only instructions that every wave issues are counted (ragged unit counts), so a
+    // wave never waits for less than it must.
+    constexpr int FULL = T::common_loads();
+    constexpr int ALLOW = (T::NS - 2) * FULL;
+    static_assert((T::NS - 1) * FULL <= 63, "vmcnt is a 6-bit counter");
     auto publish = [&]() { asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(ALLOW) : "memory"); };
 
     if (kt_count > 0) {
 #pragma unroll
-        for (int s = 0; s < T::NS - 1; ++s)
+        for (int s = 0; s < T::NS; ++s)
 #pragma unroll
             for (int l = 0; l < NL; ++l)
                 issue_one(l, s, s);
-        publish();
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((T::NS - 1) * FULL) : "memory");
 #pragma unroll
         for (int u = 0; u < NF; ++u)
             load_frag(0, 0, 0, u);
     }
     int stage = 0;                         // stage of slab kt
-    int fill = T::NS - 1;                  // stage that receives slab kt+NS-1
     for (int kt = 0; kt < kt_count; ++kt) {
         const int next = (stage + 1 == T::NS) ? 0 : stage + 1;
-#pragma unroll
-        for (int l = 0; l < NL; ++l)
-            issue_one(l, kt + T::NS - 1, fill);
 #pragma unroll
         for (int kstep = 0; kstep < T::KSTEPS - 1; ++kstep) {
 #pragma unroll
@@ -350,12 +349,14 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         }
         publish();
 #pragma unroll
+        for (int l = 0; l < NL; ++l)
+            issue_one(l, kt + T::NS, stage);
+#pragma unroll
         for (int u = 0; u < NF; ++u)
             load_frag(next, 0, 0, u);
 #pragma unroll
         for (int m = 0; m < T::TM * T::TN; ++m)
             mma_one((T::KSTEPS - 1) & 1, m / T::TM, m % T::TM);
-        fill = stage;
         stage = next;
     }
     // nothing may still be in flight towards LDS when the workgroup ends

@@ -59,10 +59,10 @@ static gemm_hw make_default_hw()
     h.reduce_launch_clk = 7200.0;
     h.under_occ_frac = 0.72;
     h.seg_eff_lo = 0.15;
-    h.l_mi_clk[GEMM_BF16][0] = 39.7;      // v_mfma_f32_32x32x16_bf16  (2030 TFLOP/s device-wide)
-    h.l_mi_clk[GEMM_BF16][1] = 31.8;      // v_mfma_f32_16x16x32_bf16  (1267 TFLOP/s)
-    h.l_mi_clk[GEMM_FP8_E4M3][0] = 69.4;  // v_mfma_f32_32x32x64_f8f6f4 (4642 TFLOP/s)
-    h.l_mi_clk[GEMM_FP8_E4M3][1] = 65.7;  // v_mfma_f32_16x16x128_f8f6f4 (4904 TFLOP/s)
+    h.l_mi_clk[GEMM_BF16][0] = 35.6;      // v_mfma_f32_32x32x16_bf16  (2259 TFLOP/s device-wide)
+    h.l_mi_clk[GEMM_BF16][1] = 27.8;      // v_mfma_f32_16x16x32_bf16  (1449 TFLOP/s)
+    h.l_mi_clk[GEMM_FP8_E4M3][0] = 65.0;  // v_mfma_f32_32x32x64_f8f6f4 (4953 TFLOP/s)
+    h.l_mi_clk[GEMM_FP8_E4M3][1] = 35.0;  // v_mfma_f32_16x16x128_f8f6f4 (4599 TFLOP/s)
     return h;
 }
 
