@@ -130,6 +130,50 @@ def main():
         g.gemm_select(big, big, big, g.GEMM_BF16)
     select_us = (time.perf_counter() - t1) / 200 * 1e6
 
+    # ---- secondary figures (outside the timed region above): per-shape rates, the fp8 and the
+    # bandwidth-bound paths, and the measured ceilings both rooflines are also quoted against
+    def timed_us(cfg, dA, dB, dC, reps=10):
+        need = g.gemm_workspace_bytes(cfg)
+        nonlocal ws
+        if need and (ws is None or ws.numel() * 4 < need):
+            ws = torch.empty(need // 4, dtype=torch.float32, device="cuda")
+            g.gemm_set_workspace(ws)
+        for _ in range(2):
+            g.gemm_run(cfg, dA, dB, dC)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.gemm_run(cfg, dA, dB, dC)
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
+    also = {}
+    for n in sizes:
+        us = timed_us(g.gemm_select(n, n, n, g.GEMM_BF16), *dev[n])
+        also["bf16_%d_tflops" % n] = 2.0 * n ** 3 / us * 1e-6
+    scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
+    also["mfma_only_bf16_tflops"] = g.gemm_probe_mfma(g.GEMM_BF16, 32, scratch)
+    n8 = 8192
+    Aq, Bq, sa, sb = wl.config4(n8)
+    cfg8 = g.gemm_select(n8, n8, n8, g.GEMM_FP8_E4M3)
+    cfg8.alpha = float(sa) * float(sb)
+    us = timed_us(cfg8, torch.from_numpy(Aq).cuda(), torch.from_numpy(Bq).cuda(), dev[n8][2])
+    also["fp8_8192"] = {"tflops": 2.0 * n8 ** 3 / us * 1e-6, "frac_of_fp8_peak": 2.0 * n8 ** 3 / us * 1e-6 / PEAK_TFLOPS["fp8"],
+                        "picked": cfg8.describe()}
+    del Aq, Bq
+    Ms, Ns, Ks = 16, 28672, 8192
+    As, Bs = wl.config3(Ms, Ns, Ks)
+    cfgs = g.gemm_select(Ms, Ns, Ks, g.GEMM_BF16)
+    dBs = torch.from_numpy(Bs.view(np.int16)).cuda()
+    us = timed_us(cfgs, torch.from_numpy(As.view(np.int16)).cuda(), dBs,
+                  torch.empty((Ms, Ns), dtype=torch.int16, device="cuda"))
+    sk_bytes = (Ms * Ks + Ks * Ns + Ms * Ns) * 2.0
+    also["skinny_bf16_M16_N28672_K8192"] = {"us": us, "gbps": sk_bytes / us * 1e-3,
+                                            "frac_of_hbm_peak": sk_bytes / us * 1e-3 / PEAK_HBM_GBPS,
+                                            "picked": cfgs.describe()}
+    also["hbm_stream_gbps"] = g.gemm_probe_stream(dBs, scratch)
+
     out = {
         "metric": "GEMM TFLOP/s (bf16 in, fp32 accumulate, bf16 out; analytic kernel selection included)",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -143,6 +187,7 @@ def main():
                      "frac": achieved / PEAK_TFLOPS["bf16"], "kernel": "gemm_kernel<%s> on 8192^3" % cfg_big.describe(),
                      "avg_launch_ms": kern_ms, "traffic": read_traffic("gemm_bf16_8192_counters.txt")},
     }
+    out["also"] = also
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(host[big][0], host[big][1], args.cpu_rows)
     print(json.dumps(out))
