@@ -7,7 +7,7 @@ latency of one loop iteration), Algorithm 8 (latency of one output tile) and Alg
 (total latency).  The `alg*` functions take the steps in the paper's order and notation,
 with no reading added.  `predict` composes them for one kernel variant the way the shipped
 selector is specified to (every place where the paper is silent or inconsistent is marked
-READING and listed in the design doc); the tests compare the C++ selector's terms with it.
+READING); the tests compare the C++ selector's terms with it.
 
 Shares no code with the product; nothing under the product package imports this module.
 The selector's final pick is a heuristic ranked empirically against a sweep, so beyond the

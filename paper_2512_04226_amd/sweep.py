@@ -5,7 +5,7 @@ gemm_cfg_at plus the analytical pick of gemm_select, and records the paper's sel
 efficiency (Section V-A): throughput of the pick divided by the best throughput found.
 Nothing here is used by gemm_select or gemm_run.
 
-    python -m paper_2512_04226_amd.sweep --set config5 --out gpurun_out/sweep_config5.jsonl
+    python -m paper_2512_04226_amd.sweep --set config5 --out sweep_config5.jsonl
 """
 import argparse
 import json
@@ -115,7 +115,7 @@ def shape_set(name):
 def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--set", default="config5")
-    ap.add_argument("--out", default="gpurun_out/sweep.jsonl")
+    ap.add_argument("--out", default="sweep.jsonl")
     ap.add_argument("--limit", type=int, default=0)
     ap.add_argument("--quick", action="store_true")
     ap.add_argument("--all-rows", action="store_true", help="also write every config's timing")
