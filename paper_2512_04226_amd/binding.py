@@ -14,7 +14,7 @@ import os
 import torch  # noqa: F401
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libgemm355.so")
+LIB_PATH = os.environ.get("GEMM355_LIB") or os.path.join(_PKG, "libgemm355.so")   # override: a differently built copy
 
 GEMM_BF16 = 0
 GEMM_FP8_E4M3 = 1
