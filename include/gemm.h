@@ -3,7 +3,9 @@
  *
  * Computes C = alpha * A * B (the paper's Section II-A definition with beta = 0):
  *   A  M x K, row-major, leading dimension lda (elements), bf16 or fp8 e4m3 (OCP "e4m3fn")
- *   B  K x N, row-major, leading dimension ldb
+ *   B  K x N, row-major, leading dimension ldb (GEMM_B_ROW_MAJOR, the default), or stored as its
+ *      transpose, N x K row-major, K-contiguous, ldb >= K (GEMM_B_K_CONTIGUOUS: the operand layout of
+ *      the paper's own runs, Section V, and of an nn.Linear weight)
  *   C  M x N, row-major, leading dimension ldc, bf16, rounded to nearest even from an
  *      fp32 accumulator.
  * A, B, C and the split-K workspace are DEVICE pointers owned by the caller; the library
@@ -33,6 +35,11 @@ typedef enum gemm_dtype {
     GEMM_BF16 = 0,     /* A, B bf16 */
     GEMM_FP8_E4M3 = 1  /* A, B one byte per element, OCP e4m3fn (max finite 448) */
 } gemm_dtype;
+
+typedef enum gemm_b_layout {
+    GEMM_B_ROW_MAJOR = 0,    /* B[k][n] at B + k*ldb + n */
+    GEMM_B_K_CONTIGUOUS = 1  /* B[k][n] at B + n*ldb + k */
+} gemm_b_layout;
 
 typedef enum gemm_status {
     GEMM_OK = 0,
@@ -98,7 +105,7 @@ typedef struct gemm_cfg {
     uint32_t abi_version;
     int32_t dtype;            /* gemm_dtype */
     int64_t M, N, K;
-    int64_t lda, ldb, ldc;    /* elements; gemm_select sets K, N, N */
+    int64_t lda, ldb, ldc;    /* elements; gemm_select sets K, N (K for K-contiguous B), N */
     int32_t kernel_id;        /* index into the compiled variant table */
     uint16_t block_m, block_n, block_k; /* workgroup tile M_T x N_T x K_T */
     uint8_t waves_m, waves_n; /* wave grid inside the workgroup */
@@ -110,6 +117,8 @@ typedef struct gemm_cfg {
     uint8_t xcd_remap;        /* 1: workgroup ids are renumbered so that each XCD owns a contiguous id range */
     uint8_t stages;           /* LDS ring depth: K_T slabs resident or in flight per workgroup */
     uint16_t slab_clk;        /* the variant's calibrated cost: clocks per K_T slab of one tile on a full CU */
+    uint8_t b_layout;         /* gemm_b_layout */
+    uint8_t reserved[3];
     float alpha;              /* default 1; the caller may overwrite it before gemm_run */
     int32_t bottleneck;       /* gemm_bottleneck of the prediction */
     double predicted_us;      /* model's total latency for this cfg */
@@ -149,6 +158,8 @@ const char *gemm_strerror(int status);
  * 16 (fp8) elements (else GEMM_ERR_ALIGN).
  */
 int gemm_select(int64_t M, int64_t N, int64_t K, int dtype, gemm_cfg *out);
+/* The same for a given storage of B (gemm_select is b_layout = GEMM_B_ROW_MAJOR). */
+int gemm_select_ex(int64_t M, int64_t N, int64_t K, int dtype, int b_layout, gemm_cfg *out);
 
 /*
  * Enqueue C = alpha * A * B on hip_stream (a hipStream_t; NULL = the default stream) with
@@ -171,6 +182,7 @@ int gemm_set_workspace(void *dev_ptr, size_t bytes);
  * variant idx cannot run the shape (e.g. more K slices than K slabs). */
 int gemm_cfg_count(int dtype);
 int gemm_cfg_at(int idx, int64_t M, int64_t N, int64_t K, int dtype, gemm_cfg *out);
+int gemm_cfg_at_ex(int idx, int64_t M, int64_t N, int64_t K, int dtype, int b_layout, gemm_cfg *out);
 
 /* Model terms for a cfg (Algorithms 3-9), host only. */
 int gemm_predict(const gemm_cfg *cfg, gemm_prediction *out);

@@ -131,10 +131,11 @@ def segment_efficiency(hw, seg):
     return min(1.0, hw["seg_eff_lo"] + (1.0 - hw["seg_eff_lo"]) * math.log2(s / 32.0) / 3.0)
 
 
-def predict(hw, dtype, M, N, K, v, split_k):
+def predict(hw, dtype, M, N, K, v, split_k, b_layout=0):
     """Model terms for variant v (dict: block_m/n/k, waves_m/n, mfma, stages, slab_clk) with the
-    reduction split split_k ways; hw is a dict of the hardware descriptor's fields.  Returns a
-    dict with the names of the C ABI's gemm_prediction plus group_m."""
+    reduction split split_k ways; hw is a dict of the hardware descriptor's fields; b_layout 0 =
+    B row-major K x N, 1 = B stored K-contiguous (then v["slab_clk"] is that layout's constant).
+    Returns a dict with the names of the C ABI's gemm_prediction plus group_m."""
     es = 2 if dtype == 0 else 1
     mi = v["mfma"]
     mi_k = {(0, 32): 16, (0, 16): 32, (1, 32): 64, (1, 16): 128}[(dtype, mi)]
@@ -184,14 +185,16 @@ def predict(hw, dtype, M, N, K, v, split_k):
         b_bytes = v["block_n"] * v["block_k"] * es * per_cu
         ld_cu = a_bytes + b_bytes
         l_issue = ld_cu / hw["vmem_bytes_per_clk"]
+        # READING: K-contiguous B is read with ds_read_b128 like A, row-major B with transpose reads
+        b_rate = hw["lds_bytes_per_clk"] if b_layout else hw["lds_tr_bytes_per_clk"]
         l_lds = (v["block_m"] * v["waves_n"] * v["block_k"] * es / hw["lds_bytes_per_clk"]
-                 + v["block_n"] * v["waves_m"] * v["block_k"] * es / hw["lds_tr_bytes_per_clk"]) * per_cu
+                 + v["block_n"] * v["waves_m"] * v["block_k"] * es / b_rate) * per_cu
         total = ld_cu * act
         xcds = min(hw["n_xcd"], max(1.0, act))
         l_l2 = (total / xcds) / hw["l2_bytes_per_clk"]
         l_mall = (1.0 - h1) * total / hw["mall_bytes_per_clk"]
         ea = segment_efficiency(hw, v["block_k"] * es)
-        eb = segment_efficiency(hw, v["block_n"] * es)
+        eb = segment_efficiency(hw, (v["block_k"] if b_layout else v["block_n"]) * es)
         t_m = (1.0 - h2) * (1.0 - h1) * (a_bytes / ea + b_bytes / eb) * act
         l_hbm = t_m / hw["hbm_bytes_per_clk"] + hw["mem_latency_clk"] / max(1.0, per_cu * (v["stages"] - 1))
         return dict(l_issue=l_issue, l_lds=l_lds, l_l2=l_l2, l_mall=l_mall, l_hbm=l_hbm,

@@ -19,6 +19,8 @@ LIB_PATH = os.environ.get("GEMM355_LIB") or os.path.join(_PKG, "libgemm355.so") 
 GEMM_BF16 = 0
 GEMM_FP8_E4M3 = 1
 GEMM_ABI_VERSION = 1
+GEMM_B_ROW_MAJOR = 0
+GEMM_B_K_CONTIGUOUS = 1
 
 STATUS = {0: "GEMM_OK", -1: "GEMM_ERR_NULL", -2: "GEMM_ERR_SHAPE", -3: "GEMM_ERR_DTYPE", -4: "GEMM_ERR_CFG_ILLEGAL",
           -5: "GEMM_ERR_ALIGN", -6: "GEMM_ERR_WORKSPACE", -7: "GEMM_ERR_ABI", -8: "GEMM_ERR_HIP", -9: "GEMM_ERR_INDEX"}
@@ -54,13 +56,13 @@ class gemm_cfg(ctypes.Structure):
                 ("waves_n", ctypes.c_uint8), ("mfma", ctypes.c_uint8), ("k_unroll", ctypes.c_uint8),
                 ("split_k", ctypes.c_uint16), ("group_m", ctypes.c_uint16), ("group_n", ctypes.c_uint16),
                 ("xcd_remap", ctypes.c_uint8), ("stages", ctypes.c_uint8),
-                ("slab_clk", ctypes.c_uint16), ("alpha", ctypes.c_float),
+                ("slab_clk", ctypes.c_uint16), ("b_layout", ctypes.c_uint8), ("reserved", ctypes.c_uint8 * 3), ("alpha", ctypes.c_float),
                 ("bottleneck", ctypes.c_int32), ("predicted_us", ctypes.c_double)]
 
     def describe(self):
-        return ("%dx%dx%d w%dx%d mfma%d s%d split%d g%d%s" % (
+        return ("%dx%dx%d w%dx%d mfma%d s%d split%d g%d%s%s" % (
             self.block_m, self.block_n, self.block_k, self.waves_m, self.waves_n, self.mfma, self.stages,
-            self.split_k, self.group_m, "" if self.xcd_remap else " noxcd"))
+            self.split_k, self.group_m, "" if self.xcd_remap else " noxcd", " Bkc" if self.b_layout else ""))
 
     def copy(self):
         c = gemm_cfg()
@@ -88,6 +90,10 @@ _lib.gemm_strerror.restype = ctypes.c_char_p
 _lib.gemm_strerror.argtypes = [_int]
 _lib.gemm_select.restype = _int
 _lib.gemm_select.argtypes = [_i64, _i64, _i64, _int, ctypes.POINTER(gemm_cfg)]
+_lib.gemm_select_ex.restype = _int
+_lib.gemm_select_ex.argtypes = [_i64, _i64, _i64, _int, _int, ctypes.POINTER(gemm_cfg)]
+_lib.gemm_cfg_at_ex.restype = _int
+_lib.gemm_cfg_at_ex.argtypes = [_int, _i64, _i64, _i64, _int, _int, ctypes.POINTER(gemm_cfg)]
 _lib.gemm_run.restype = _int
 _lib.gemm_run.argtypes = [ctypes.POINTER(gemm_cfg), _vp, _vp, _vp, _vp]
 _lib.gemm_workspace_bytes.restype = ctypes.c_size_t
@@ -152,6 +158,22 @@ def _check(rc, where):
 def gemm_select(M, N, K, dtype):
     cfg = gemm_cfg()
     _check(_lib.gemm_select(M, N, K, dtype, ctypes.byref(cfg)), "gemm_select")
+    return cfg
+
+
+def gemm_select_ex(M, N, K, dtype, b_layout):
+    cfg = gemm_cfg()
+    _check(_lib.gemm_select_ex(M, N, K, dtype, b_layout, ctypes.byref(cfg)), "gemm_select_ex")
+    return cfg
+
+
+def gemm_cfg_at_ex(idx, M, N, K, dtype, b_layout):
+    """Returns the cfg, or None when variant idx is not legal for the shape."""
+    cfg = gemm_cfg()
+    rc = _lib.gemm_cfg_at_ex(idx, M, N, K, dtype, b_layout, ctypes.byref(cfg))
+    if rc == -4:
+        return None
+    _check(rc, "gemm_cfg_at_ex")
     return cfg
 
 

@@ -54,8 +54,15 @@ int gemm_cfg_count(int dtype)
 
 int gemm_cfg_at(int idx, int64_t M, int64_t N, int64_t K, int dtype, gemm_cfg *out)
 {
+    return gemm_cfg_at_ex(idx, M, N, K, dtype, GEMM_B_ROW_MAJOR, out);
+}
+
+int gemm_cfg_at_ex(int idx, int64_t M, int64_t N, int64_t K, int dtype, int b_layout, gemm_cfg *out)
+{
     if (!out)
         return GEMM_ERR_NULL;
+    if (b_layout != GEMM_B_ROW_MAJOR && b_layout != GEMM_B_K_CONTIGUOUS)
+        return GEMM_ERR_CFG_ILLEGAL;
     const int rc = check_problem(M, N, K, dtype);
     if (rc)
         return rc;
@@ -65,14 +72,21 @@ int gemm_cfg_at(int idx, int64_t M, int64_t N, int64_t K, int dtype, gemm_cfg *o
     const gemm_hw &hw = hw_current();
     if (!variant_legal(hw, variant_at(dtype, id), dtype, M, N, K, split))
         return GEMM_ERR_CFG_ILLEGAL;
-    fill_cfg(hw, dtype, M, N, K, id, split, out);
+    fill_cfg(hw, dtype, b_layout, M, N, K, id, split, out);
     return GEMM_OK;
 }
 
 int gemm_select(int64_t M, int64_t N, int64_t K, int dtype, gemm_cfg *out)
 {
+    return gemm_select_ex(M, N, K, dtype, GEMM_B_ROW_MAJOR, out);
+}
+
+int gemm_select_ex(int64_t M, int64_t N, int64_t K, int dtype, int b_layout, gemm_cfg *out)
+{
     if (!out)
         return GEMM_ERR_NULL;
+    if (b_layout != GEMM_B_ROW_MAJOR && b_layout != GEMM_B_K_CONTIGUOUS)
+        return GEMM_ERR_CFG_ILLEGAL;
     const int rc = check_problem(M, N, K, dtype);
     if (rc)
         return rc;
@@ -87,7 +101,7 @@ int gemm_select(int64_t M, int64_t N, int64_t K, int dtype, gemm_cfg *out)
                 continue;
             gemm_prediction p;
             int gm, gn;
-            predict(hw, dtype, M, N, K, v, kSplitKs[s], &p, &gm, &gn);
+            predict(hw, dtype, b_layout, M, N, K, v, kSplitKs[s], &p, &gm, &gn);
             if (best_id < 0 || p.l_total < best) {
                 best = p.l_total;
                 best_id = id;
@@ -97,7 +111,7 @@ int gemm_select(int64_t M, int64_t N, int64_t K, int dtype, gemm_cfg *out)
     }
     if (best_id < 0)
         return GEMM_ERR_CFG_ILLEGAL;
-    fill_cfg(hw, dtype, M, N, K, best_id, best_split, out);
+    fill_cfg(hw, dtype, b_layout, M, N, K, best_id, best_split, out);
     return GEMM_OK;
 }
 
@@ -117,7 +131,9 @@ int gemm_predict(const gemm_cfg *cfg, gemm_prediction *out)
     if (!variant_legal(hw, v, cfg->dtype, cfg->M, cfg->N, cfg->K, cfg->split_k))
         return GEMM_ERR_CFG_ILLEGAL;
     int gm, gn;
-    predict(hw, cfg->dtype, cfg->M, cfg->N, cfg->K, v, cfg->split_k, out, &gm, &gn);
+    if (cfg->b_layout > 1)
+        return GEMM_ERR_CFG_ILLEGAL;
+    predict(hw, cfg->dtype, cfg->b_layout, cfg->M, cfg->N, cfg->K, v, cfg->split_k, out, &gm, &gn);
     return GEMM_OK;
 }
 

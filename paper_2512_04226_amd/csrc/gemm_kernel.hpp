@@ -2,8 +2,8 @@
 // CUs in space, the reduction dimension in time; inside a tile, waves across m and n and
 // MFMA k-steps in time).  One template covers the whole variant table.
 //
-//   A  M x K row-major, B  K x N row-major, C  M x N row-major bf16 (or fp32 partial slabs
-//   when the reduction is split across workgroups).
+//   A  M x K row-major, B  K x N row-major (or N x K row-major, K-contiguous), C  M x N
+//   row-major bf16 (or fp32 partial slabs when the reduction is split across workgroups).
 //
 // Data path per K slab: 128-bit buffer loads straight into LDS (A along K, B along N,
 // out-of-range chunks arrive as zero; no register staging) -> swizzled LDS ring of NS
@@ -46,9 +46,11 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define G355_LDS __attribute__((address_space(3)))
 
-template <int ES_, int BM_, int BN_, int BK_, int WM_, int WN_, int MI_, int NS_>
+// BL_: storage of B.  0: K x N row-major (N-contiguous).  1: N x K row-major (K-contiguous, the
+// layout of the paper's own runs, Section V): B is then staged and read exactly like A.
+template <int ES_, int BM_, int BN_, int BK_, int WM_, int WN_, int MI_, int NS_, int BL_>
 struct Tile {
-    static constexpr int ES = ES_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MI = MI_, NS = NS_;
+    static constexpr int ES = ES_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MI = MI_, NS = NS_, BL = BL_;
     static constexpr int NW = WM * WN;
     static constexpr int NT = WM * WN * 64;
     static constexpr int WTM = BM / WM, WTN = BN / WN;      // wave tile
@@ -58,8 +60,8 @@ struct Tile {
     static constexpr int KL = KI / KG;                      // k elements held by one lane
     static constexpr int KSTEPS = BK / KI;
     static constexpr int RA = BK * ES;                      // bytes per A row in LDS
-    static constexpr int RB = BN * ES;                      // bytes per B row in LDS
-    static constexpr int A_BYTES = BM * RA, B_BYTES = BK * RB;
+    static constexpr int RB = (BL == 0) ? BN * ES : BK * ES; // bytes per B row in LDS (a k row, or an n row when K-contiguous)
+    static constexpr int A_BYTES = BM * RA, B_BYTES = BK * BN * ES;
     static constexpr int STAGE = A_BYTES + B_BYTES;
     static constexpr int ACH = A_BYTES / 16, BCH = B_BYTES / 16;  // 16-byte chunks per slab
     static constexpr int CA = RA / 16, CB = RB / 16;              // chunks per row
@@ -181,14 +183,18 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     // outside the buffer window and arrive as zero; chunk columns past the edge (A: k >= k_len,
     // B: n >= N) are sent outside the window by replacing the offset.
     const uint8_t *Abase = (const uint8_t *)args.A + ((size_t)m0 * args.lda + k_begin) * ES;
-    const uint8_t *Bbase = (const uint8_t *)args.B + ((size_t)k_begin * args.ldb + n0) * ES;
+    const uint8_t *Bbase = (T::BL == 0) ? (const uint8_t *)args.B + ((size_t)k_begin * args.ldb + n0) * ES
+                                        : (const uint8_t *)args.B + ((size_t)n0 * args.ldb + k_begin) * ES;
     const int a_rows_valid = (args.M - m0 < BM) ? (args.M - m0) : BM;
+    const int b_rows_valid = (args.N - n0 < BN) ? (args.N - n0) : BN;      // K-contiguous B only
     const __amdgpu_buffer_rsrc_t rsA =
         make_rsrc(Abase, (unsigned)((a_rows_valid - 1) * args.lda + k_len) * ES);
-    const __amdgpu_buffer_rsrc_t rsB = make_rsrc(Bbase, (unsigned)(k_len * args.ldb) * ES);
+    const __amdgpu_buffer_rsrc_t rsB =
+        make_rsrc(Bbase, (T::BL == 0) ? (unsigned)(k_len * args.ldb) * ES
+                                      : (unsigned)((b_rows_valid - 1) * args.ldb + k_len) * ES);
 
     unsigned a_voff[T::A_LOADS], b_voff[T::B_LOADS];
-    int a_kcol[T::A_LOADS];
+    int a_kcol[T::A_LOADS], b_kcol[T::B_LOADS];
 #pragma unroll
     for (int i = 0; i < T::A_LOADS; ++i) {
         const int c = (i * T::NW + wave) * 64 + lane;
@@ -200,9 +206,16 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     for (int i = 0; i < T::B_LOADS; ++i) {
         const int c = (i * T::NW + wave) * 64 + lane;
         const int row = c / T::CB;
-        const int lbyte = ((c % T::CB) * 16) ^ (T::b_key(row) << T::SEG_BITS);
-        const bool ok = n0 + lbyte / ES < args.N;
-        b_voff[i] = ok ? (unsigned)(row * args.ldb * ES + lbyte) : OOB_OFFSET;
+        if constexpr (T::BL == 0) {
+            const int lbyte = ((c % T::CB) * 16) ^ (T::b_key(row) << T::SEG_BITS);
+            const bool ok = n0 + lbyte / ES < args.N;
+            b_voff[i] = ok ? (unsigned)(row * args.ldb * ES + lbyte) : OOB_OFFSET;
+            b_kcol[i] = 0;
+        } else {
+            const int lch = (c % T::CB) ^ T::a_key(row);      // same row bytes as A: same key
+            b_kcol[i] = lch * (16 / ES);
+            b_voff[i] = (unsigned)(row * args.ldb * ES + lch * 16);
+        }
     }
     // Load instruction l of a slab request (A units first, then B units): asynchronous,
     // completion is counted by vmcnt.
@@ -218,7 +231,11 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         } else {
             const int i = l - T::A_LOADS, u = i * T::NW + wave;
             if (T::B_UNITS % T::NW == 0 || u < T::B_UNITS) {
-                const unsigned off = b_voff[i] + (unsigned)kk * (unsigned)(args.ldb * ES);
+                unsigned off;
+                if constexpr (T::BL == 0)
+                    off = b_voff[i] + (unsigned)kk * (unsigned)(args.ldb * ES);
+                else
+                    off = (b_kcol[i] + kk < k_len) ? b_voff[i] + (unsigned)(kk * ES) : OOB_OFFSET;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (G355_LDS void *)(sbase + T::A_BYTES + u * 1024), 16, off,
                                                          0, 0, 0);
             }
@@ -239,6 +256,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     constexpr int TRK = 16 / LPR;                   // k rows covered by one transpose read (4 or 8)
     const int b_krow_l = b_kg * T::KL + i16 / LPR;
     const int b_ncol = wn * T::WTN + b_nhalf * 16 + (i16 % LPR) * (8 / ES);   // element column
+    const int bk_row = wn * T::WTN + (lane % MI);   // K-contiguous B: the lane's n row, k group a_kg
 
     typedef typename std::conditional<MI == 32, f32x16, f32x4>::type acc_t;
     acc_t acc[T::TN][T::TM];
@@ -274,7 +292,15 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             }
         } else {
             const int j = u - T::TM;
-            if constexpr (ES == 2) {
+            if constexpr (T::BL == 1 && ES == 2) {
+                const int chunk = (k0 + a_kg * T::KL) / 8;
+                bfr[buf][j] = *(const bf16x8 *)(sB + T::a_off(bk_row + j * MI, chunk));
+            } else if constexpr (T::BL == 1) {
+                const int chunk = (k0 + a_kg * T::KL) / 16;
+                i32x4 lo = *(const i32x4 *)(sB + T::a_off(bk_row + j * MI, chunk));
+                i32x4 hi = *(const i32x4 *)(sB + T::a_off(bk_row + j * MI, chunk + 1));
+                bfr[buf][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            } else if constexpr (ES == 2) {
                 short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                     (G355_LDS short4_t *)(sB + T::b_off(k0 + b_krow_l, (b_ncol + j * MI) * 2)));
                 short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(

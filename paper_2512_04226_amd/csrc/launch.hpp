@@ -5,5 +5,7 @@
 
 namespace g355 {
 typedef hipError_t (*LaunchFn)(const KernelArgs &, hipStream_t);
-LaunchFn kLaunchBf16_0(int), kLaunchBf16_1(int), kLaunchBf16_2(int), kLaunchBf16_3(int), kLaunchFp8_0(int), kLaunchFp8_1(int);
+// (variant index inside the translation unit's list, storage of B: 0 row-major K x N, 1 K-contiguous N x K)
+LaunchFn kLaunchBf16_0(int, int), kLaunchBf16_1(int, int), kLaunchBf16_2(int, int), kLaunchBf16_3(int, int),
+    kLaunchFp8_0(int, int), kLaunchFp8_1(int, int);
 }  // namespace g355

@@ -16,7 +16,7 @@
 
 namespace g355 {
 
-#define G355_X(bm, bn, bk, wm, wn, mi, ns, tau) {bm, bn, bk, wm, wn, mi, ns, tau},
+#define G355_X(bm, bn, bk, wm, wn, mi, ns, tau) {bm, bn, bk, wm, wn, mi, ns, tau, tau},
 static const Variant kVariantsBf16[] = {G355_VARIANTS_BF16(G355_X)};
 static const Variant kVariantsFp8[] = {G355_VARIANTS_FP8(G355_X)};
 #undef G355_X
@@ -202,17 +202,19 @@ static double segment_efficiency(const gemm_hw &hw, double seg)
 // Algorithm 7 for one K iteration.  `per_cu` = tiles a CU works on at once, `active` = CUs
 // busy.  Terms: per-CU vector-memory issue, LDS fragment reads (the software-managed-memory
 // bound of Section IV-D, which the printed algorithm leaves out), L2 (per XCD), MALL and HBM.
-static MemTerms memory_latency(const gemm_hw &hw, const Variant &v, int es, double per_cu, double active, double h1,
-                               double h2)
+static MemTerms memory_latency(const gemm_hw &hw, const Variant &v, int es, int b_layout, double per_cu, double active,
+                               double h1, double h2)
 {
     MemTerms t;
     const double a_bytes = (double)v.block_m * v.block_k * es * per_cu;   // per CU and iteration
     const double b_bytes = (double)v.block_n * v.block_k * es * per_cu;
     const double ld_cu = a_bytes + b_bytes;
     t.l_issue = ld_cu / hw.vmem_bytes_per_clk;
-    // every wave reads its A rows (ds_read_b128) and its B columns (transpose reads) of the slab
+    // every wave reads its A rows (ds_read_b128) and its B columns (transpose reads, or
+    // ds_read_b128 when B is K-contiguous) of the slab
+    const double b_lds_rate = b_layout ? hw.lds_bytes_per_clk : hw.lds_tr_bytes_per_clk;
     t.l_lds = ((double)v.block_m * v.waves_n * v.block_k * es / hw.lds_bytes_per_clk +
-               (double)v.block_n * v.waves_m * v.block_k * es / hw.lds_tr_bytes_per_clk) *
+               (double)v.block_n * v.waves_m * v.block_k * es / b_lds_rate) *
               per_cu;
     const double xcds_busy = std::min<double>(hw.n_xcd, std::max(1.0, active));   // round-robin dispatch
     const double total = ld_cu * active;
@@ -220,7 +222,7 @@ static MemTerms memory_latency(const gemm_hw &hw, const Variant &v, int es, doub
     t.l_mall = (1.0 - h1) * total / hw.mall_bytes_per_clk;
     // what misses both caches, inflated by the row-segment efficiency of each operand
     const double ea = segment_efficiency(hw, (double)v.block_k * es);
-    const double eb = segment_efficiency(hw, (double)v.block_n * es);
+    const double eb = segment_efficiency(hw, (double)(b_layout ? v.block_k : v.block_n) * es);
     const double tm = (1.0 - h2) * (1.0 - h1) * (a_bytes / ea + b_bytes / eb) * active;
     t.l_hbm = tm / hw.hbm_bytes_per_clk + hw.mem_latency_clk / std::max(1.0, per_cu * (v.stages - 1));
     t.l_mem = std::max(std::max(t.l_issue, t.l_lds), std::max(std::max(t.l_l2, t.l_mall), t.l_hbm));
@@ -244,7 +246,7 @@ static int label_of(const MemTerms &t, double l_comp, bool under, double fixed, 
     return GEMM_BOUND_LS_ISSUE;
 }
 
-void predict(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, const Variant &v, int split_k,
+void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, int64_t K, const Variant &v, int split_k,
              gemm_prediction *p, int *group_m, int *group_n)
 {
     std::memset(p, 0, sizeof(*p));
@@ -301,10 +303,10 @@ void predict(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, cons
     auto tile_latency = [&](double per_cu, double act, MemTerms *mt_out, double *l_comp_out, double *pro, double *epi,
                             double *iter) {
         // per_cu tiles share the CU; fewer than fit run a little faster each, but not in proportion
-        double l_comp = (double)v.slab_clk * per_cu;
+        double l_comp = (double)(b_layout ? v.slab_clk_kc : v.slab_clk) * per_cu;
         if (per_cu < occ)
             l_comp *= hw.under_occ_frac + (1.0 - hw.under_occ_frac) * per_cu / occ;
-        const MemTerms mt = memory_latency(hw, v, es, per_cu, act, h1, h2);
+        const MemTerms mt = memory_latency(hw, v, es, b_layout, per_cu, act, h1, h2);
         const double l_pro = mt.l_mem + hw.mem_latency_clk + hw.wg_overhead_clk;
         // the store stage scales with the output tile only; results leave through HBM
         const double l_epi = act * per_cu * v.block_m * v.block_n * out_bytes / hw.hbm_bytes_per_clk + hw.epilogue_clk;
@@ -354,12 +356,13 @@ void predict(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, cons
     p->bottleneck = label_of(mt, p->l_compute, active < hw.n_cu && waves == 1.0, fixed, p->l_total - fixed);
 }
 
-void fill_cfg(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, int kernel_id, int split_k, gemm_cfg *c)
+void fill_cfg(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, int64_t K, int kernel_id, int split_k,
+              gemm_cfg *c)
 {
     const Variant &v = variant_at(dtype, kernel_id);
     gemm_prediction p;
     int gm, gn;
-    predict(hw, dtype, M, N, K, v, split_k, &p, &gm, &gn);
+    predict(hw, dtype, b_layout, M, N, K, v, split_k, &p, &gm, &gn);
     std::memset(c, 0, sizeof(*c));
     c->abi_version = GEMM_ABI_VERSION;
     c->dtype = dtype;
@@ -367,7 +370,7 @@ void fill_cfg(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, int
     c->N = N;
     c->K = K;
     c->lda = K;
-    c->ldb = N;
+    c->ldb = b_layout ? K : N;
     c->ldc = N;
     c->kernel_id = kernel_id;
     c->block_m = (uint16_t)v.block_m;
@@ -382,7 +385,8 @@ void fill_cfg(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, int
     c->group_n = (uint16_t)gn;
     c->xcd_remap = 1;
     c->stages = (uint8_t)v.stages;
-    c->slab_clk = (uint16_t)v.slab_clk;
+    c->slab_clk = (uint16_t)(b_layout ? v.slab_clk_kc : v.slab_clk);
+    c->b_layout = (uint8_t)b_layout;
     c->alpha = 1.0f;
     c->bottleneck = p.bottleneck;
     c->predicted_us = p.total_us;

@@ -14,9 +14,10 @@ int elem_bytes(int dtype);
 int mfma_k(int dtype, int mfma);
 int64_t k_per_split(const Variant &v, int64_t K, int split_k);
 bool variant_legal(const gemm_hw &hw, const Variant &v, int dtype, int64_t M, int64_t N, int64_t K, int split_k);
-void predict(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, const Variant &v, int split_k,
+void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, int64_t K, const Variant &v, int split_k,
              gemm_prediction *p, int *group_m, int *group_n);
-void fill_cfg(const gemm_hw &hw, int dtype, int64_t M, int64_t N, int64_t K, int kernel_id, int split_k, gemm_cfg *c);
+void fill_cfg(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, int64_t K, int kernel_id, int split_k,
+              gemm_cfg *c);
 // 0 or a gemm_status for the shape / dtype / alignment rules shared by select, cfg_at and run
 int check_problem(int64_t M, int64_t N, int64_t K, int dtype);
 }  // namespace g355

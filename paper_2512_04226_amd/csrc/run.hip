@@ -41,7 +41,7 @@ struct Workspace {
 };
 Workspace g_ws[kMaxDevices];
 
-LaunchFn launcher_of(int dtype, int id)
+LaunchFn launcher_of(int dtype, int id, int bl)
 {
 #define G355_COUNT(...) +1
     constexpr int n_b0 = 0 G355_VARIANTS_BF16_0(G355_COUNT);
@@ -51,16 +51,16 @@ LaunchFn launcher_of(int dtype, int id)
 #undef G355_COUNT
     if (dtype == GEMM_BF16) {
         if (id < n_b0)
-            return kLaunchBf16_0(id);
+            return kLaunchBf16_0(id, bl);
         if (id < n_b0 + n_b1)
-            return kLaunchBf16_1(id - n_b0);
+            return kLaunchBf16_1(id - n_b0, bl);
         if (id < n_b0 + n_b1 + n_b2)
-            return kLaunchBf16_2(id - n_b0 - n_b1);
-        return kLaunchBf16_3(id - n_b0 - n_b1 - n_b2);
+            return kLaunchBf16_2(id - n_b0 - n_b1, bl);
+        return kLaunchBf16_3(id - n_b0 - n_b1 - n_b2, bl);
     }
     if (id < n_f0)
-        return kLaunchFp8_0(id);
-    return kLaunchFp8_1(id - n_f0);
+        return kLaunchFp8_0(id, bl);
+    return kLaunchFp8_1(id - n_f0, bl);
 }
 
 inline int64_t cdiv64(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -103,7 +103,9 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
         return GEMM_ERR_CFG_ILLEGAL;
     if (cfg->split_k < 1 || cfg->group_m < 1 || !variant_legal(hw, v, dtype, cfg->M, cfg->N, cfg->K, cfg->split_k))
         return GEMM_ERR_CFG_ILLEGAL;
-    if (cfg->lda < cfg->K || cfg->ldb < cfg->N || cfg->ldc < cfg->N)
+    if (cfg->b_layout > 1)
+        return GEMM_ERR_CFG_ILLEGAL;
+    if (cfg->lda < cfg->K || cfg->ldb < (cfg->b_layout ? cfg->K : cfg->N) || cfg->ldc < cfg->N)
         return GEMM_ERR_SHAPE;
     const int per16 = 16 / es;
     if (((uintptr_t)A & 15) || ((uintptr_t)B & 15) || ((uintptr_t)C & 15) || cfg->lda % per16 || cfg->ldb % per16 ||
@@ -113,7 +115,9 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
     const int64_t tiles_m = cdiv64(cfg->M, v.block_m), tiles_n = cdiv64(cfg->N, v.block_n);
     // the kernel addresses a tile's operands with 32-bit byte offsets below 2 GiB
     const int64_t lim = (int64_t)1 << 31;
-    if ((int64_t)v.block_m * cfg->lda * es >= lim || (kps + (int64_t)v.stages * v.block_k) * cfg->ldb * es >= lim ||
+    const int64_t b_window = cfg->b_layout ? (int64_t)v.block_n * cfg->ldb * es
+                                           : (kps + (int64_t)v.stages * v.block_k) * cfg->ldb * es;
+    if ((int64_t)v.block_m * cfg->lda * es >= lim || b_window >= lim ||
         tiles_m * tiles_n * cfg->split_k >= lim || cfg->M * cfg->N >= ((int64_t)1 << 40))
         return GEMM_ERR_SHAPE;
 
@@ -150,7 +154,7 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
     a.n_xcd = hw.n_xcd;
 
     hipStream_t stream = (hipStream_t)hip_stream;
-    if (launcher_of(dtype, cfg->kernel_id)(a, stream) != hipSuccess) {
+    if (launcher_of(dtype, cfg->kernel_id, cfg->b_layout)(a, stream) != hipSuccess) {
         (void)hipGetLastError();
         return GEMM_ERR_HIP;
     }

@@ -77,7 +77,9 @@
 
 namespace g355 {
 struct Variant {
-    int block_m, block_n, block_k, waves_m, waves_n, mfma, stages, slab_clk;
+    int block_m, block_n, block_k, waves_m, waves_n, mfma, stages;
+    int slab_clk;     // B row-major
+    int slab_clk_kc;  // B K-contiguous
 };
 // Spatial K-unroll factors offered with every variant.
 constexpr int kSplitKs[] = {1, 2, 4, 8, 16, 32};

@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_struct_sizes_match_header_layout():
     # gemm_cfg: 4+4 + 6*8 + 4 + 3*2 + 4*1 + 3*2 + 1+1+2 + 4 + 4 (+pad) + 8
-    assert ctypes.sizeof(g.gemm_cfg) == 96
+    assert ctypes.sizeof(g.gemm_cfg) == 104
     assert ctypes.sizeof(g.gemm_prediction) == 26 * 8 + 8
     assert ctypes.sizeof(g.gemm_hw) == 16 + 18 * 8 + 4 * 8
 

@@ -203,3 +203,57 @@ def test_runs_on_a_side_stream(g, oracle):
     g.gemm_run(cfg, dA, dB, dC, stream=s)
     s.synchronize()
     assert np.array_equal(dC.cpu().numpy().view(np.uint16), ref16)
+
+
+# ---------------- B stored K-contiguous (N x K row-major): the paper's operand layout ----------------
+
+@pytest.mark.parametrize("shape", [(200, 264, 328), (512, 512, 512), (1, 8, 8), (33, 1000, 72)])
+def test_k_contiguous_b_every_variant_bit_exact(g, oracle, shape):
+    from gpu_util import run_cfg, to_dev
+    M, N, K = shape
+    A, B = wl.integer_bf16(M, N, K, seed=21, case=M + K)
+    ref16, _ = oracle.gemm(A, B, BF16)                   # the oracle always takes B as K x N
+    dA, dBt = to_dev(A), to_dev(np.ascontiguousarray(B.T))
+    n_run = 0
+    for idx in range(g.gemm_cfg_count(BF16)):
+        c = g.gemm_cfg_at_ex(idx, M, N, K, BF16, g.GEMM_B_K_CONTIGUOUS)
+        if c is None:
+            continue
+        out = run_cfg(c, dA, dBt, M, N)
+        assert np.array_equal(out, ref16), (c.describe(), int((out != ref16).sum()))
+        n_run += 1
+    assert n_run >= 30
+
+
+def test_k_contiguous_b_fp8_and_padded_ldb(g, oracle):
+    from gpu_util import run_cfg, to_dev
+    M, N, K = 200, 272, 336
+    gen = np.random.default_rng(4)
+    vals = np.array([0, 1, 2, 3, 4, -1, -2, -3, -4], dtype=np.float64)
+    A = oracle.encode_e4m3(vals[gen.integers(0, 9, size=(M, K))])
+    B = oracle.encode_e4m3(vals[gen.integers(0, 9, size=(K, N))])
+    ref16, _ = oracle.gemm(A, B, E4M3, alpha=0.25)
+    ldb = K + 48
+    Bt = np.full((N, ldb), 0x7F, np.uint8)               # NaN codes in the padding
+    Bt[:, :K] = B.T
+    dA, dBt = to_dev(A), to_dev(Bt)
+    for idx in range(g.gemm_cfg_count(E4M3)):
+        c = g.gemm_cfg_at_ex(idx, M, N, K, E4M3, g.GEMM_B_K_CONTIGUOUS)
+        if c is None:
+            continue
+        c.ldb = ldb
+        out = run_cfg(c, dA, dBt, M, N, alpha=0.25)
+        assert np.array_equal(out, ref16), (c.describe(), int((out != ref16).sum()))
+
+
+def test_k_contiguous_b_square_4096(g, oracle):
+    n = 4096
+    A, B = wl.config2(n)
+    cfg = g.gemm_select_ex(n, n, n, BF16, g.GEMM_B_K_CONTIGUOUS)
+    from gpu_util import bf16_to_f64, run_cfg, to_dev
+    out = run_cfg(cfg, to_dev(A), to_dev(np.ascontiguousarray(B.T)), n, n)
+    rows = _rows_to_check(n, cfg.block_m)
+    _, ref64 = oracle.gemm_rows(A, B, rows, BF16)
+    max_a = float(np.abs(wl.bf16_bits_to_f32(A)).max())
+    max_b = float(np.abs(wl.bf16_bits_to_f32(B)).max())
+    assert np.max(np.abs(bf16_to_f64(out[rows]) - ref64)) <= oracle.tolerance(n, max_a, max_b, BF16)

@@ -122,8 +122,9 @@ SHAPES = [(512, 512, 512), (4096, 4096, 4096), (8192, 8192, 8192), (1, 28672, 81
           (256, 28672, 8192), (64, 64, 16384), (1808, 7344, 272), (11296, 64, 13504), (300, 520, 72), (16384, 16384, 64)]
 
 
+@pytest.mark.parametrize("b_layout", [0, 1])
 @pytest.mark.parametrize("dtype", [0, 1])
-def test_shipped_model_terms_match_the_oracle(dtype):
+def test_shipped_model_terms_match_the_oracle(dtype, b_layout):
     from paper_2512_04226_amd import binding as g
     hw = _hw_dict(g)
     fields = ["n_mi", "l_mt_ideal", "l_compute", "tiles", "waves", "active_cu", "f_m", "f_n", "h_l2", "h_mall",
@@ -134,11 +135,12 @@ def test_shipped_model_terms_match_the_oracle(dtype):
         if dtype == 1 and (N % 16 or K % 16):
             continue
         for idx in range(g.gemm_cfg_count(dtype)):
-            c = g.gemm_cfg_at(idx, M, N, K, dtype)
+            c = g.gemm_cfg_at_ex(idx, M, N, K, dtype, b_layout)
             if c is None:
                 continue
+            assert c.b_layout == b_layout and c.ldb == (K if b_layout else N)
             p = g.gemm_predict(c)
-            o = sm.predict(hw, dtype, M, N, K, _variant_dict(c), c.split_k)
+            o = sm.predict(hw, dtype, M, N, K, _variant_dict(c), c.split_k, b_layout)
             for f in fields:
                 assert getattr(p, f) == pytest.approx(o[f], rel=1e-9, abs=1e-9), (M, N, K, c.describe(), f)
             assert c.group_m == o["group_m"] and c.predicted_us == pytest.approx(o["total_us"], rel=1e-9)
