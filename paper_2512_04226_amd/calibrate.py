@@ -5,7 +5,8 @@ gemm_select or gemm_run):
   * SLAB_CLK of every kernel variant: steady-state clocks per K slab of one tile on a full CU,
     from one large compute-bound problem per datatype (8192^3).
 
-Prints the hardware lines and the variants.hpp rows with the measured last column.
+Prints the hardware lines and the variants.hpp rows with the two measured columns (B row-major,
+B K-contiguous).
 
     python -m paper_2512_04226_amd.calibrate [--n 8192]
 """
@@ -33,7 +34,7 @@ def measure_rates():
     return out
 
 
-def measure_slab_clk(dtype, n):
+def measure_slab_clk(dtype, n, b_layout=0):
     hw = g.gemm_hw_get()
     A, B, C = make_operands(n, n, n, dtype)
     ws = Workspace()
@@ -41,7 +42,7 @@ def measure_slab_clk(dtype, n):
     count = g.gemm_cfg_count(dtype)
     seen = set()
     for idx in range(count):
-        cfg = g.gemm_cfg_at(idx, n, n, n, dtype)
+        cfg = g.gemm_cfg_at_ex(idx, n, n, n, dtype, b_layout)
         if cfg is None or cfg.split_k != 1 or cfg.kernel_id in seen:
             continue
         seen.add(cfg.kernel_id)
@@ -67,10 +68,12 @@ def main():
                 print("MFMA %s %dx%d: %.0f TFLOP/s device-wide -> L_MI = %.1f clk" % (key[0], key[1], key[1], val[0], val[1]))
     for dtype, name in ((g.GEMM_BF16, "BF16"), (g.GEMM_FP8_E4M3, "FP8")):
         print("// %s variants, SLAB_CLK measured on %d^3" % (name, args.n))
-        for cfg, us, tau in measure_slab_clk(dtype, args.n):
-            print("    X(%d, %d, %d, %d, %d, %d, %d, %d)   // %.1f us, %.0f TFLOP/s" % (
-                cfg.block_m, cfg.block_n, cfg.block_k, cfg.waves_m, cfg.waves_n, cfg.mfma, cfg.stages, round(tau), us,
-                2.0 * args.n ** 3 / us * 1e-6), flush=True)
+        rows = measure_slab_clk(dtype, args.n, 0)
+        rows_kc = measure_slab_clk(dtype, args.n, 1)
+        for (cfg, us, tau), (_, us_kc, tau_kc) in zip(rows, rows_kc):
+            print("    X(%d, %d, %d, %d, %d, %d, %d, %d, %d)   // %.1f us %.0f TFLOP/s | K-contiguous B %.1f us %.0f TFLOP/s" % (
+                cfg.block_m, cfg.block_n, cfg.block_k, cfg.waves_m, cfg.waves_n, cfg.mfma, cfg.stages, round(tau),
+                round(tau_kc), us, 2.0 * args.n ** 3 / us * 1e-6, us_kc, 2.0 * args.n ** 3 / us_kc * 1e-6), flush=True)
 
 
 if __name__ == "__main__":
