@@ -152,6 +152,13 @@ def main():
     for n in sizes:
         us = timed_us(g.gemm_select(n, n, n, g.GEMM_BF16), *dev[n])
         also["bf16_%d_tflops" % n] = 2.0 * n ** 3 / us * 1e-6
+    # the paper's own operand layout (both operands K-contiguous, Section V): same product, B stored N x K
+    n_big = sizes[-1]
+    dBt = dev[n_big][1].t().contiguous()
+    cfg_kc = g.gemm_select_ex(n_big, n_big, n_big, g.GEMM_BF16, g.GEMM_B_K_CONTIGUOUS)
+    us = timed_us(cfg_kc, dev[n_big][0], dBt, dev[n_big][2])
+    also["bf16_%d_b_k_contiguous" % n_big] = {"tflops": 2.0 * n_big ** 3 / us * 1e-6, "picked": cfg_kc.describe()}
+    del dBt
     scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
     also["mfma_only_bf16_tflops"] = g.gemm_probe_mfma(g.GEMM_BF16, 32, scratch)
     n8 = 8192

@@ -75,24 +75,24 @@ def time_cfg(cfg, A, B, C, ws, min_ms=1.0, max_iters=200, repeats=3):
     return float(np.median(times))
 
 
-def sweep_shape(M, N, K, dtype, ws, quick=False):
+def sweep_shape(M, N, K, dtype, ws, quick=False, b_layout=0):
     A, B, C = make_operands(M, N, K, dtype)
     flops = 2.0 * M * N * K
     rows = []
     for idx in range(g.gemm_cfg_count(dtype)):
-        cfg = g.gemm_cfg_at(idx, M, N, K, dtype)
+        cfg = g.gemm_cfg_at_ex(idx, M, N, K, dtype, b_layout)
         if cfg is None:
             continue
         us = time_cfg(cfg, A, B, C, ws, min_ms=0.5 if quick else 1.0)
         rows.append({"idx": idx, "cfg": cfg.describe(), "us": us, "pred_us": cfg.predicted_us})
-    pick = g.gemm_select(M, N, K, dtype)
+    pick = g.gemm_select_ex(M, N, K, dtype, b_layout)
     pick_us = time_cfg(pick, A, B, C, ws)
     best = min(rows, key=lambda r: r["us"])
     # the pick is one of the swept configs; use the better of its two timings against noise
     same = [r for r in rows if r["cfg"] == pick.describe()]
     if same:
         pick_us = min(pick_us, same[0]["us"])
-    rec = {"M": M, "N": N, "K": K, "dtype": dtype, "n_cfgs": len(rows), "best": best, "pick": pick.describe(),
+    rec = {"M": M, "N": N, "K": K, "dtype": dtype, "b_layout": b_layout, "n_cfgs": len(rows), "best": best, "pick": pick.describe(),
            "pick_us": pick_us, "pick_pred_us": pick.predicted_us, "efficiency": best["us"] / pick_us,
            "best_tflops": flops / best["us"] * 1e-6, "pick_tflops": flops / pick_us * 1e-6,
            "bottleneck": g.BOTTLENECKS[pick.bottleneck],
@@ -118,6 +118,7 @@ def main(argv=None):
     ap.add_argument("--out", default="sweep.jsonl")
     ap.add_argument("--limit", type=int, default=0)
     ap.add_argument("--quick", action="store_true")
+    ap.add_argument("--b-layout", type=int, default=0, help="0: B row-major K x N, 1: B stored K-contiguous (N x K)")
     ap.add_argument("--all-rows", action="store_true", help="also write every config's timing")
     args = ap.parse_args(argv)
     shapes = shape_set(args.set)
@@ -128,7 +129,8 @@ def main(argv=None):
         for line in open(args.out):
             try:
                 r = json.loads(line)
-                done.add((r["M"], r["N"], r["K"], r["dtype"]))
+                if r.get("b_layout", 0) == args.b_layout:
+                    done.add((r["M"], r["N"], r["K"], r["dtype"]))
             except ValueError:
                 pass
     os.makedirs(os.path.dirname(args.out) or ".", exist_ok=True)
@@ -139,7 +141,7 @@ def main(argv=None):
             if (M, N, K, dt) in done:
                 continue
             t0 = time.time()
-            rec, rows = sweep_shape(M, N, K, dt, ws, quick=args.quick)
+            rec, rows = sweep_shape(M, N, K, dt, ws, quick=args.quick, b_layout=args.b_layout)
             if args.all_rows:
                 rec["rows"] = rows
             f.write(json.dumps(rec) + "\n")
