@@ -194,6 +194,21 @@ int gemm_hw_set(const gemm_hw *in);
 int gemm_hw_reset(void);
 
 /*
+ * Built-in descriptors (Section I: porting the selector to another GPU is a matter of
+ * replacing the hardware table; Section V evaluates on a 304-CU part).  Writes the table to
+ * *out without installing it; pass it to gemm_hw_set to retarget gemm_select / gemm_predict.
+ *   GEMM_HW_MI355X       the default: 256 CUs in 8 XCDs, 160 KB LDS, measured rates.
+ *   GEMM_HW_MI300X_LIKE  304 CUs in 8 XCDs of 38, 64 KB LDS, 4 MB L2 per XCD, 256 MB MALL,
+ *                        2.1 GHz, public bandwidth figures, matrix-instruction intervals of
+ *                        the half-rate CDNA3 matrix cores.  For the selector only: the kernels
+ *                        of this library are gfx950 code, and variants whose LDS ring exceeds
+ *                        64 KB are not candidates under this table.
+ * Errors: GEMM_ERR_NULL, GEMM_ERR_INDEX (unknown id).
+ */
+typedef enum { GEMM_HW_MI355X = 0, GEMM_HW_MI300X_LIKE = 1 } gemm_hw_id;
+int gemm_hw_preset(int id, gemm_hw *out);
+
+/*
  * Calibration probes (Section I: the model's hardware rates come from micro-benchmarks).
  * Each runs two launches on hip_stream, times the second with HIP events, synchronises and
  * writes the measured rate.  scratch4: caller-owned device memory, at least 4 bytes.

@@ -112,6 +112,8 @@ _lib.gemm_hw_set.restype = _int
 _lib.gemm_hw_set.argtypes = [ctypes.POINTER(gemm_hw)]
 _lib.gemm_hw_reset.restype = _int
 _lib.gemm_hw_reset.argtypes = []
+_lib.gemm_hw_preset.restype = _int
+_lib.gemm_hw_preset.argtypes = [_int, ctypes.POINTER(gemm_hw)]
 
 
 _lib.gemm_probe_mfma.restype = _int
@@ -208,6 +210,15 @@ def gemm_hw_get():
 
 def gemm_hw_set(h):
     _check(_lib.gemm_hw_set(ctypes.byref(h)), "gemm_hw_set")
+
+
+GEMM_HW_MI355X, GEMM_HW_MI300X_LIKE = 0, 1
+
+
+def gemm_hw_preset(hw_id):
+    hw = gemm_hw()
+    _check(_lib.gemm_hw_preset(int(hw_id), ctypes.byref(hw)), "gemm_hw_preset")
+    return hw
 
 
 def gemm_hw_reset():

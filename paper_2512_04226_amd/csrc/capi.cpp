@@ -164,6 +164,13 @@ int gemm_hw_reset(void)
     return GEMM_OK;
 }
 
+int gemm_hw_preset(int id, gemm_hw *out)
+{
+    if (!out)
+        return GEMM_ERR_NULL;
+    return hw_preset(id, out) ? GEMM_OK : GEMM_ERR_INDEX;
+}
+
 size_t gemm_workspace_bytes(const gemm_cfg *cfg)
 {
     if (!cfg || cfg->split_k <= 1 || cfg->M < 1 || cfg->N < 1)

@@ -66,6 +66,36 @@ static gemm_hw make_default_hw()
     return h;
 }
 
+// A 304-CU CDNA3-class part as the paper's evaluation platform (Section V): public sizes and
+// bandwidths; matrix instructions at half the per-CU rate; fixed costs left as measured here.
+static gemm_hw make_mi300x_like_hw()
+{
+    gemm_hw h = make_default_hw();
+    h.n_cu = 304;
+    h.n_xcd = 8;
+    h.lds_bytes = 64.0 * 1024;
+    h.clk_ghz = 2.1;
+    h.hbm_bytes_per_clk = 5300.0 * 0.75 / 2.1;   // 5.3 TB/s pins, three quarters sustained
+    h.mall_bytes_per_clk = 17200.0 / 2.1 * 0.6;  // 17.2 TB/s peak Infinity Cache rate
+    h.lds_bytes_per_clk = 118.0;
+    h.lds_tr_bytes_per_clk = 30.0;               // no transpose LDS reads: narrow reads instead
+    for (int d = 0; d < 2; ++d)
+        for (int m = 0; m < 2; ++m)
+            h.l_mi_clk[d][m] = 2.0 * make_default_hw().l_mi_clk[d][m];
+    return h;
+}
+
+bool hw_preset(int id, gemm_hw *out)
+{
+    if (id == GEMM_HW_MI355X)
+        *out = make_default_hw();
+    else if (id == GEMM_HW_MI300X_LIKE)
+        *out = make_mi300x_like_hw();
+    else
+        return false;
+    return true;
+}
+
 static gemm_hw g_hw = make_default_hw();
 
 const gemm_hw &hw_current() { return g_hw; }

@@ -10,6 +10,7 @@ const Variant &variant_at(int dtype, int id);
 const gemm_hw &hw_current();
 void hw_replace(const gemm_hw &h);
 void hw_reset();
+bool hw_preset(int id, gemm_hw *out);
 int elem_bytes(int dtype);
 int mfma_k(int dtype, int mfma);
 int64_t k_per_split(const Variant &v, int64_t K, int split_k);

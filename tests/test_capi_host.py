@@ -21,7 +21,7 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported():
     names = _declared_functions()
     assert {"gemm_select", "gemm_run", "gemm_workspace_bytes", "gemm_set_workspace", "gemm_cfg_count",
-            "gemm_cfg_at", "gemm_predict", "gemm_hw_get", "gemm_hw_set", "gemm_hw_reset", "gemm_strerror",
+            "gemm_cfg_at", "gemm_predict", "gemm_hw_get", "gemm_hw_set", "gemm_hw_reset", "gemm_hw_preset", "gemm_strerror",
             "gemm_abi_version"} <= set(names)
     lib = ctypes.CDLL(g.LIB_PATH)
     for n in names:

@@ -181,3 +181,42 @@ def test_model_reduces_to_the_papers_form_when_extras_are_off():
     assert o["l_tile"] == pytest.approx(l_tile)
     assert o["l_total"] == pytest.approx(sm.alg9_total_latency(8192, 8192, 256, 256, 256, l_tile))
     assert o["h_l2"] == pytest.approx(sm.alg5_hit_rate(4, 8, 256, 256, 64))
+
+
+def test_retargeting_to_a_304_cu_table_changes_waves_cache_tiles_and_candidates():
+    """Section I / V: the selector is ported by swapping the hardware table.  Under the 304-CU table
+    Algorithm 4 must count waves of 304 tiles and Algorithm 6 must factor 38 CUs per L2; every
+    shipped term must still agree with the oracle evaluated on that table."""
+    from paper_2512_04226_amd import binding as g
+    base = bytes(g.gemm_hw_get())
+    try:
+        g.gemm_hw_set(g.gemm_hw_preset(g.GEMM_HW_MI300X_LIKE))
+        hw = _hw_dict(g)
+        assert hw["n_cu"] == 304 and hw["n_xcd"] == 8 and hw["lds_bytes"] == 64 * 1024
+        seen = 0
+        for idx in range(g.gemm_cfg_count(0)):
+            c = g.gemm_cfg_at(idx, 2432, 2048, 4096, 0)
+            if c is None:
+                continue
+            # candidates must fit the smaller LDS
+            assert c.stages * (c.block_m + c.block_n) * c.block_k * 2 <= 64 * 1024, c.describe()
+            p = g.gemm_predict(c)
+            o = sm.predict(hw, 0, 2432, 2048, 4096, _variant_dict(c), c.split_k)
+            for f in ("tiles", "waves", "active_cu", "f_m", "f_n", "h_l2", "h_mall", "l_mem", "l_total"):
+                assert getattr(p, f) == pytest.approx(o[f], rel=1e-9, abs=1e-9), (c.describe(), f)
+            if (c.block_m, c.block_n, c.block_k, c.stages, c.split_k) == (128, 128, 64, 2, 1):
+                # 19 x 16 = 304 tiles, one workgroup per CU (the ring fills the 64 KB LDS): exactly one full wave
+                assert p.tiles == 304 and p.waves == 1 and p.active_cu == 304
+                assert p.f_m * p.f_n == 38 and {p.f_m, p.f_n} == {2.0, 19.0}
+                seen += 1
+        assert seen >= 1
+        pick_304 = g.gemm_select(2432, 2048, 4096, 0)
+        assert pick_304.stages * (pick_304.block_m + pick_304.block_n) * pick_304.block_k * 2 <= 64 * 1024
+    finally:
+        g.gemm_hw_reset()
+    assert bytes(g.gemm_hw_get()) == base
+    p = g.gemm_predict(g.gemm_cfg_at(0, 4864, 4096, 4096, 0))
+    assert p.waves == 2 and p.active_cu == 48
+    with pytest.raises(g.GemmError):
+        g.gemm_hw_preset(7)
+    assert bytes(g.gemm_hw_preset(g.GEMM_HW_MI355X)) == base
