@@ -29,7 +29,7 @@
 extern "C" {
 #endif
 
-#define GEMM_ABI_VERSION 1u
+#define GEMM_ABI_VERSION 2u
 
 typedef enum gemm_dtype {
     GEMM_BF16 = 0,     /* A, B bf16 */
@@ -118,7 +118,8 @@ typedef struct gemm_cfg {
     uint8_t stages;           /* LDS ring depth: K_T slabs resident or in flight per workgroup */
     uint16_t slab_clk;        /* the variant's calibrated cost: clocks per K_T slab of one tile on a full CU */
     uint8_t b_layout;         /* gemm_b_layout */
-    uint8_t reserved[3];
+    uint8_t stream_k;         /* 1: the last partial wave of tiles is split along K over sk_workers workgroups (needs split_k = 1) */
+    uint16_t sk_workers;      /* stream-K workgroups G (= workgroup slots of the device for this variant); 0 when stream_k = 0 */
     float alpha;              /* default 1; the caller may overwrite it before gemm_run */
     int32_t bottleneck;       /* gemm_bottleneck of the prediction */
     double predicted_us;      /* model's total latency for this cfg */
@@ -164,15 +165,46 @@ int gemm_select_ex(int64_t M, int64_t N, int64_t K, int dtype, int b_layout, gem
 /*
  * Enqueue C = alpha * A * B on hip_stream (a hipStream_t; NULL = the default stream) with
  * the kernel cfg names; returns without synchronising.  A, B, C: device pointers,
- * 16-byte aligned.  When cfg->split_k > 1 a workspace of gemm_workspace_bytes(cfg) must
- * have been registered with gemm_set_workspace for the current device.
+ * 16-byte aligned.  When cfg->split_k > 1 or cfg->stream_k = 1 a workspace of
+ * gemm_workspace_bytes(cfg) must have been registered with gemm_set_workspace for the
+ * current device.
  */
 int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void *C, void *hip_stream);
 
-/* fp32 partial-sum slabs: split_k * M * N * 4 bytes when split_k > 1, else 0. */
+/* fp32 partial sums: split_k * M * N * 4 bytes when split_k > 1; 2 * sk_workers * block_m *
+ * block_n * 4 bytes (two partial tiles per stream-K workgroup) when stream_k = 1; else 0. */
 size_t gemm_workspace_bytes(const gemm_cfg *cfg);
 
-/* Register (or, with NULL/0, drop) a caller-owned device buffer used by split-K runs.
+/*
+ * Stream-K work split of a cfg with stream_k = 1 (Section V-E: the paper's kernels use
+ * Stream-K against wave quantisation).  Host only, no GPU: the same arithmetic the kernel
+ * runs, exposed for tests and tools.  Tiles are taken in rasterisation order; the first
+ * dp_tiles get one workgroup each, the last sk_tiles = tiles % sk_workers are cut along K:
+ * with S = ceil(K / block_k) slabs per tile, worker g owns iterations
+ * [g * sk_tiles * S / G, (g + 1) * sk_tiles * S / G) of the tile-major numbering.
+ *   gemm_stream_k_plan      writes {workers G, sk_tiles, dp_tiles, slabs S} to plan4.
+ *   gemm_stream_k_segments  writes worker g's segments (at most 2) and returns their number
+ *                           (>= 0) or a negative gemm_status.  A segment with complete = 1 is
+ *                           stored to C by its worker; any other leaves an fp32 partial tile in
+ *                           workspace slot 2 * g + (segment number) for the summation pass.
+ *   gemm_stream_k_contributors  what the summation pass adds up for stream-K tile j: writes
+ *                           {first worker, last worker, segment number of the first worker's
+ *                           partial} to out3; the partials of the later workers are their
+ *                           segment 0.  first == last means one worker stored the whole tile.
+ * Errors: GEMM_ERR_NULL, GEMM_ERR_ABI, GEMM_ERR_CFG_ILLEGAL (not a legal stream-K cfg),
+ * GEMM_ERR_INDEX (worker outside [0, G), tile outside [0, sk_tiles)).
+ */
+typedef struct gemm_sk_segment {
+    int32_t tile_m, tile_n;   /* output tile coordinates */
+    int32_t slab0, count;     /* K_T slabs [slab0, slab0 + count) of the tile */
+    int32_t complete;         /* 1: the whole tile */
+    int32_t sk_tile;          /* index among the stream-K tiles */
+} gemm_sk_segment;
+int gemm_stream_k_plan(const gemm_cfg *cfg, int32_t plan4[4]);
+int gemm_stream_k_segments(const gemm_cfg *cfg, int worker, gemm_sk_segment seg[2]);
+int gemm_stream_k_contributors(const gemm_cfg *cfg, int sk_tile, int32_t out3[3]);
+
+/* Register (or, with NULL/0, drop) a caller-owned device buffer used by split-K and stream-K runs.
  * The buffer must outlive every gemm_run that uses it; runs that share it must be
  * stream-ordered. */
 int gemm_set_workspace(void *dev_ptr, size_t bytes);

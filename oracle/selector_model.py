@@ -131,10 +131,23 @@ def segment_efficiency(hw, seg):
     return min(1.0, hw["seg_eff_lo"] + (1.0 - hw["seg_eff_lo"]) * math.log2(s / 32.0) / 3.0)
 
 
-def predict(hw, dtype, M, N, K, v, split_k, b_layout=0):
+def stream_k_split(tiles, slots, slabs):
+    """Hybrid Stream-K split (Section V-E names Stream-K as the paper kernels' answer to wave
+    quantisation; READING: whole waves of `slots` tiles stay one-tile-per-workgroup, the
+    tiles % slots left over are cut along K into `slots` equal ranges).  Returns (whole waves,
+    stream-K tiles, slabs per worker) or None when there is no partial wave or fewer slabs than
+    workers."""
+    sk = tiles % slots
+    if sk == 0 or sk * slabs < slots:
+        return None
+    return (tiles - sk) // slots, sk, sk * slabs / slots
+
+
+def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0):
     """Model terms for variant v (dict: block_m/n/k, waves_m/n, mfma, stages, slab_clk) with the
     reduction split split_k ways; hw is a dict of the hardware descriptor's fields; b_layout 0 =
-    B row-major K x N, 1 = B stored K-contiguous (then v["slab_clk"] is that layout's constant).
+    B row-major K x N, 1 = B stored K-contiguous (then v["slab_clk"] is that layout's constant);
+    stream_k = 1 prices the hybrid Stream-K split of the last partial wave (needs split_k = 1).
     Returns a dict with the names of the C ABI's gemm_prediction plus group_m."""
     es = 2 if dtype == 0 else 1
     mi = v["mfma"]
@@ -233,5 +246,23 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0):
     # Algorithm 9.  READING: full waves and the under-occupied last wave are priced separately,
     # plus one launch.
     out["l_total"] = hw["launch_clk"] + (waves - 1) * full["l_tile"] + tail["l_tile"] + l_reduce
+
+    if stream_k:
+        # READING (fractional waves in Algorithms 4 and 9): after `whole` full waves the remaining
+        # sk tiles cost w slabs per slot instead of a whole tile; every CU is full; a share
+        # sk/slots of the workers works on two tiles and pays prologue and store stage twice;
+        # partial tiles are fp32 and a second pass reads (slots + sk) of them and writes sk tiles.
+        whole, sk, w = stream_k_split(tiles, slots, slabs)
+        tile_elems = v["block_m"] * v["block_n"]
+        l_epi_sk = hw["n_cu"] * occ * tile_elems * 4.0 / hw["hbm_bytes_per_clk"] + hw["epilogue_clk"]
+        l_sk = (1.0 + sk / slots) * (full["l_prologue"] + l_epi_sk) + full["l_iter"] * (w - 1.0) + full["l_compute"]
+        nbytes = (slots + sk) * tile_elems * 4.0 + sk * tile_elems * 2.0
+        rate = hw["mall_bytes_per_clk"] if nbytes <= hw["cache_eff_frac"] * hw["mall_bytes"] else hw["hbm_bytes_per_clk"]
+        l_sum = hw["reduce_launch_clk"] + nbytes / rate
+        for k in ("l_compute", "l_issue", "l_lds", "l_l2", "l_mall", "l_hbm", "l_mem", "l_prologue", "l_epilogue",
+                  "l_iter", "l_tile"):
+            out[k] = full[k]
+        out.update(waves=whole + sk / slots, active_cu=hw["n_cu"], l_mem_tail=full["l_mem"], l_tile_tail=l_sk,
+                   l_reduce=l_sum, l_total=hw["launch_clk"] + whole * full["l_tile"] + l_sk + l_sum)
     out["total_us"] = out["l_total"] / (hw["clk_ghz"] * 1e3)
     return out

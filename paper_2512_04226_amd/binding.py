@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("GEMM355_LIB") or os.path.join(_PKG, "libgemm355.so") 
 
 GEMM_BF16 = 0
 GEMM_FP8_E4M3 = 1
-GEMM_ABI_VERSION = 1
+GEMM_ABI_VERSION = 2
 GEMM_B_ROW_MAJOR = 0
 GEMM_B_K_CONTIGUOUS = 1
 
@@ -56,13 +56,15 @@ class gemm_cfg(ctypes.Structure):
                 ("waves_n", ctypes.c_uint8), ("mfma", ctypes.c_uint8), ("k_unroll", ctypes.c_uint8),
                 ("split_k", ctypes.c_uint16), ("group_m", ctypes.c_uint16), ("group_n", ctypes.c_uint16),
                 ("xcd_remap", ctypes.c_uint8), ("stages", ctypes.c_uint8),
-                ("slab_clk", ctypes.c_uint16), ("b_layout", ctypes.c_uint8), ("reserved", ctypes.c_uint8 * 3), ("alpha", ctypes.c_float),
+                ("slab_clk", ctypes.c_uint16), ("b_layout", ctypes.c_uint8), ("stream_k", ctypes.c_uint8),
+                ("sk_workers", ctypes.c_uint16), ("alpha", ctypes.c_float),
                 ("bottleneck", ctypes.c_int32), ("predicted_us", ctypes.c_double)]
 
     def describe(self):
-        return ("%dx%dx%d w%dx%d mfma%d s%d split%d g%d%s%s" % (
+        return ("%dx%dx%d w%dx%d mfma%d s%d %s g%d%s%s" % (
             self.block_m, self.block_n, self.block_k, self.waves_m, self.waves_n, self.mfma, self.stages,
-            self.split_k, self.group_m, "" if self.xcd_remap else " noxcd", " Bkc" if self.b_layout else ""))
+            ("streamk%d" % self.sk_workers) if self.stream_k else ("split%d" % self.split_k), self.group_m,
+            "" if self.xcd_remap else " noxcd", " Bkc" if self.b_layout else ""))
 
     def copy(self):
         c = gemm_cfg()
@@ -223,6 +225,43 @@ def gemm_hw_preset(hw_id):
 
 def gemm_hw_reset():
     _check(_lib.gemm_hw_reset(), "gemm_hw_reset")
+
+
+class gemm_sk_segment(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("tile_m", "tile_n", "slab0", "count", "complete", "sk_tile")]
+
+
+_lib.gemm_stream_k_plan.restype = _int
+_lib.gemm_stream_k_plan.argtypes = [ctypes.POINTER(gemm_cfg), ctypes.POINTER(ctypes.c_int32)]
+_lib.gemm_stream_k_segments.restype = _int
+_lib.gemm_stream_k_segments.argtypes = [ctypes.POINTER(gemm_cfg), _int, ctypes.POINTER(gemm_sk_segment)]
+
+
+_lib.gemm_stream_k_contributors.restype = _int
+_lib.gemm_stream_k_contributors.argtypes = [ctypes.POINTER(gemm_cfg), _int, ctypes.POINTER(ctypes.c_int32)]
+
+
+def gemm_stream_k_contributors(cfg, sk_tile):
+    """(first worker, last worker, segment number of the first worker's partial) of a stream-K tile."""
+    out = (ctypes.c_int32 * 3)()
+    _check(_lib.gemm_stream_k_contributors(ctypes.byref(cfg), int(sk_tile), out), "gemm_stream_k_contributors")
+    return tuple(out)
+
+
+def gemm_stream_k_plan(cfg):
+    """(workers, sk_tiles, dp_tiles, slabs) of a stream-K cfg."""
+    out = (ctypes.c_int32 * 4)()
+    _check(_lib.gemm_stream_k_plan(ctypes.byref(cfg), out), "gemm_stream_k_plan")
+    return tuple(out)
+
+
+def gemm_stream_k_segments(cfg, worker):
+    """Worker's segments as a list of gemm_sk_segment (at most two)."""
+    seg = (gemm_sk_segment * 2)()
+    n = _lib.gemm_stream_k_segments(ctypes.byref(cfg), int(worker), seg)
+    if n < 0:
+        raise GemmError(n, "gemm_stream_k_segments")
+    return [seg[i] for i in range(n)]
 
 
 def gemm_workspace_bytes(cfg):

@@ -17,13 +17,15 @@
 #include <stdint.h>
 #include <type_traits>
 
+#include "stream_k.hpp"
+
 namespace g355 {
 
 struct KernelArgs {
     const void *A;
     const void *B;
-    void *C;       // bf16 output (split_k == 1)
-    float *ws;     // fp32 slabs [split_k][M][N] (split_k > 1)
+    void *C;       // bf16 output
+    float *ws;     // fp32 slabs [split_k][M][N] (split_k > 1), or stream-K partial tiles
     int M, N, K;
     int lda, ldb, ldc;  // elements
     float alpha;
@@ -33,6 +35,10 @@ struct KernelArgs {
     int group_m;
     int xcd_remap;
     int n_xcd;
+    // Stream-K (sk.workers > 0, split_k == 1): workgroups [0, sk.workers) are stream-K workers,
+    // the rest compute the sk.dp_tiles data-parallel tiles; ws then holds the workers' partial
+    // tiles, [2 * workers][BLOCK_M][BLOCK_N] fp32.
+    SkPlan sk;
 };
 
 typedef short short4_t __attribute__((ext_vector_type(4)));
@@ -113,25 +119,18 @@ struct Tile {
 // and inside the tile grid the ids run column-major through bands of group_m tile rows,
 // so the workgroups that share an L2 at one time form a compact group_m x (CUs/group_m)
 // block of output tiles (the cache tile of Algorithms 5 and 6).
-__device__ inline void tile_coords(const KernelArgs &a, int pid, int &tm, int &tn, int &ks)
+// pid in [0, grid), grid = data-parallel tiles * split_k.
+__device__ inline void tile_coords(const KernelArgs &a, int pid, int grid, int &tm, int &tn, int &ks)
 {
     const int tiles = a.tiles_m * a.tiles_n;
     int l = pid;
     if (a.xcd_remap) {
-        const int grid = tiles * a.split_k;
         const int per = grid / a.n_xcd, rem = grid % a.n_xcd;
         const int x = pid % a.n_xcd, q = pid / a.n_xcd;
         l = x * per + (x < rem ? x : rem) + q;
     }
     ks = l / tiles;
-    const int t = l - ks * tiles;
-    const int band_sz = a.group_m * a.tiles_n;
-    const int band = t / band_sz;
-    const int first_m = band * a.group_m;
-    const int rows = (a.tiles_m - first_m < a.group_m) ? (a.tiles_m - first_m) : a.group_m;
-    const int r = t - band * band_sz;
-    tm = first_m + r % rows;
-    tn = r / rows;
+    logical_tile(a.tiles_m, a.tiles_n, a.group_m, l - ks * tiles, tm, tn);
 }
 
 __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned bytes)
@@ -143,37 +142,52 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned by
 // beyond every window (windows are validated to stay below 2 GiB); small advances keep it there
 constexpr unsigned OOB_OFFSET = 0x80000000u;
 
-// The same descriptor as four dwords, for inline assembly.
-__device__ inline i32x4 make_rsrc_words(const void *base, unsigned bytes)
-{
-    const uint64_t p = (uint64_t)base;
-    i32x4 w;
-    w[0] = (int)(uint32_t)p;
-    w[1] = (int)(uint32_t)((p >> 32) & 0xFFFFu);
-    w[2] = (int)bytes;
-    w[3] = 0x00020000;
-    return w;
-}
-
 template <class T>
 __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
 {
     constexpr int ES = T::ES, BM = T::BM, BN = T::BN, BK = T::BK, MI = T::MI, NT = T::NT;
     __shared__ __attribute__((aligned(1024))) uint8_t smem[T::NS * T::STAGE];
 
-    int tm, tn, ks;
-    tile_coords(args, blockIdx.x, tm, tn, ks);
-    const int m0 = tm * BM, n0 = tn * BN;
-    const int k_begin = ks * args.k_per_split;
-    int k_len = args.K - k_begin;
-    if (k_len > args.k_per_split)
-        k_len = args.k_per_split;
-    const int kt_count = (k_len + BK - 1) / BK;
+    // Work of this workgroup: one (tile, K slice) for a data-parallel or split-K launch, up to
+    // two (tile, slab range) segments for a stream-K worker.
+    const bool sk_worker = (int)blockIdx.x < args.sk.workers;
+    SkSegment segs[2];
+    int nseg = 1;
+    if (sk_worker)
+        nseg = sk_segments(args.sk, (int)blockIdx.x, segs);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept scalar
     const int wm = wave / T::WN, wn = wave % T::WN;
+
+    for (int seg = 0; seg < nseg; ++seg) {
+    // out_mode 0: bf16 C;  1: fp32 split-K slab ks;  2: fp32 partial tile of a stream-K segment
+    int tm, tn, ks = 0, k_begin, k_len, out_mode;
+    if (sk_worker) {
+        const SkSegment sg = (seg == 0) ? segs[0] : segs[1];
+        logical_tile(args.tiles_m, args.tiles_n, args.group_m, args.sk.dp_tiles + sg.tile, tm, tn);
+        k_begin = sg.slab0 * BK;
+        k_len = sg.count * BK;
+        if (k_len > args.K - k_begin)
+            k_len = args.K - k_begin;
+        out_mode = sg.complete ? 0 : 2;
+        if (seg) {
+            // the previous segment's stores have left and every wave is done with its LDS stages
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+        }
+    } else {
+        const int grid = (args.sk.workers > 0) ? args.sk.dp_tiles : args.tiles_m * args.tiles_n * args.split_k;
+        tile_coords(args, (int)blockIdx.x - args.sk.workers, grid, tm, tn, ks);
+        k_begin = ks * args.k_per_split;
+        k_len = args.K - k_begin;
+        if (k_len > args.k_per_split)
+            k_len = args.k_per_split;
+        out_mode = (args.split_k > 1) ? 1 : 0;
+    }
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int kt_count = (k_len + BK - 1) / BK;
 
     // ---- global -> LDS bookkeeping ----
     // Load instruction i of wave w fills LDS unit u = i*NW + w of the stage: lane l writes the
@@ -409,8 +423,11 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     v[r] = acc[j][i][q * 4 + r];
-                if (args.split_k > 1) {
+                if (out_mode == 1) {
                     float *dst = args.ws + ((size_t)ks * args.M + m) * args.N + n;
+                    *(f32x4 *)dst = v;
+                } else if (out_mode == 2) {
+                    float *dst = args.ws + ((size_t)(2 * blockIdx.x + seg) * BM + (m - m0)) * BN + (n - n0);
                     *(f32x4 *)dst = v;
                 } else {
                     bf16x4 o;
@@ -423,6 +440,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             }
         }
     }
+    }   // segments
 }
 
 }  // namespace g355

@@ -12,6 +12,7 @@
 
 #include "../../include/gemm.h"
 #include "model.hpp"
+#include "stream_k.hpp"
 #include "variants.hpp"
 
 namespace g355 {
@@ -118,11 +119,21 @@ int64_t k_per_split(const Variant &v, int64_t K, int split_k)
     return cdiv(cdiv(K, v.block_k), split_k) * v.block_k;
 }
 
-bool variant_legal(const gemm_hw &hw, const Variant &v, int dtype, int64_t M, int64_t N, int64_t K, int split_k)
+static int occupancy(const gemm_hw &hw, const Variant &v, int dtype);
+
+int stream_k_workers(const gemm_hw &hw, const Variant &v, int dtype) { return hw.n_cu * occupancy(hw, v, dtype); }
+
+bool variant_legal(const gemm_hw &hw, const Variant &v, int dtype, int64_t M, int64_t N, int64_t K, int split_k,
+                   int stream_k)
 {
-    (void)M;
-    (void)N;
     const int es = elem_bytes(dtype);
+    if (stream_k) {
+        // stream-K splits the last partial wave of tiles; it needs one, and work for every worker
+        SkPlan plan;
+        if (split_k != 1 || !sk_make_plan(cdiv(M, v.block_m) * cdiv(N, v.block_n), stream_k_workers(hw, v, dtype),
+                                          cdiv(K, v.block_k), &plan))
+            return false;
+    }
     const double lds = (double)v.stages * (v.block_m + v.block_n) * v.block_k * es;
     if (lds > hw.lds_bytes)
         return false;
@@ -277,7 +288,7 @@ static int label_of(const MemTerms &t, double l_comp, bool under, double fixed, 
 }
 
 void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, int64_t K, const Variant &v, int split_k,
-             gemm_prediction *p, int *group_m, int *group_n)
+             int stream_k, gemm_prediction *p, int *group_m, int *group_n)
 {
     std::memset(p, 0, sizeof(*p));
     const int es = elem_bytes(dtype);
@@ -381,18 +392,53 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
 
     // Algorithm 9, with full waves and the under-occupied last wave priced separately.
     p->l_total = hw.launch_clk + (waves - 1.0) * l_tile_full + l_tile_tail + l_reduce;
+
+    if (stream_k) {
+        // Fractional last wave: the tiles % slots tiles left over after the whole waves are cut
+        // along K into one equal range of w slabs per slot, so the last "wave" costs w slabs
+        // instead of a whole tile.  Every CU is full; a share sk/slots of the workers straddles
+        // two tiles and pays the prologue and store stage twice; partial tiles leave as fp32 and a
+        // second pass sums them (read (slots + sk) partial tiles, write sk tiles).
+        const double sk = std::fmod(tiles, slots);
+        const double whole = (tiles - sk) / slots;
+        const double w = sk * slabs / slots;
+        const double tile_bytes = (double)v.block_m * v.block_n;
+        const double l_epi_sk = hw.n_cu * occ * tile_bytes * 4.0 / hw.hbm_bytes_per_clk + hw.epilogue_clk;
+        const double l_sk = (1.0 + sk / slots) * (pro + l_epi_sk) + iter * (w - 1.0) + lc_full;
+        const double bytes = (slots + sk) * tile_bytes * 4.0 + sk * tile_bytes * 2.0;
+        const double rate = (bytes <= hw.cache_eff_frac * hw.mall_bytes) ? hw.mall_bytes_per_clk : hw.hbm_bytes_per_clk;
+        l_reduce = hw.reduce_launch_clk + bytes / rate;
+        p->waves = whole + sk / slots;
+        p->active_cu = hw.n_cu;
+        p->l_compute = lc_full;
+        p->l_issue = mt_full.l_issue;
+        p->l_lds = mt_full.l_lds;
+        p->l_l2 = mt_full.l_l2;
+        p->l_mall = mt_full.l_mall;
+        p->l_hbm = mt_full.l_hbm;
+        p->l_mem = mt_full.l_mem;
+        p->l_mem_tail = mt_full.l_mem;
+        p->l_prologue = pro;
+        p->l_epilogue = epi;
+        p->l_iter = iter;
+        p->l_tile = l_tile_full;
+        p->l_tile_tail = l_sk;
+        p->l_reduce = l_reduce;
+        p->l_total = hw.launch_clk + whole * l_tile_full + l_sk + l_reduce;
+    }
     p->total_us = p->l_total / (hw.clk_ghz * 1e3);
     const double fixed = hw.launch_clk + l_reduce + waves * (p->l_prologue + p->l_epilogue);
-    p->bottleneck = label_of(mt, p->l_compute, active < hw.n_cu && waves == 1.0, fixed, p->l_total - fixed);
+    p->bottleneck = label_of(stream_k ? mt_full : mt, p->l_compute, !stream_k && active < hw.n_cu && waves == 1.0, fixed,
+                             p->l_total - fixed);
 }
 
 void fill_cfg(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, int64_t K, int kernel_id, int split_k,
-              gemm_cfg *c)
+              int stream_k, gemm_cfg *c)
 {
     const Variant &v = variant_at(dtype, kernel_id);
     gemm_prediction p;
     int gm, gn;
-    predict(hw, dtype, b_layout, M, N, K, v, split_k, &p, &gm, &gn);
+    predict(hw, dtype, b_layout, M, N, K, v, split_k, stream_k, &p, &gm, &gn);
     std::memset(c, 0, sizeof(*c));
     c->abi_version = GEMM_ABI_VERSION;
     c->dtype = dtype;
@@ -417,6 +463,8 @@ void fill_cfg(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, 
     c->stages = (uint8_t)v.stages;
     c->slab_clk = (uint16_t)(b_layout ? v.slab_clk_kc : v.slab_clk);
     c->b_layout = (uint8_t)b_layout;
+    c->stream_k = (uint8_t)(stream_k ? 1 : 0);
+    c->sk_workers = (uint16_t)(stream_k ? stream_k_workers(hw, v, dtype) : 0);
     c->alpha = 1.0f;
     c->bottleneck = p.bottleneck;
     c->predicted_us = p.total_us;

@@ -1,6 +1,8 @@
 // gemm_run and the split-K workspace: the only entry points that touch the GPU.
 #include <hip/hip_runtime.h>
 
+#include <cstring>
+
 #include "../../include/gemm.h"
 #include "gemm_kernel.hpp"
 #include "launch.hpp"
@@ -29,6 +31,44 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
             o[r] = (__bf16)(s[r] * alpha);
         *(bf16x4 *)(C + m * ldc + n) = o;
     }
+}
+
+
+// Stream-K second pass: for every stream-K tile that more than one worker contributed to,
+// sum the workers' fp32 partial tiles in worker order (deterministic), scale, round to bf16.
+// One thread per 4 consecutive n; blocks_per_tile blocks of 256 threads cover a tile.
+__global__ __launch_bounds__(256) void streamk_sum_kernel(const float *__restrict__ ws, __bf16 *__restrict__ C, int M,
+                                                          int N, int ldc, float alpha, int tiles_m, int tiles_n,
+                                                          int group_m, SkPlan sk, int BM, int BN, int blocks_per_tile)
+{
+    const int j = blockIdx.x / blocks_per_tile;
+    const int q = (blockIdx.x % blocks_per_tile) * 256 + threadIdx.x;
+    if (j >= sk.sk_tiles || q >= BM * BN / 4)
+        return;
+    int g_first, g_last;
+    sk_contributors(sk, j, &g_first, &g_last);
+    if (g_first == g_last)
+        return;   // one worker computed the whole tile and stored it
+    int tm, tn;
+    logical_tile(tiles_m, tiles_n, group_m, sk.dp_tiles + j, tm, tn);
+    const int row = q / (BN / 4), col = (q % (BN / 4)) * 4;
+    const int m = tm * BM + row, n = tn * BN + col;
+    if (m >= M || n >= N)
+        return;
+    const size_t tile_elems = (size_t)BM * BN;
+    const size_t off = (size_t)row * BN + col;
+    // the first contributor's partial is its second segment unless its range starts with this
+    // tile; every later contributor's range starts inside this tile (first segment)
+    f32x4 s = *(const f32x4 *)(ws + (size_t)(2 * g_first + sk_slot_of(sk, g_first, j)) * tile_elems + off);
+    for (int g = g_first + 1; g <= g_last; ++g) {
+        f32x4 t = *(const f32x4 *)(ws + (size_t)(2 * g) * tile_elems + off);
+        s += t;
+    }
+    bf16x4 o;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        o[r] = (__bf16)(s[r] * alpha);
+    *(bf16x4 *)(C + (size_t)m * ldc + n) = o;
 }
 
 }  // namespace g355
@@ -101,9 +141,14 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
     if (cfg->block_m != v.block_m || cfg->block_n != v.block_n || cfg->block_k != v.block_k ||
         cfg->waves_m != v.waves_m || cfg->waves_n != v.waves_n || cfg->mfma != v.mfma || cfg->stages != v.stages)
         return GEMM_ERR_CFG_ILLEGAL;
-    if (cfg->split_k < 1 || cfg->group_m < 1 || !variant_legal(hw, v, dtype, cfg->M, cfg->N, cfg->K, cfg->split_k))
+    if (cfg->split_k < 1 || cfg->group_m < 1 || !variant_legal(hw, v, dtype, cfg->M, cfg->N, cfg->K, cfg->split_k, 0))
         return GEMM_ERR_CFG_ILLEGAL;
-    if (cfg->b_layout > 1)
+    if (cfg->b_layout > 1 || cfg->stream_k > 1)
+        return GEMM_ERR_CFG_ILLEGAL;
+    // stream-K: the plan is rebuilt from the cfg's own worker count and must exist
+    SkPlan sk;
+    std::memset(&sk, 0, sizeof(sk));
+    if (cfg->stream_k && !cfg_stream_k_plan(cfg, &sk))
         return GEMM_ERR_CFG_ILLEGAL;
     if (cfg->lda < cfg->K || cfg->ldb < (cfg->b_layout ? cfg->K : cfg->N) || cfg->ldc < cfg->N)
         return GEMM_ERR_SHAPE;
@@ -118,11 +163,11 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
     const int64_t b_window = cfg->b_layout ? (int64_t)v.block_n * cfg->ldb * es
                                            : (kps + (int64_t)v.stages * v.block_k) * cfg->ldb * es;
     if ((int64_t)v.block_m * cfg->lda * es >= lim || b_window >= lim ||
-        tiles_m * tiles_n * cfg->split_k >= lim || cfg->M * cfg->N >= ((int64_t)1 << 40))
+        tiles_m * tiles_n * cfg->split_k + cfg->sk_workers >= lim || cfg->M * cfg->N >= ((int64_t)1 << 40))
         return GEMM_ERR_SHAPE;
 
     float *ws = nullptr;
-    if (cfg->split_k > 1) {
+    if (cfg->split_k > 1 || cfg->stream_k) {
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
             (void)hipGetLastError();
@@ -152,13 +197,21 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
     a.group_m = cfg->group_m;
     a.xcd_remap = cfg->xcd_remap ? 1 : 0;
     a.n_xcd = hw.n_xcd;
+    a.sk = sk;   // workers == 0 unless stream-K
 
     hipStream_t stream = (hipStream_t)hip_stream;
     if (launcher_of(dtype, cfg->kernel_id, cfg->b_layout)(a, stream) != hipSuccess) {
         (void)hipGetLastError();
         return GEMM_ERR_HIP;
     }
-    if (cfg->split_k > 1) {
+    if (cfg->stream_k) {
+        const int bpt = (v.block_m * v.block_n / 4 + 255) / 256;
+        (void)hipGetLastError();
+        hipLaunchKernelGGL(streamk_sum_kernel, dim3((unsigned)(sk.sk_tiles * bpt)), dim3(256), 0, stream, ws, (__bf16 *)C,
+                           a.M, a.N, a.ldc, a.alpha, a.tiles_m, a.tiles_n, a.group_m, sk, v.block_m, v.block_n, bpt);
+        if (hipGetLastError() != hipSuccess)
+            return GEMM_ERR_HIP;
+    } else if (cfg->split_k > 1) {
         const size_t quads = (size_t)cfg->M * (size_t)(cfg->N / 4);
         size_t blocks = (quads + 255) / 256;
         if (blocks > 256 * 8)

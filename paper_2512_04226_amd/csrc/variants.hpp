@@ -85,4 +85,8 @@ struct Variant {
 // Spatial K-unroll factors offered with every variant.
 constexpr int kSplitKs[] = {1, 2, 4, 8, 16, 32};
 constexpr int kNumSplitKs = sizeof(kSplitKs) / sizeof(kSplitKs[0]);
+// Work splits offered with every variant: the split-K factors, then stream-K.
+constexpr int kNumSplits = kNumSplitKs + 1;
+inline int split_k_of(int mode) { return mode < kNumSplitKs ? kSplitKs[mode] : 1; }
+inline int stream_k_of(int mode) { return mode == kNumSplitKs ? 1 : 0; }
 }  // namespace g355

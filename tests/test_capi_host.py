@@ -65,11 +65,16 @@ def test_cfg_at_enumeration_and_legality():
     seen = set()
     for i in range(n):
         c = g.gemm_cfg_at(i, 4096, 4096, 8192, 0)
-        assert c is not None and c.abi_version == 1 and c.M == 4096 and c.lda == 8192 and c.ldb == 4096
+        if c is None:
+            # only a stream-K entry may be illegal here: the tile count has no partial wave to split
+            assert i % 7 == 6
+            continue
+        assert c.abi_version == g.GEMM_ABI_VERSION and c.M == 4096 and c.lda == 8192 and c.ldb == 4096
+        assert (c.stream_k == 1) == (i % 7 == 6) and (c.sk_workers > 0) == (c.stream_k == 1)
         assert c.block_k % (16 if c.mfma == 32 else 32) == 0 and c.k_unroll == c.block_k // (16 if c.mfma == 32 else 32)
         assert c.stages * (c.block_m + c.block_n) * c.block_k * 2 <= 160 * 1024
-        seen.add((c.kernel_id, c.split_k))
-    assert len(seen) == n
+        seen.add((c.kernel_id, c.split_k, c.stream_k))
+    assert n - n // 7 <= len(seen) <= n and any(k[2] for k in seen)
 
 
 def test_run_rejects_bad_arguments_without_launching():
@@ -78,7 +83,7 @@ def test_run_rejects_bad_arguments_without_launching():
     p = ctypes.c_void_p(0x1000)     # never dereferenced: every case fails validation first
     assert run(None, p, p, p, None) == -1
     assert run(ctypes.byref(cfg), None, p, p, None) == -1
-    bad = cfg.copy(); bad.abi_version = 2
+    bad = cfg.copy(); bad.abi_version = 99
     assert run(ctypes.byref(bad), p, p, p, None) == -7
     bad = cfg.copy(); bad.kernel_id = 10_000
     assert run(ctypes.byref(bad), p, p, p, None) == -4

@@ -130,7 +130,7 @@ def test_shipped_model_terms_match_the_oracle(dtype, b_layout):
     fields = ["n_mi", "l_mt_ideal", "l_compute", "tiles", "waves", "active_cu", "f_m", "f_n", "h_l2", "h_mall",
               "l_issue", "l_lds", "l_l2", "l_mall", "l_hbm", "l_mem", "l_mem_tail", "l_prologue", "l_epilogue",
               "l_iter", "iters", "l_tile", "l_tile_tail", "l_reduce", "l_total", "total_us"]
-    checked = 0
+    checked = n_sk = 0
     for (M, N, K) in SHAPES:
         if dtype == 1 and (N % 16 or K % 16):
             continue
@@ -140,12 +140,13 @@ def test_shipped_model_terms_match_the_oracle(dtype, b_layout):
                 continue
             assert c.b_layout == b_layout and c.ldb == (K if b_layout else N)
             p = g.gemm_predict(c)
-            o = sm.predict(hw, dtype, M, N, K, _variant_dict(c), c.split_k, b_layout)
+            o = sm.predict(hw, dtype, M, N, K, _variant_dict(c), c.split_k, b_layout, c.stream_k)
+            n_sk += c.stream_k
             for f in fields:
                 assert getattr(p, f) == pytest.approx(o[f], rel=1e-9, abs=1e-9), (M, N, K, c.describe(), f)
             assert c.group_m == o["group_m"] and c.predicted_us == pytest.approx(o["total_us"], rel=1e-9)
             checked += 1
-    assert checked > 500
+    assert checked > 500 and n_sk > 30
 
 
 def test_pick_is_the_oracle_argmin():
@@ -158,11 +159,11 @@ def test_pick_is_the_oracle_argmin():
             c = g.gemm_cfg_at(idx, M, N, K, 0)
             if c is None:
                 continue
-            t = sm.predict(hw, 0, M, N, K, _variant_dict(c), c.split_k)["l_total"]
+            t = sm.predict(hw, 0, M, N, K, _variant_dict(c), c.split_k, 0, c.stream_k)["l_total"]
             if best is None or t < best[0] * (1 - 1e-12):
-                best = (t, c.kernel_id, c.split_k)
+                best = (t, c.kernel_id, c.split_k, c.stream_k)
         pick = g.gemm_select(M, N, K, 0)
-        assert (pick.kernel_id, pick.split_k) == best[1:], (M, N, K, pick.describe())
+        assert (pick.kernel_id, pick.split_k, pick.stream_k) == best[1:], (M, N, K, pick.describe())
 
 
 def test_model_reduces_to_the_papers_form_when_extras_are_off():
@@ -201,10 +202,10 @@ def test_retargeting_to_a_304_cu_table_changes_waves_cache_tiles_and_candidates(
             # candidates must fit the smaller LDS
             assert c.stages * (c.block_m + c.block_n) * c.block_k * 2 <= 64 * 1024, c.describe()
             p = g.gemm_predict(c)
-            o = sm.predict(hw, 0, 2432, 2048, 4096, _variant_dict(c), c.split_k)
+            o = sm.predict(hw, 0, 2432, 2048, 4096, _variant_dict(c), c.split_k, 0, c.stream_k)
             for f in ("tiles", "waves", "active_cu", "f_m", "f_n", "h_l2", "h_mall", "l_mem", "l_total"):
                 assert getattr(p, f) == pytest.approx(o[f], rel=1e-9, abs=1e-9), (c.describe(), f)
-            if (c.block_m, c.block_n, c.block_k, c.stages, c.split_k) == (128, 128, 64, 2, 1):
+            if (c.block_m, c.block_n, c.block_k, c.stages, c.split_k, c.stream_k) == (128, 128, 64, 2, 1, 0):
                 # 19 x 16 = 304 tiles, one workgroup per CU (the ring fills the 64 KB LDS): exactly one full wave
                 assert p.tiles == 304 and p.waves == 1 and p.active_cu == 304
                 assert p.f_m * p.f_n == 38 and {p.f_m, p.f_n} == {2.0, 19.0}
