@@ -190,10 +190,11 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0):
     out["iters"] = slabs - 1
     out_bytes = 4.0 if split_k > 1 else 2.0
 
-    def memory(per_cu, act):
+    def memory(per_cu, act, h_l2=None):
         # Algorithm 7 in bytes and clocks.  READING: Ld_CU = (BM + BN) * BK bytes per tile; an LDS
         # fragment-read term is added; the HBM term carries the row-segment efficiency and the
         # latency is shared by the slabs in flight.
+        hit1 = h1 if h_l2 is None else h_l2
         a_bytes = v["block_m"] * v["block_k"] * es * per_cu
         b_bytes = v["block_n"] * v["block_k"] * es * per_cu
         ld_cu = a_bytes + b_bytes
@@ -205,10 +206,10 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0):
         total = ld_cu * act
         xcds = min(hw["n_xcd"], max(1.0, act))
         l_l2 = (total / xcds) / hw["l2_bytes_per_clk"]
-        l_mall = (1.0 - h1) * total / hw["mall_bytes_per_clk"]
+        l_mall = (1.0 - hit1) * total / hw["mall_bytes_per_clk"]
         ea = segment_efficiency(hw, v["block_k"] * es)
         eb = segment_efficiency(hw, (v["block_k"] if b_layout else v["block_n"]) * es)
-        t_m = (1.0 - h2) * (1.0 - h1) * (a_bytes / ea + b_bytes / eb) * act
+        t_m = (1.0 - h2) * (1.0 - hit1) * (a_bytes / ea + b_bytes / eb) * act
         l_hbm = t_m / hw["hbm_bytes_per_clk"] + hw["mem_latency_clk"] / max(1.0, per_cu * (v["stages"] - 1))
         return dict(l_issue=l_issue, l_lds=l_lds, l_l2=l_l2, l_mall=l_mall, l_hbm=l_hbm,
                     l_mem=max(l_issue, l_lds, l_l2, l_mall, l_hbm))
@@ -254,11 +255,21 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0):
         # partial tiles are fp32 and a second pass reads (slots + sk) of them and writes sk tiles.
         whole, sk, w = stream_k_split(tiles, slots, slabs)
         tile_elems = v["block_m"] * v["block_n"]
+        # READING: workers that share an L2 sit at different K offsets of different tiles, so the
+        # stream-K phase is priced with an L2 hit rate of zero.
+        m_sk = memory(float(occ), float(hw["n_cu"]), h_l2=0.0)
+        iter_sk = max(full["l_compute"], m_sk["l_mem"])
+        pro_sk = m_sk["l_mem"] + hw["mem_latency_clk"] + hw["wg_overhead_clk"]
         l_epi_sk = hw["n_cu"] * occ * tile_elems * 4.0 / hw["hbm_bytes_per_clk"] + hw["epilogue_clk"]
-        l_sk = (1.0 + sk / slots) * (full["l_prologue"] + l_epi_sk) + full["l_iter"] * (w - 1.0) + full["l_compute"]
+        l_sk = (1.0 + sk / slots) * (pro_sk + l_epi_sk) + iter_sk * (w - 1.0) + full["l_compute"]
         nbytes = (slots + sk) * tile_elems * 4.0 + sk * tile_elems * 2.0
         rate = hw["mall_bytes_per_clk"] if nbytes <= hw["cache_eff_frac"] * hw["mall_bytes"] else hw["hbm_bytes_per_clk"]
-        l_sum = hw["reduce_launch_clk"] + nbytes / rate
+        # READING: one output's contributors (at most slots // sk + 2) are added by 1, 4 or 8 thread
+        # rows, chosen by that count, with 4 loads in flight each
+        contrib = slots // sk + 2
+        rows = 8 if contrib > 32 else 4 if contrib > 8 else 1
+        chain = math.ceil(contrib / (4.0 * rows)) * hw["mem_latency_clk"]
+        l_sum = hw["reduce_launch_clk"] + nbytes / rate + chain
         for k in ("l_compute", "l_issue", "l_lds", "l_l2", "l_mall", "l_hbm", "l_mem", "l_prologue", "l_epilogue",
                   "l_iter", "l_tile"):
             out[k] = full[k]

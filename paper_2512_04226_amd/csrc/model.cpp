@@ -47,7 +47,7 @@ static gemm_hw make_default_hw()
     h.mall_bytes = 256.0 * 1024 * 1024;
     h.clk_ghz = 2.4;
     h.hbm_bytes_per_clk = 2500.0;    // 6.0 TB/s sustained of the 8 TB/s pins
-    h.mall_bytes_per_clk = 11600.0;
+    h.mall_bytes_per_clk = 4000.0;   // what L2 misses are served at when the MALL holds the data (fitted; a streaming read sees 6.5 TB/s)
     h.l2_bytes_per_clk = 2048.0;     // 16 channels x 128 B per XCD
     h.lds_bytes_per_clk = 118.0;     // ds_read_b128 fragments
     h.lds_tr_bytes_per_clk = 62.0;   // ds_read_b64_tr_* fragments
@@ -402,12 +402,21 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
         const double sk = std::fmod(tiles, slots);
         const double whole = (tiles - sk) / slots;
         const double w = sk * slabs / slots;
-        const double tile_bytes = (double)v.block_m * v.block_n;
-        const double l_epi_sk = hw.n_cu * occ * tile_bytes * 4.0 / hw.hbm_bytes_per_clk + hw.epilogue_clk;
-        const double l_sk = (1.0 + sk / slots) * (pro + l_epi_sk) + iter * (w - 1.0) + lc_full;
-        const double bytes = (slots + sk) * tile_bytes * 4.0 + sk * tile_bytes * 2.0;
+        const double tile_elems = (double)v.block_m * v.block_n;
+        // workers that share an L2 are at different K offsets of different tiles: no L2 reuse
+        const MemTerms mt_sk = memory_latency(hw, v, es, b_layout, (double)occ, (double)hw.n_cu, 0.0, h2);
+        const double iter_sk = std::max(lc_full, mt_sk.l_mem);
+        const double pro_sk = mt_sk.l_mem + hw.mem_latency_clk + hw.wg_overhead_clk;
+        const double l_epi_sk = hw.n_cu * occ * tile_elems * 4.0 / hw.hbm_bytes_per_clk + hw.epilogue_clk;
+        const double l_sk = (1.0 + sk / slots) * (pro_sk + l_epi_sk) + iter_sk * (w - 1.0) + lc_full;
+        // second pass: bytes through MALL or HBM, plus the dependent chain of one output's
+        // contributors (1, 4 or 8 thread rows share them, 4 loads in flight each)
+        const double bytes = (slots + sk) * tile_elems * 4.0 + sk * tile_elems * 2.0;
         const double rate = (bytes <= hw.cache_eff_frac * hw.mall_bytes) ? hw.mall_bytes_per_clk : hw.hbm_bytes_per_clk;
-        l_reduce = hw.reduce_launch_clk + bytes / rate;
+        const double contrib = std::floor(slots / sk) + 2.0;
+        const double rows = contrib > 32.0 ? 8.0 : contrib > 8.0 ? 4.0 : 1.0;
+        const double chain = std::ceil(contrib / (4.0 * rows)) * hw.mem_latency_clk;
+        l_reduce = hw.reduce_launch_clk + bytes / rate + chain;
         p->waves = whole + sk / slots;
         p->active_cu = hw.n_cu;
         p->l_compute = lc_full;

@@ -35,40 +35,61 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 
 
 // Stream-K second pass: for every stream-K tile that more than one worker contributed to,
-// sum the workers' fp32 partial tiles in worker order (deterministic), scale, round to bf16.
-// One thread per 4 consecutive n; blocks_per_tile blocks of 256 threads cover a tile.
+// sum the workers' fp32 partial tiles, scale, round to bf16.  A block of 256 threads is R
+// thread rows of 256 / R groups of 4 consecutive outputs; the rows share the contributor
+// list (row r adds contributors r, r + R, ... in worker order) and are combined through LDS
+// as a fixed binary tree.  The host picks R from the number of contributors per tile, so
+// the result depends only on the plan: deterministic.
+template <int R>
 __global__ __launch_bounds__(256) void streamk_sum_kernel(const float *__restrict__ ws, __bf16 *__restrict__ C, int M,
                                                           int N, int ldc, float alpha, int tiles_m, int tiles_n,
                                                           int group_m, SkPlan sk, int BM, int BN, int blocks_per_tile)
 {
+    constexpr int Q = 256 / R;
+    __shared__ f32x4 part[R][Q];
     const int j = blockIdx.x / blocks_per_tile;
-    const int q = (blockIdx.x % blocks_per_tile) * 256 + threadIdx.x;
-    if (j >= sk.sk_tiles || q >= BM * BN / 4)
-        return;
+    const int quad = threadIdx.x % Q, r = threadIdx.x / Q;
+    const int q = (blockIdx.x % blocks_per_tile) * Q + quad;
     int g_first, g_last;
     sk_contributors(sk, j, &g_first, &g_last);
     if (g_first == g_last)
-        return;   // one worker computed the whole tile and stored it
+        return;   // one worker computed the whole tile and stored it (uniform over the block)
     int tm, tn;
     logical_tile(tiles_m, tiles_n, group_m, sk.dp_tiles + j, tm, tn);
     const int row = q / (BN / 4), col = (q % (BN / 4)) * 4;
     const int m = tm * BM + row, n = tn * BN + col;
-    if (m >= M || n >= N)
-        return;
-    const size_t tile_elems = (size_t)BM * BN;
-    const size_t off = (size_t)row * BN + col;
-    // the first contributor's partial is its second segment unless its range starts with this
-    // tile; every later contributor's range starts inside this tile (first segment)
-    f32x4 s = *(const f32x4 *)(ws + (size_t)(2 * g_first + sk_slot_of(sk, g_first, j)) * tile_elems + off);
-    for (int g = g_first + 1; g <= g_last; ++g) {
-        f32x4 t = *(const f32x4 *)(ws + (size_t)(2 * g) * tile_elems + off);
-        s += t;
+    const bool live = q < BM * BN / 4 && m < M && n < N;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (live) {
+        const size_t tile_elems = (size_t)BM * BN;
+        const float *base = ws + (size_t)row * BN + col;
+        // the first contributor's partial is its second segment unless its range starts with
+        // this tile; every later contributor's range starts inside this tile (first segment)
+        const int slot_first = sk_slot_of(sk, g_first, j);
+#pragma unroll 4
+        for (int g = g_first + r; g <= g_last; g += R) {
+            const int slot = (g == g_first) ? slot_first : 0;
+            s += *(const f32x4 *)(base + (size_t)(2 * g + slot) * tile_elems);
+        }
     }
-    bf16x4 o;
+    if constexpr (R > 1) {
+        part[r][quad] = s;
+        __syncthreads();
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-        o[r] = (__bf16)(s[r] * alpha);
-    *(bf16x4 *)(C + (size_t)m * ldc + n) = o;
+        for (int half = R / 2; half >= 1; half /= 2) {
+            if (r < half)
+                part[r][quad] += part[r + half][quad];
+            __syncthreads();
+        }
+        s = part[0][quad];
+    }
+    if (r == 0 && live) {
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            o[e] = (__bf16)(s[e] * alpha);
+        *(bf16x4 *)(C + (size_t)m * ldc + n) = o;
+    }
 }
 
 }  // namespace g355
@@ -205,10 +226,23 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
         return GEMM_ERR_HIP;
     }
     if (cfg->stream_k) {
-        const int bpt = (v.block_m * v.block_n / 4 + 255) / 256;
+        // thread rows per output group: enough to keep one output's chain of contributors short
+        const int contributors = sk.workers / sk.sk_tiles + 2;
+        const int rows = contributors > 32 ? 8 : contributors > 8 ? 4 : 1;
+        const int quads = 256 / rows;
+        const int bpt = (v.block_m * v.block_n / 4 + quads - 1) / quads;
+        const dim3 grid((unsigned)(sk.sk_tiles * bpt)), block(256);
         (void)hipGetLastError();
-        hipLaunchKernelGGL(streamk_sum_kernel, dim3((unsigned)(sk.sk_tiles * bpt)), dim3(256), 0, stream, ws, (__bf16 *)C,
-                           a.M, a.N, a.ldc, a.alpha, a.tiles_m, a.tiles_n, a.group_m, sk, v.block_m, v.block_n, bpt);
+#define G355_SUM(R)                                                                                                   \
+    hipLaunchKernelGGL(streamk_sum_kernel<R>, grid, block, 0, stream, ws, (__bf16 *)C, a.M, a.N, a.ldc, a.alpha,      \
+                       a.tiles_m, a.tiles_n, a.group_m, sk, v.block_m, v.block_n, bpt)
+        if (rows == 8)
+            G355_SUM(8);
+        else if (rows == 4)
+            G355_SUM(4);
+        else
+            G355_SUM(1);
+#undef G355_SUM
         if (hipGetLastError() != hipSuccess)
             return GEMM_ERR_HIP;
     } else if (cfg->split_k > 1) {
