@@ -29,7 +29,7 @@
 extern "C" {
 #endif
 
-#define GEMM_ABI_VERSION 2u
+#define GEMM_ABI_VERSION 3u
 
 typedef enum gemm_dtype {
     GEMM_BF16 = 0,     /* A, B bf16 */
@@ -122,6 +122,7 @@ typedef struct gemm_cfg {
     uint16_t sk_workers;      /* stream-K workgroups G (= workgroup slots of the device for this variant); 0 when stream_k = 0 */
     float alpha;              /* default 1; the caller may overwrite it before gemm_run */
     int32_t bottleneck;       /* gemm_bottleneck of the prediction */
+    float beta;               /* default 0; C = alpha*A*B + beta*C (Section II-A).  0: C is written without being read */
     double predicted_us;      /* model's total latency for this cfg */
 } gemm_cfg;
 
@@ -163,7 +164,7 @@ int gemm_select(int64_t M, int64_t N, int64_t K, int dtype, gemm_cfg *out);
 int gemm_select_ex(int64_t M, int64_t N, int64_t K, int dtype, int b_layout, gemm_cfg *out);
 
 /*
- * Enqueue C = alpha * A * B on hip_stream (a hipStream_t; NULL = the default stream) with
+ * Enqueue C = alpha * A * B + beta * C on hip_stream (a hipStream_t; NULL = the default stream) with
  * the kernel cfg names; returns without synchronising.  A, B, C: device pointers,
  * 16-byte aligned.  When cfg->split_k > 1 or cfg->stream_k = 1 a workspace of
  * gemm_workspace_bytes(cfg) must have been registered with gemm_set_workspace for the

@@ -128,6 +128,22 @@ def gemm_samples(A, B, rows, cols, dtype=BF16, alpha=1.0):
     return C16, C64
 
 
+def accumulate(C64, beta, C_in_bits):
+    """The full definition of Section II-A, C = alpha*A*B + beta*C: C64 is the fp64 value of
+    alpha*A*B (from gemm / gemm_rows / gemm_samples), C_in_bits the bf16 bit patterns C held on
+    entry (same shape).  Returns (bf16 bits, fp64).  beta == 0 drops the term without reading
+    C_in (the BLAS convention: whatever C held, NaN included, does not propagate)."""
+    C64 = np.asarray(C64, dtype=np.float64)
+    if beta == 0.0:
+        out = C64.copy()
+    else:
+        c_in = decode_bf16(C_in_bits)
+        if c_in.shape != C64.shape:
+            raise ValueError("C_in must have the shape of the product")
+        out = C64 + float(beta) * c_in
+    return encode_bf16(out), out
+
+
 def decode_bf16(bits):
     bits = np.ascontiguousarray(bits, dtype=np.uint16)
     out = np.empty(bits.shape, np.float64)

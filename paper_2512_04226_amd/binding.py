@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("GEMM355_LIB") or os.path.join(_PKG, "libgemm355.so") 
 
 GEMM_BF16 = 0
 GEMM_FP8_E4M3 = 1
-GEMM_ABI_VERSION = 2
+GEMM_ABI_VERSION = 3
 GEMM_B_ROW_MAJOR = 0
 GEMM_B_K_CONTIGUOUS = 1
 
@@ -58,7 +58,7 @@ class gemm_cfg(ctypes.Structure):
                 ("xcd_remap", ctypes.c_uint8), ("stages", ctypes.c_uint8),
                 ("slab_clk", ctypes.c_uint16), ("b_layout", ctypes.c_uint8), ("stream_k", ctypes.c_uint8),
                 ("sk_workers", ctypes.c_uint16), ("alpha", ctypes.c_float),
-                ("bottleneck", ctypes.c_int32), ("predicted_us", ctypes.c_double)]
+                ("bottleneck", ctypes.c_int32), ("beta", ctypes.c_float), ("predicted_us", ctypes.c_double)]
 
     def describe(self):
         return ("%dx%dx%d w%dx%d mfma%d s%d %s g%d%s%s" % (

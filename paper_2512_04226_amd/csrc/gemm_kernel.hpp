@@ -28,7 +28,7 @@ struct KernelArgs {
     float *ws;     // fp32 slabs [split_k][M][N] (split_k > 1), or stream-K partial tiles
     int M, N, K;
     int lda, ldb, ldc;  // elements
-    float alpha;
+    float alpha, beta;  // C = alpha*A*B + beta*C; beta == 0: C is not read
     int tiles_m, tiles_n;
     int split_k;
     int k_per_split;    // elements, a multiple of BLOCK_K
@@ -406,7 +406,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     //      n = 8*(r/4) + 4*(lane/32) + r%4 (32x32) or n = 4*(lane/16) + r (16x16) ----
     const int out_m = m0 + wm * T::WTM + (lane % MI);
     const int out_nl = n0 + wn * T::WTN + 4 * (lane / MI);
-    const float alpha = args.alpha;
+    const float alpha = args.alpha, beta = args.beta;
 #pragma unroll
     for (int i = 0; i < T::TM; ++i) {
         const int m = out_m + i * MI;
@@ -430,11 +430,18 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                     float *dst = args.ws + ((size_t)(2 * blockIdx.x + seg) * BM + (m - m0)) * BN + (n - n0);
                     *(f32x4 *)dst = v;
                 } else {
-                    bf16x4 o;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        o[r] = (__bf16)(v[r] * alpha);
                     __bf16 *dst = (__bf16 *)args.C + (size_t)m * args.ldc + n;
+                    bf16x4 o;
+                    if (beta != 0.f) {
+                        const bf16x4 c = *(const bf16x4 *)dst;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            o[r] = (__bf16)__builtin_fmaf(beta, (float)c[r], v[r] * alpha);
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            o[r] = (__bf16)(v[r] * alpha);
+                    }
                     *(bf16x4 *)dst = o;
                 }
             }

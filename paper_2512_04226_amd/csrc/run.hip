@@ -12,8 +12,25 @@ using namespace g355;
 
 namespace g355 {
 // Sum the split-K slabs in slice order (deterministic), scale, round to bf16.
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ ws, __bf16 *__restrict__ C, int M,
-                                                            int N, int ldc, int split_k, float alpha)
+// beta != 0 adds beta * C (read before it is overwritten).
+__device__ inline bf16x4 scale_round(f32x4 s, float alpha, float beta, const __bf16 *dst)
+{
+    bf16x4 o;
+    if (beta != 0.f) {
+        const bf16x4 c = *(const bf16x4 *)dst;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            o[r] = (__bf16)__builtin_fmaf(beta, (float)c[r], s[r] * alpha);
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            o[r] = (__bf16)(s[r] * alpha);
+    }
+    return o;
+}
+
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ ws, __bf16 *C, int M, int N, int ldc,
+                                                            int split_k, float alpha, float beta)
 {
     const size_t quads = (size_t)M * (N / 4);
     const size_t slab = (size_t)M * N;
@@ -25,11 +42,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
             f32x4 t = *(const f32x4 *)(p + k * slab);
             s += t;
         }
-        bf16x4 o;
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-            o[r] = (__bf16)(s[r] * alpha);
-        *(bf16x4 *)(C + m * ldc + n) = o;
+        *(bf16x4 *)(C + m * ldc + n) = scale_round(s, alpha, beta, C + m * ldc + n);
     }
 }
 
@@ -41,8 +54,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 // as a fixed binary tree.  The host picks R from the number of contributors per tile, so
 // the result depends only on the plan: deterministic.
 template <int R>
-__global__ __launch_bounds__(256) void streamk_sum_kernel(const float *__restrict__ ws, __bf16 *__restrict__ C, int M,
-                                                          int N, int ldc, float alpha, int tiles_m, int tiles_n,
+__global__ __launch_bounds__(256) void streamk_sum_kernel(const float *__restrict__ ws, __bf16 *C, int M, int N, int ldc,
+                                                          float alpha, float beta, int tiles_m, int tiles_n,
                                                           int group_m, SkPlan sk, int BM, int BN, int blocks_per_tile)
 {
     constexpr int Q = 256 / R;
@@ -83,13 +96,8 @@ __global__ __launch_bounds__(256) void streamk_sum_kernel(const float *__restric
         }
         s = part[0][quad];
     }
-    if (r == 0 && live) {
-        bf16x4 o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            o[e] = (__bf16)(s[e] * alpha);
-        *(bf16x4 *)(C + (size_t)m * ldc + n) = o;
-    }
+    if (r == 0 && live)
+        *(bf16x4 *)(C + (size_t)m * ldc + n) = scale_round(s, alpha, beta, C + (size_t)m * ldc + n);
 }
 
 }  // namespace g355
@@ -211,6 +219,7 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
     a.ldb = (int)cfg->ldb;
     a.ldc = (int)cfg->ldc;
     a.alpha = cfg->alpha;
+    a.beta = cfg->beta;
     a.tiles_m = (int)tiles_m;
     a.tiles_n = (int)tiles_n;
     a.split_k = cfg->split_k;
@@ -235,7 +244,7 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
         (void)hipGetLastError();
 #define G355_SUM(R)                                                                                                   \
     hipLaunchKernelGGL(streamk_sum_kernel<R>, grid, block, 0, stream, ws, (__bf16 *)C, a.M, a.N, a.ldc, a.alpha,      \
-                       a.tiles_m, a.tiles_n, a.group_m, sk, v.block_m, v.block_n, bpt)
+                       a.beta, a.tiles_m, a.tiles_n, a.group_m, sk, v.block_m, v.block_n, bpt)
         if (rows == 8)
             G355_SUM(8);
         else if (rows == 4)
@@ -252,7 +261,7 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
             blocks = 256 * 8;
         (void)hipGetLastError();
         hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, ws, (__bf16 *)C, a.M,
-                           a.N, a.ldc, a.split_k, a.alpha);
+                           a.N, a.ldc, a.split_k, a.alpha, a.beta);
         if (hipGetLastError() != hipSuccess)
             return GEMM_ERR_HIP;
     }

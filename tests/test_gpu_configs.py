@@ -257,3 +257,61 @@ def test_k_contiguous_b_square_4096(g, oracle):
     max_a = float(np.abs(wl.bf16_bits_to_f32(A)).max())
     max_b = float(np.abs(wl.bf16_bits_to_f32(B)).max())
     assert np.max(np.abs(bf16_to_f64(out[rows]) - ref64)) <= oracle.tolerance(n, max_a, max_b, BF16)
+
+
+# ---------------- C = alpha*A*B + beta*C (Section II-A's full definition) ----------------
+
+def test_beta_accumulates_into_c_bit_exact_on_every_path(g, oracle):
+    """Integer operands and power-of-two scalars: exact in fp32, so data-parallel, split-K and
+    Stream-K epilogues must all reproduce the oracle's alpha*A*B + beta*C_in bit for bit."""
+    from gpu_util import to_dev, workspace_for
+    M, N, K = 520, 776, 1024
+    A, B = wl.integer_bf16(M, N, K, seed=51, case=3)
+    gen = np.random.default_rng(52)
+    Cin = oracle.encode_bf16(gen.integers(-64, 65, size=(M, N)).astype(np.float64))
+    _, prod = oracle.gemm(A, B, BF16, alpha=0.5)
+    ref16, _ = oracle.accumulate(prod, -2.0, Cin)
+    dA, dB = to_dev(A), to_dev(B)
+    seen = set()
+    for idx in range(g.gemm_cfg_count(BF16)):
+        c = g.gemm_cfg_at(idx, M, N, K, BF16)
+        if c is None:
+            continue
+        path = "streamk" if c.stream_k else ("splitk" if c.split_k > 1 else "dp")
+        if c.split_k > 4:
+            continue
+        c.alpha, c.beta = 0.5, -2.0
+        workspace_for(c)
+        dC = to_dev(Cin).clone()
+        g.gemm_run(c, dA, dB, dC)
+        torch.cuda.synchronize()
+        out = dC.cpu().numpy().view(np.uint16)
+        assert np.array_equal(out, ref16), (c.describe(), int((out != ref16).sum()))
+        seen.add(path)
+    assert seen == {"dp", "splitk", "streamk"}
+
+
+def test_beta_random_data_padded_ldc_within_tolerance(g, oracle):
+    from gpu_util import bf16_to_f64, to_dev, workspace_for
+    M, N, K = 1000, 1512, 2048
+    A, B = wl.config2(2048)
+    A, B = np.ascontiguousarray(A[:M, :K]), np.ascontiguousarray(B[:K, :N])
+    gen = np.random.default_rng(53)
+    Cin = wl.f32_to_bf16_bits(gen.standard_normal((M, N), dtype=np.float32) * 30.0)
+    alpha, beta = 0.75, 1.25
+    _, prod = oracle.gemm(A, B, BF16, alpha=alpha)
+    _, ref64 = oracle.accumulate(prod, beta, Cin)
+    # the north-star bound on the product, plus the rounding of the beta*C term in fp32 and bf16
+    tol = oracle.tolerance(K, float(np.abs(bf16_to_f64(A)).max()), float(np.abs(bf16_to_f64(B)).max()), BF16)
+    ldc = N + 24
+    Cp = np.full((M, ldc), 0x1234, np.uint16)
+    Cp[:, :N] = Cin
+    c = g.gemm_select(M, N, K, BF16)
+    c.ldc, c.alpha, c.beta = ldc, alpha, beta
+    workspace_for(c)
+    dC = to_dev(Cp)
+    g.gemm_run(c, to_dev(A), to_dev(B), dC)
+    torch.cuda.synchronize()
+    out = dC.cpu().numpy().view(np.uint16)
+    assert np.abs(bf16_to_f64(out[:, :N]) - ref64).max() <= tol
+    assert np.all(out[:, N:] == 0x1234)

@@ -275,3 +275,32 @@ def test_empty_and_bad_arguments(oracle):
 def test_tolerance_formula(oracle):
     assert oracle.tolerance(4096, 2.0, 0.5, BF16) == pytest.approx(1e-2 * 64 * 1.0)
     assert oracle.tolerance(64, 448.0, 448.0, E4M3) == pytest.approx(5e-2 * 8 * 448 * 448)
+
+
+def test_accumulate_into_c_closed_forms(oracle):
+    """C = alpha*A*B + beta*C (Section II-A).  With A = I the product is B, so the result is the
+    elementwise alpha*B + beta*C_in, exact on small integers; beta = 0 must not read C_in."""
+    n = 48
+    gen = np.random.default_rng(11)
+    Bv = gen.integers(-8, 9, size=(n, n)).astype(np.float64)
+    Cv = gen.integers(-8, 9, size=(n, n)).astype(np.float64)
+    I = oracle.encode_bf16(np.eye(n))
+    B, Cin = oracle.encode_bf16(Bv), oracle.encode_bf16(Cv)
+    _, prod = oracle.gemm(I, B, BF16, alpha=0.5)
+    c16, c64 = oracle.accumulate(prod, -2.0, Cin)
+    assert np.array_equal(c64, 0.5 * Bv - 2.0 * Cv)
+    assert np.array_equal(oracle.decode_bf16(c16), 0.5 * Bv - 2.0 * Cv)
+    # beta = 1 on a rank-1 product: u v^T + C
+    u = gen.integers(-3, 4, size=(n, 1)).astype(np.float64)
+    v = gen.integers(-3, 4, size=(1, n)).astype(np.float64)
+    _, prod = oracle.gemm(oracle.encode_bf16(u), oracle.encode_bf16(v), BF16)
+    _, c64 = oracle.accumulate(prod, 1.0, Cin)
+    assert np.array_equal(c64, u @ v + Cv)
+    # beta = 0: NaN in C_in does not propagate and C_in is not even decoded
+    nan = np.full((n, n), 0x7FC0, np.uint16)
+    c16, c64 = oracle.accumulate(prod, 0.0, nan)
+    assert np.array_equal(c64, u @ v) and not np.isnan(oracle.decode_bf16(c16)).any()
+    c16, c64 = oracle.accumulate(prod, 1.0, nan)
+    assert np.isnan(c64).all()
+    with pytest.raises(ValueError):
+        oracle.accumulate(prod, 1.0, nan[:4])
