@@ -8,11 +8,13 @@
  * What it computes: the paper's Section II-A definition C = alpha*A*B + beta*C
  * with beta = 0, evaluated exactly as the paper's Algorithm 1 states it -- for
  * every output element, a running sum over the reduction index in ascending
- * order -- in fp64.  Inputs are bf16 or OCP fp8 e4m3 ("e4m3fn": 1-4-3, bias 7,
- * no infinities, S.1111.111 is NaN, largest finite 448) bit patterns decoded
- * exactly; a product of two such values is exact in fp64, so the only rounding
- * is the fp64 accumulation (relative error <= K * 2^-53) and the final
- * round-to-nearest-even to bf16.
+ * order -- in fp64.  Inputs are bf16, IEEE binary16 ("fp16": 1-5-10, bias 15;
+ * the precision of the paper's own runs, Section V) or OCP fp8 e4m3 ("e4m3fn":
+ * 1-4-3, bias 7, no infinities, S.1111.111 is NaN, largest finite 448) bit
+ * patterns decoded exactly; a product of two such values is exact in fp64, so
+ * the only rounding is the fp64 accumulation (relative error <= K * 2^-53) and
+ * the final round-to-nearest-even to the output format: bf16, or fp16 when the
+ * inputs are fp16.
  *
  * Pins (tests/test_oracle_*.py): identity, permutations, rank-1 closed forms,
  * exact small-integer sums against an integer-only computation, codec
@@ -26,6 +28,7 @@
 
 #define ORACLE_BF16 0
 #define ORACLE_E4M3 1
+#define ORACLE_FP16 2
 
 /* ---- decoders: bit pattern -> exact fp64 value (from the format definitions) ---- */
 
@@ -41,6 +44,22 @@ double oracle_bf16_to_f64(uint16_t bits)
         v = ldexp((double)m, -126 - 7);          /* subnormal: m * 2^-133 */
     else
         v = ldexp((double)(128 + m), e - 127 - 7); /* (1 + m/128) * 2^(e-127) */
+    return sign ? -v : v;
+}
+
+/* IEEE 754 binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits. */
+double oracle_fp16_to_f64(uint16_t bits)
+{
+    int sign = bits >> 15;
+    int e = (bits >> 10) & 0x1F;
+    int m = bits & 0x3FF;
+    double v;
+    if (e == 0x1F)
+        v = m ? NAN : INFINITY;
+    else if (e == 0)
+        v = ldexp((double)m, -14 - 10);            /* subnormal: m * 2^-24 */
+    else
+        v = ldexp((double)(1024 + m), e - 15 - 10); /* (1 + m/1024) * 2^(e-15) */
     return sign ? -v : v;
 }
 
@@ -96,6 +115,29 @@ uint16_t oracle_f64_to_bf16(double x)
     return sign | (uint16_t)(u >> 16);
 }
 
+/* fp64 -> binary16, round-to-nearest-even; what rounds to 2^16 or beyond becomes infinity. */
+uint16_t oracle_f64_to_fp16(double x)
+{
+    uint16_t sign = signbit(x) ? 0x8000u : 0;
+    if (isnan(x))
+        return 0x7E00u;
+    double ax = fabs(x);
+    if (isinf(ax))
+        return sign | 0x7C00u;
+    double r = round_to_format(ax, 10, -14);
+    if (r >= 65536.0)
+        return sign | 0x7C00u;
+    if (r == 0.0)
+        return sign;
+    int ex;
+    double f = frexp(r, &ex);     /* r = f * 2^ex, f in [0.5, 1) */
+    int e = ex - 1;
+    if (e < -14)                  /* subnormal: r = m * 2^-24 */
+        return sign | (uint16_t)ldexp(r, 24);
+    int m = (int)ldexp(f, 11) - 1024;   /* 2f in [1,2): 2f = 1 + m/1024 */
+    return sign | (uint16_t)(((e + 15) << 10) | m);
+}
+
 /* fp64 -> e4m3fn, round-to-nearest-even, magnitudes beyond 448 saturate to 448. */
 uint8_t oracle_f64_to_e4m3(double x)
 {
@@ -121,6 +163,7 @@ uint8_t oracle_f64_to_e4m3(double x)
 
 /* Value tables filled once from the two decoders above (every code of each format). */
 static double bf16_table[65536];
+static double fp16_table[65536];
 static double e4m3_table[256];
 static int tables_ready = 0;
 
@@ -130,6 +173,8 @@ static void fill_tables(void)
         return;
     for (int c = 0; c < 65536; ++c)
         bf16_table[c] = oracle_bf16_to_f64((uint16_t)c);
+    for (int c = 0; c < 65536; ++c)
+        fp16_table[c] = oracle_fp16_to_f64((uint16_t)c);
     for (int c = 0; c < 256; ++c)
         e4m3_table[c] = oracle_e4m3_to_f64((uint8_t)c);
     tables_ready = 1;
@@ -139,20 +184,30 @@ static inline double decode(const void *p, int64_t idx, int dtype)
 {
     if (dtype == ORACLE_BF16)
         return bf16_table[((const uint16_t *)p)[idx]];
+    if (dtype == ORACLE_FP16)
+        return fp16_table[((const uint16_t *)p)[idx]];
     return e4m3_table[((const uint8_t *)p)[idx]];
+}
+
+static inline int known_dtype(int dtype) { return dtype == ORACLE_BF16 || dtype == ORACLE_E4M3 || dtype == ORACLE_FP16; }
+
+/* The 16-bit output code: fp16 for fp16 inputs, bf16 otherwise. */
+static inline uint16_t encode_out(double c, int dtype)
+{
+    return dtype == ORACLE_FP16 ? oracle_f64_to_fp16(c) : oracle_f64_to_bf16(c);
 }
 
 /*
  * Algorithm 1 verbatim in structure: i, then j, then the reduction index
  * ascending.  A is M x K row-major (leading dimension lda), B is K x N
  * row-major (ldb).  Writes alpha * sum as fp64 (C64, ld = N, may be NULL) and
- * its bf16 rounding (C16, ld = ldc, may be NULL).  Returns 0, or -1 on bad
+ * its rounding to the 16-bit output format (C16, ld = ldc, may be NULL).  Returns 0, or -1 on bad
  * arguments.
  */
 int oracle_gemm_alg1(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                      int64_t ldb, int dtype, double alpha, uint16_t *C16, int64_t ldc, double *C64)
 {
-    if (M < 0 || N < 0 || K < 0 || (dtype != ORACLE_BF16 && dtype != ORACLE_E4M3))
+    if (M < 0 || N < 0 || K < 0 || !known_dtype(dtype))
         return -1;
     fill_tables();
     for (int64_t i = 0; i < M; ++i)
@@ -164,7 +219,7 @@ int oracle_gemm_alg1(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda
             if (C64)
                 C64[i * N + j] = c;
             if (C16)
-                C16[i * ldc + j] = oracle_f64_to_bf16(c);
+                C16[i * ldc + j] = encode_out(c, dtype);
         }
     return 0;
 }
@@ -178,7 +233,7 @@ int oracle_gemm_alg1(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda
 int oracle_gemm(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                 int64_t ldb, int dtype, double alpha, uint16_t *C16, int64_t ldc, double *C64)
 {
-    if (M < 0 || N < 0 || K < 0 || (dtype != ORACLE_BF16 && dtype != ORACLE_E4M3))
+    if (M < 0 || N < 0 || K < 0 || !known_dtype(dtype))
         return -1;
     fill_tables();
     int failed = 0;
@@ -208,7 +263,7 @@ int oracle_gemm(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, con
                 if (C64)
                     C64[i * N + j] = c;
                 if (C16)
-                    C16[i * ldc + j] = oracle_f64_to_bf16(c);
+                    C16[i * ldc + j] = encode_out(c, dtype);
             }
         }
         free(acc);
@@ -226,7 +281,7 @@ int oracle_gemm_rows(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda
                      int64_t ldb, int dtype, double alpha, int64_t n_rows, const int64_t *rows,
                      uint16_t *C16, double *C64)
 {
-    if (M < 0 || N < 0 || K < 0 || n_rows < 0 || (dtype != ORACLE_BF16 && dtype != ORACLE_E4M3))
+    if (M < 0 || N < 0 || K < 0 || n_rows < 0 || !known_dtype(dtype))
         return -1;
     for (int64_t r = 0; r < n_rows; ++r)
         if (rows[r] < 0 || rows[r] >= M)
@@ -257,7 +312,7 @@ int oracle_gemm_rows(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda
                 if (C64)
                     C64[r * N + j] = c;
                 if (C16)
-                    C16[r * N + j] = oracle_f64_to_bf16(c);
+                    C16[r * N + j] = encode_out(c, dtype);
             }
         }
         free(acc);
@@ -270,7 +325,7 @@ int oracle_gemm_samples(int64_t M, int64_t N, int64_t K, const void *A, int64_t 
                         int64_t ldb, int dtype, double alpha, int64_t n, const int64_t *rows,
                         const int64_t *cols, uint16_t *C16, double *C64)
 {
-    if (M < 0 || N < 0 || K < 0 || n < 0 || (dtype != ORACLE_BF16 && dtype != ORACLE_E4M3))
+    if (M < 0 || N < 0 || K < 0 || n < 0 || !known_dtype(dtype))
         return -1;
     for (int64_t s = 0; s < n; ++s)
         if (rows[s] < 0 || rows[s] >= M || cols[s] < 0 || cols[s] >= N)
@@ -285,7 +340,7 @@ int oracle_gemm_samples(int64_t M, int64_t N, int64_t K, const void *A, int64_t 
         if (C64)
             C64[s] = c;
         if (C16)
-            C16[s] = oracle_f64_to_bf16(c);
+            C16[s] = encode_out(c, dtype);
     }
     return 0;
 }
@@ -295,6 +350,16 @@ void oracle_decode_bf16(int64_t n, const uint16_t *in, double *out)
 {
     for (int64_t i = 0; i < n; ++i)
         out[i] = oracle_bf16_to_f64(in[i]);
+}
+void oracle_decode_fp16(int64_t n, const uint16_t *in, double *out)
+{
+    for (int64_t i = 0; i < n; ++i)
+        out[i] = oracle_fp16_to_f64(in[i]);
+}
+void oracle_encode_fp16(int64_t n, const double *in, uint16_t *out)
+{
+    for (int64_t i = 0; i < n; ++i)
+        out[i] = oracle_f64_to_fp16(in[i]);
 }
 void oracle_decode_e4m3(int64_t n, const uint8_t *in, double *out)
 {

@@ -1,10 +1,10 @@
 """ctypes front end of the CPU GEMM oracle (TEST INFRASTRUCTURE ONLY).
 
 Wraps oracle/gemm_oracle.c: Algorithm 1 of the paper (Section II-A) in fp64 with the
-result rounded once to bf16.  Nothing under the product package imports this module;
+result rounded once to the 16-bit output format (bf16; fp16 for fp16 inputs).  Nothing under the product package imports this module;
 it is for tests, the smoke check and the bench's cpu_baseline leg.
 
-Arrays are numpy: bf16 as uint16 bit patterns, e4m3 as uint8 bit patterns.
+Arrays are numpy: bf16 and fp16 as uint16 bit patterns, e4m3 as uint8 bit patterns.
 """
 import ctypes
 import os
@@ -14,6 +14,7 @@ import numpy as np
 
 BF16 = 0
 E4M3 = 1
+FP16 = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gemm_oracle.c")
@@ -46,7 +47,8 @@ def _load():
     lib.oracle_gemm_rows.argtypes = [i64, i64, i64, vp, i64, vp, i64, ci, dbl, i64, vp, vp, vp]
     lib.oracle_gemm_samples.restype = ci
     lib.oracle_gemm_samples.argtypes = [i64, i64, i64, vp, i64, vp, i64, ci, dbl, i64, vp, vp, vp, vp]
-    for name in ("oracle_decode_bf16", "oracle_decode_e4m3", "oracle_encode_bf16", "oracle_encode_e4m3"):
+    for name in ("oracle_decode_bf16", "oracle_decode_e4m3", "oracle_encode_bf16", "oracle_encode_e4m3",
+                 "oracle_decode_fp16", "oracle_encode_fp16"):
         f = getattr(lib, name)
         f.restype = None
         f.argtypes = [i64, vp, vp]
@@ -55,11 +57,11 @@ def _load():
 
 
 def _in_dtype(dtype):
-    if dtype == BF16:
+    if dtype in (BF16, FP16):
         return np.uint16
     if dtype == E4M3:
         return np.uint8
-    raise ValueError("dtype must be BF16 (0) or E4M3 (1)")
+    raise ValueError("dtype must be BF16 (0), E4M3 (1) or FP16 (2)")
 
 
 def _check_operands(A, B, dtype):
@@ -128,20 +130,20 @@ def gemm_samples(A, B, rows, cols, dtype=BF16, alpha=1.0):
     return C16, C64
 
 
-def accumulate(C64, beta, C_in_bits):
+def accumulate(C64, beta, C_in_bits, dtype=BF16):
     """The full definition of Section II-A, C = alpha*A*B + beta*C: C64 is the fp64 value of
-    alpha*A*B (from gemm / gemm_rows / gemm_samples), C_in_bits the bf16 bit patterns C held on
-    entry (same shape).  Returns (bf16 bits, fp64).  beta == 0 drops the term without reading
+    alpha*A*B (from gemm / gemm_rows / gemm_samples), C_in_bits the 16-bit codes C held on
+    entry (same shape; fp16 when dtype is FP16, else bf16).  Returns (16-bit codes, fp64).  beta == 0 drops the term without reading
     C_in (the BLAS convention: whatever C held, NaN included, does not propagate)."""
     C64 = np.asarray(C64, dtype=np.float64)
     if beta == 0.0:
         out = C64.copy()
     else:
-        c_in = decode_bf16(C_in_bits)
+        c_in = decode_out(C_in_bits, dtype)
         if c_in.shape != C64.shape:
             raise ValueError("C_in must have the shape of the product")
         out = C64 + float(beta) * c_in
-    return encode_bf16(out), out
+    return (encode_fp16(out) if dtype == FP16 else encode_bf16(out)), out
 
 
 def decode_bf16(bits):
@@ -158,8 +160,27 @@ def decode_e4m3(bits):
     return out
 
 
+def decode_fp16(bits):
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    out = np.empty(bits.shape, np.float64)
+    _load().oracle_decode_fp16(bits.size, _ptr(bits), _ptr(out))
+    return out
+
+
+def encode_fp16(x):
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    out = np.empty(x.shape, np.uint16)
+    _load().oracle_encode_fp16(x.size, _ptr(x), _ptr(out))
+    return out
+
+
 def decode(bits, dtype):
-    return decode_bf16(bits) if dtype == BF16 else decode_e4m3(bits)
+    return {BF16: decode_bf16, E4M3: decode_e4m3, FP16: decode_fp16}[dtype](bits)
+
+
+def decode_out(bits, dtype):
+    """Value of 16-bit output codes: fp16 for fp16 inputs, bf16 otherwise."""
+    return decode_fp16(bits) if dtype == FP16 else decode_bf16(bits)
 
 
 def encode_bf16(x):
@@ -177,6 +198,9 @@ def encode_e4m3(x):
 
 
 def tolerance(K, max_abs_a, max_abs_b, dtype=BF16):
-    """Acceptance bound on max|C - C_ref| for random data: 1e-2 (bf16) or 5e-2 (e4m3)
-    times sqrt(K) * max|A| * max|B|, with the maxima taken on the real-valued operands."""
-    return (1e-2 if dtype == BF16 else 5e-2) * np.sqrt(float(K)) * float(max_abs_a) * float(max_abs_b)
+    """Acceptance bound on max|C - C_ref| for random data: 1e-2 (bf16), 5e-2 (e4m3) or 2e-3
+    (fp16: the output carries 11 significant bits against bf16's 8, so the bf16 bound shrinks by
+    2^3, rounded up) times sqrt(K) * max|A| * max|B|, with the maxima taken on the real-valued
+    operands."""
+    factor = {BF16: 1e-2, E4M3: 5e-2, FP16: 2e-3}[dtype]
+    return factor * np.sqrt(float(K)) * float(max_abs_a) * float(max_abs_b)

@@ -304,3 +304,64 @@ def test_accumulate_into_c_closed_forms(oracle):
     assert np.isnan(c64).all()
     with pytest.raises(ValueError):
         oracle.accumulate(prod, 1.0, nan[:4])
+
+
+FP16 = 2
+
+
+def test_fp16_codec_every_code_against_numpy_half(oracle):
+    """binary16 decode of all 65536 codes and encode of many doubles against numpy's float16,
+    an independent implementation of the same IEEE format."""
+    codes = np.arange(65536, dtype=np.uint16)
+    got = oracle.decode_fp16(codes)
+    with np.errstate(invalid="ignore"):
+        ref = codes.view(np.float16).astype(np.float64)
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan) and np.array_equal(got[~nan], ref[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(ref[~nan]))
+    # every finite code survives a round trip
+    assert np.array_equal(oracle.encode_fp16(got[~nan]), codes[~nan])
+    gen = np.random.default_rng(12)
+    x = np.concatenate([gen.standard_normal(200000) * 10.0 ** gen.integers(-9, 6, 200000),
+                        [0.0, -0.0, 65504.0, 65519.999, 65520.0, 1e9, -1e9, np.inf, -np.inf,
+                         2.0 ** -24, 2.0 ** -25, 1.5 * 2.0 ** -25, 2.0 ** -14, 2.0 ** -14 - 2.0 ** -25]])
+    # midpoints between neighbouring codes: ties must go to the even code
+    lo = gen.integers(0, 0x7BFF, 20000).astype(np.uint16)
+    mids = (oracle.decode_fp16(lo) + oracle.decode_fp16(lo + 1)) / 2.0
+    x = np.concatenate([x, mids, -mids])
+    with np.errstate(over="ignore"):
+        ref = x.astype(np.float16).view(np.uint16)
+    assert np.array_equal(oracle.encode_fp16(x), ref)
+    assert oracle.encode_fp16(np.array([np.nan]))[0] & 0x7C00 == 0x7C00 and oracle.encode_fp16(np.array([np.nan]))[0] & 0x3FF
+
+
+def test_fp16_gemm_closed_forms_and_literal_loop(oracle):
+    n = 40
+    gen = np.random.default_rng(13)
+    X = gen.integers(-20, 21, size=(n, n)).astype(np.float64) / 8.0       # exact in fp16
+    Xh = oracle.encode_fp16(X)
+    I = oracle.encode_fp16(np.eye(n))
+    c16, c64 = oracle.gemm(I, Xh, FP16)
+    assert np.array_equal(c16, Xh) and np.array_equal(c64, X)            # output codes are fp16, not bf16
+    P = np.eye(n)[gen.permutation(n)]
+    c16, c64 = oracle.gemm(oracle.encode_fp16(P), Xh, FP16, alpha=2.0)
+    assert np.array_equal(c64, 2.0 * (P @ X)) and np.array_equal(oracle.decode_fp16(c16), 2.0 * (P @ X))
+    u = gen.integers(-6, 7, size=(n, 1)).astype(np.float64)
+    v = gen.integers(-6, 7, size=(1, n)).astype(np.float64)
+    _, c64 = oracle.gemm(oracle.encode_fp16(u), oracle.encode_fp16(v), FP16)
+    assert np.array_equal(c64, u @ v)
+    A = gen.standard_normal((17, 33)).astype(np.float16).view(np.uint16)
+    B = gen.standard_normal((33, 24)).astype(np.float16).view(np.uint16)
+    a16, a64 = oracle.gemm(A, B, FP16, alpha=0.375, literal=True)
+    b16, b64 = oracle.gemm(A, B, FP16, alpha=0.375)
+    assert np.array_equal(a16, b16) and np.array_equal(a64, b64)
+    ref = 0.375 * (A.view(np.float16).astype(np.float64) @ B.view(np.float16).astype(np.float64))
+    assert np.max(np.abs(a64 - ref)) <= 1e-12
+    r16, r64 = oracle.gemm_rows(A, B, np.array([0, 16]), FP16, alpha=0.375)
+    assert np.array_equal(r16, a16[[0, 16]])
+    s16, _ = oracle.gemm_samples(A, B, np.array([3, 9]), np.array([5, 23]), FP16, alpha=0.375)
+    assert np.array_equal(s16, a16[[3, 9], [5, 23]])
+    # a sum that overflows binary16 becomes infinity in the code and stays finite in fp64
+    big = oracle.encode_fp16(np.full((1, 8), 200.0))
+    c16, c64 = oracle.gemm(big, big.T.copy(), FP16)
+    assert c64[0, 0] == 320000.0 and c16[0, 0] == 0x7C00
