@@ -159,6 +159,14 @@ def main():
     us = timed_us(cfg_kc, dev[n_big][0], dBt, dev[n_big][2])
     also["bf16_%d_b_k_contiguous" % n_big] = {"tflops": 2.0 * n_big ** 3 / us * 1e-6, "picked": cfg_kc.describe()}
     del dBt
+    # the paper's own precision and layout (Section V): fp16 in / fp16 out, both operands K-contiguous
+    Ah, Bh = wl.normal_fp16(n_big, n_big, n_big, seed=1)
+    dAh = torch.from_numpy(Ah.view(np.int16)).cuda()
+    dBh = torch.from_numpy(np.ascontiguousarray(Bh.T).view(np.int16)).cuda()
+    cfg_h = g.gemm_select_ex(n_big, n_big, n_big, g.GEMM_FP16, g.GEMM_B_K_CONTIGUOUS)
+    us = timed_us(cfg_h, dAh, dBh, dev[n_big][2])
+    also["fp16_%d_b_k_contiguous" % n_big] = {"tflops": 2.0 * n_big ** 3 / us * 1e-6, "picked": cfg_h.describe()}
+    del Ah, Bh, dAh, dBh
     scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
     also["mfma_only_bf16_tflops"] = g.gemm_probe_mfma(g.GEMM_BF16, 32, scratch)
     n8 = 8192

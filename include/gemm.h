@@ -32,8 +32,10 @@ extern "C" {
 #define GEMM_ABI_VERSION 3u
 
 typedef enum gemm_dtype {
-    GEMM_BF16 = 0,     /* A, B bf16 */
-    GEMM_FP8_E4M3 = 1  /* A, B one byte per element, OCP e4m3fn (max finite 448) */
+    GEMM_BF16 = 0,     /* A, B bf16; C bf16 */
+    GEMM_FP8_E4M3 = 1, /* A, B one byte per element, OCP e4m3fn (max finite 448); C bf16 */
+    GEMM_FP16 = 2      /* A, B IEEE binary16 (the precision of the paper's runs, Section V); C binary16.
+                          Same tile list, calibration constants and model row as bf16. */
 } gemm_dtype;
 
 typedef enum gemm_b_layout {

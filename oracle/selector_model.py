@@ -149,14 +149,16 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0):
     B row-major K x N, 1 = B stored K-contiguous (then v["slab_clk"] is that layout's constant);
     stream_k = 1 prices the hybrid Stream-K split of the last partial wave (needs split_k = 1).
     Returns a dict with the names of the C ABI's gemm_prediction plus group_m."""
-    es = 2 if dtype == 0 else 1
+    # dtype 0 bf16, 1 fp8 e4m3, 2 fp16.  READING: fp16 shares bf16's instruction shapes and rates.
+    row = 1 if dtype == 1 else 0
+    es = 1 if dtype == 1 else 2
     mi = v["mfma"]
-    mi_k = {(0, 32): 16, (0, 16): 32, (1, 32): 64, (1, 16): 128}[(dtype, mi)]
+    mi_k = {(0, 32): 16, (0, 16): 32, (1, 32): 64, (1, 16): 128}[(row, mi)]
     waves_wg = v["waves_m"] * v["waves_n"]
     out = {}
 
     # Algorithm 3 (count, and latency at full utilisation spread over the workgroup's SIMDs)
-    l_mi = hw["l_mi_clk"][dtype][0 if mi == 32 else 1]
+    l_mi = hw["l_mi_clk"][row][0 if mi == 32 else 1]
     n_mi, l_mt = alg3_compute_latency(mi, mi, mi_k, v["block_m"], v["block_n"], v["block_k"], l_mi)
     out["n_mi"] = n_mi
     out["l_mt_ideal"] = l_mt / min(hw["simd_per_cu"], waves_wg)

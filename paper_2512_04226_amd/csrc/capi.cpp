@@ -11,7 +11,7 @@ using namespace g355;
 namespace g355 {
 int check_problem(int64_t M, int64_t N, int64_t K, int dtype)
 {
-    if (dtype != GEMM_BF16 && dtype != GEMM_FP8_E4M3)
+    if (dtype != GEMM_BF16 && dtype != GEMM_FP8_E4M3 && dtype != GEMM_FP16)
         return GEMM_ERR_DTYPE;
     if (M < 1 || N < 1 || K < 1)
         return GEMM_ERR_SHAPE;
@@ -58,7 +58,7 @@ const char *gemm_strerror(int status)
 
 int gemm_cfg_count(int dtype)
 {
-    if (dtype != GEMM_BF16 && dtype != GEMM_FP8_E4M3)
+    if (dtype != GEMM_BF16 && dtype != GEMM_FP8_E4M3 && dtype != GEMM_FP16)
         return GEMM_ERR_DTYPE;
     return variant_count(dtype) * kNumSplits;
 }

@@ -24,7 +24,7 @@ namespace g355 {
 struct KernelArgs {
     const void *A;
     const void *B;
-    void *C;       // bf16 output
+    void *C;       // bf16 (fp16 for fp16 inputs) output
     float *ws;     // fp32 slabs [split_k][M][N] (split_k > 1), or stream-K partial tiles
     int M, N, K;
     int lda, ldb, ldc;  // elements
@@ -47,6 +47,8 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
@@ -54,9 +56,13 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 // BL_: storage of B.  0: K x N row-major (N-contiguous).  1: N x K row-major (K-contiguous, the
 // layout of the paper's own runs, Section V): B is then staged and read exactly like A.
-template <int ES_, int BM_, int BN_, int BK_, int WM_, int WN_, int MI_, int NS_, int BL_>
+// FT_ (16-bit inputs only): 0 bf16 in / bf16 out, 1 IEEE fp16 in / fp16 out (the precision of the
+// paper's runs); the data path is the same, only the MFMA instruction and the output rounding differ.
+template <int ES_, int BM_, int BN_, int BK_, int WM_, int WN_, int MI_, int NS_, int BL_, int FT_ = 0>
 struct Tile {
     static constexpr int ES = ES_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MI = MI_, NS = NS_, BL = BL_;
+    static constexpr int FT = FT_;
+    static_assert(FT == 0 || ES == 2, "fp16 is a 16-bit input type");
     static constexpr int NW = WM * WN;
     static constexpr int NT = WM * WN * 64;
     static constexpr int WTM = BM / WM, WTN = BN / WN;      // wave tile
@@ -336,7 +342,13 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     };
     constexpr int NF = T::TM + T::TN;     // fragments per k-step
     auto mma_one = [&](int buf, int j, int i) {
-        if constexpr (ES == 2 && MI == 32)
+        if constexpr (ES == 2 && T::FT == 1 && MI == 32)
+            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, bfr[buf][j]),
+                                                               __builtin_bit_cast(f16x8, af[buf][i]), acc[j][i], 0, 0, 0);
+        else if constexpr (ES == 2 && T::FT == 1)
+            acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, bfr[buf][j]),
+                                                               __builtin_bit_cast(f16x8, af[buf][i]), acc[j][i], 0, 0, 0);
+        else if constexpr (ES == 2 && MI == 32)
             acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[buf][j], af[buf][i], acc[j][i], 0, 0, 0);
         else if constexpr (ES == 2)
             acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[buf][j], af[buf][i], acc[j][i], 0, 0, 0);
@@ -430,19 +442,21 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                     float *dst = args.ws + ((size_t)(2 * blockIdx.x + seg) * BM + (m - m0)) * BN + (n - n0);
                     *(f32x4 *)dst = v;
                 } else {
-                    __bf16 *dst = (__bf16 *)args.C + (size_t)m * args.ldc + n;
-                    bf16x4 o;
+                    typedef typename std::conditional<T::FT == 1, _Float16, __bf16>::type out_t;
+                    typedef typename std::conditional<T::FT == 1, f16x4, bf16x4>::type out4_t;
+                    out_t *dst = (out_t *)args.C + (size_t)m * args.ldc + n;
+                    out4_t o;
                     if (beta != 0.f) {
-                        const bf16x4 c = *(const bf16x4 *)dst;
+                        const out4_t c = *(const out4_t *)dst;
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
-                            o[r] = (__bf16)__builtin_fmaf(beta, (float)c[r], v[r] * alpha);
+                            o[r] = (out_t)__builtin_fmaf(beta, (float)c[r], v[r] * alpha);
                     } else {
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
-                            o[r] = (__bf16)(v[r] * alpha);
+                            o[r] = (out_t)(v[r] * alpha);
                     }
-                    *(bf16x4 *)dst = o;
+                    *(out4_t *)dst = o;
                 }
             }
         }

@@ -24,12 +24,13 @@ static const Variant kVariantsFp8[] = {G355_VARIANTS_FP8(G355_X)};
 
 int variant_count(int dtype)
 {
-    return dtype == GEMM_BF16 ? (int)(sizeof(kVariantsBf16) / sizeof(Variant))
-                              : (int)(sizeof(kVariantsFp8) / sizeof(Variant));
+    // fp16 runs the bf16 tile list (same data path, same matrix-core rate)
+    return dtype != GEMM_FP8_E4M3 ? (int)(sizeof(kVariantsBf16) / sizeof(Variant))
+                                  : (int)(sizeof(kVariantsFp8) / sizeof(Variant));
 }
 const Variant &variant_at(int dtype, int id)
 {
-    return dtype == GEMM_BF16 ? kVariantsBf16[id] : kVariantsFp8[id];
+    return dtype != GEMM_FP8_E4M3 ? kVariantsBf16[id] : kVariantsFp8[id];
 }
 
 // One MI355X.  Matrix-instruction issue intervals come from register-resident MFMA loops on
@@ -105,11 +106,11 @@ void hw_reset() { g_hw = make_default_hw(); }
 
 static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-int elem_bytes(int dtype) { return dtype == GEMM_BF16 ? 2 : 1; }
+int elem_bytes(int dtype) { return dtype == GEMM_FP8_E4M3 ? 1 : 2; }
 
 int mfma_k(int dtype, int mfma)
 {
-    if (dtype == GEMM_BF16)
+    if (dtype != GEMM_FP8_E4M3)
         return mfma == 32 ? 16 : 32;
     return mfma == 32 ? 64 : 128;
 }
@@ -298,7 +299,8 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
     // Algorithm 3: instruction count and the latency it would have at full matrix-core
     // utilisation (reported); the latency the model uses is the kernel's measured slab cost.
     const double n_mi = (double)cdiv(v.block_m, v.mfma) * cdiv(v.block_n, v.mfma) * cdiv(v.block_k, mi_k);
-    const double l_mi = hw.l_mi_clk[dtype][v.mfma == 32 ? 0 : 1];
+    // the fp16 and bf16 matrix instructions issue at the same rate: one row of the table
+    const double l_mi = hw.l_mi_clk[dtype == GEMM_FP8_E4M3 ? 1 : 0][v.mfma == 32 ? 0 : 1];
     p->n_mi = n_mi;
     p->l_mt_ideal = n_mi * l_mi / std::min<double>(hw.simd_per_cu, waves_wg);
 

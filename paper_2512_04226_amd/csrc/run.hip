@@ -12,25 +12,29 @@ using namespace g355;
 
 namespace g355 {
 // Sum the split-K slabs in slice order (deterministic), scale, round to bf16.
-// beta != 0 adds beta * C (read before it is overwritten).
-__device__ inline bf16x4 scale_round(f32x4 s, float alpha, float beta, const __bf16 *dst)
+// Scale four sums, add beta * C when beta != 0 (C is read before it is overwritten), round to
+// the 16-bit output format (f16 != 0: IEEE fp16, else bf16) and store.
+__device__ inline void scale_round_store(f32x4 s, float alpha, float beta, void *dst, int f16)
 {
-    bf16x4 o;
-    if (beta != 0.f) {
-        const bf16x4 c = *(const bf16x4 *)dst;
+    if (f16) {
+        f16x4 o;
+        const f16x4 c = (beta != 0.f) ? *(const f16x4 *)dst : f16x4{0, 0, 0, 0};
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            o[r] = (__bf16)__builtin_fmaf(beta, (float)c[r], s[r] * alpha);
+            o[r] = (beta != 0.f) ? (_Float16)__builtin_fmaf(beta, (float)c[r], s[r] * alpha) : (_Float16)(s[r] * alpha);
+        *(f16x4 *)dst = o;
     } else {
+        bf16x4 o;
+        const bf16x4 c = (beta != 0.f) ? *(const bf16x4 *)dst : bf16x4{0, 0, 0, 0};
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            o[r] = (__bf16)(s[r] * alpha);
+            o[r] = (beta != 0.f) ? (__bf16)__builtin_fmaf(beta, (float)c[r], s[r] * alpha) : (__bf16)(s[r] * alpha);
+        *(bf16x4 *)dst = o;
     }
-    return o;
 }
 
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ ws, __bf16 *C, int M, int N, int ldc,
-                                                            int split_k, float alpha, float beta)
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ ws, uint16_t *C, int M, int N, int ldc,
+                                                            int split_k, float alpha, float beta, int f16)
 {
     const size_t quads = (size_t)M * (N / 4);
     const size_t slab = (size_t)M * N;
@@ -42,7 +46,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
             f32x4 t = *(const f32x4 *)(p + k * slab);
             s += t;
         }
-        *(bf16x4 *)(C + m * ldc + n) = scale_round(s, alpha, beta, C + m * ldc + n);
+        scale_round_store(s, alpha, beta, C + m * ldc + n, f16);
     }
 }
 
@@ -54,8 +58,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 // as a fixed binary tree.  The host picks R from the number of contributors per tile, so
 // the result depends only on the plan: deterministic.
 template <int R>
-__global__ __launch_bounds__(256) void streamk_sum_kernel(const float *__restrict__ ws, __bf16 *C, int M, int N, int ldc,
-                                                          float alpha, float beta, int tiles_m, int tiles_n,
+__global__ __launch_bounds__(256) void streamk_sum_kernel(const float *__restrict__ ws, uint16_t *C, int M, int N, int ldc,
+                                                          float alpha, float beta, int f16, int tiles_m, int tiles_n,
                                                           int group_m, SkPlan sk, int BM, int BN, int blocks_per_tile)
 {
     constexpr int Q = 256 / R;
@@ -97,7 +101,7 @@ __global__ __launch_bounds__(256) void streamk_sum_kernel(const float *__restric
         s = part[0][quad];
     }
     if (r == 0 && live)
-        *(bf16x4 *)(C + (size_t)m * ldc + n) = scale_round(s, alpha, beta, C + (size_t)m * ldc + n);
+        scale_round_store(s, alpha, beta, C + (size_t)m * ldc + n, f16);
 }
 
 }  // namespace g355
@@ -118,6 +122,15 @@ LaunchFn launcher_of(int dtype, int id, int bl)
     constexpr int n_b2 = 0 G355_VARIANTS_BF16_2(G355_COUNT);
     constexpr int n_f0 = 0 G355_VARIANTS_FP8_0(G355_COUNT);
 #undef G355_COUNT
+    if (dtype == GEMM_FP16) {
+        if (id < n_b0)
+            return kLaunchFp16_0(id, bl);
+        if (id < n_b0 + n_b1)
+            return kLaunchFp16_1(id - n_b0, bl);
+        if (id < n_b0 + n_b1 + n_b2)
+            return kLaunchFp16_2(id - n_b0 - n_b1, bl);
+        return kLaunchFp16_3(id - n_b0 - n_b1 - n_b2, bl);
+    }
     if (dtype == GEMM_BF16) {
         if (id < n_b0)
             return kLaunchBf16_0(id, bl);
@@ -230,6 +243,7 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
     a.sk = sk;   // workers == 0 unless stream-K
 
     hipStream_t stream = (hipStream_t)hip_stream;
+    const int f16 = (dtype == GEMM_FP16) ? 1 : 0;
     if (launcher_of(dtype, cfg->kernel_id, cfg->b_layout)(a, stream) != hipSuccess) {
         (void)hipGetLastError();
         return GEMM_ERR_HIP;
@@ -243,8 +257,8 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
         const dim3 grid((unsigned)(sk.sk_tiles * bpt)), block(256);
         (void)hipGetLastError();
 #define G355_SUM(R)                                                                                                   \
-    hipLaunchKernelGGL(streamk_sum_kernel<R>, grid, block, 0, stream, ws, (__bf16 *)C, a.M, a.N, a.ldc, a.alpha,      \
-                       a.beta, a.tiles_m, a.tiles_n, a.group_m, sk, v.block_m, v.block_n, bpt)
+    hipLaunchKernelGGL(streamk_sum_kernel<R>, grid, block, 0, stream, ws, (uint16_t *)C, a.M, a.N, a.ldc, a.alpha,     \
+                       a.beta, f16, a.tiles_m, a.tiles_n, a.group_m, sk, v.block_m, v.block_n, bpt)
         if (rows == 8)
             G355_SUM(8);
         else if (rows == 4)
@@ -260,8 +274,8 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
         if (blocks > 256 * 8)
             blocks = 256 * 8;
         (void)hipGetLastError();
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, ws, (__bf16 *)C, a.M,
-                           a.N, a.ldc, a.split_k, a.alpha, a.beta);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, ws, (uint16_t *)C, a.M,
+                           a.N, a.ldc, a.split_k, a.alpha, a.beta, f16);
         if (hipGetLastError() != hipSuccess)
             return GEMM_ERR_HIP;
     }

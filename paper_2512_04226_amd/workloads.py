@@ -54,6 +54,28 @@ def uniform_bf16(M, N, K, seed, case=0):
     return f32_to_bf16_bits(A), f32_to_bf16_bits(B)
 
 
+def f32_to_fp16_bits(x):
+    """float32 -> IEEE binary16 bit patterns (numpy's round-to-nearest-even cast)."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def integer_fp16(M, N, K, seed, case=0, lo=-4, hi=4):
+    """Integer-valued operands in [lo, hi] as fp16 bits (exactly representable)."""
+    g = _rng(seed, case)
+    A = g.integers(lo, hi + 1, size=(M, K)).astype(np.float32)
+    B = g.integers(lo, hi + 1, size=(K, N)).astype(np.float32)
+    return f32_to_fp16_bits(A), f32_to_fp16_bits(B)
+
+
+def normal_fp16(M, N, K, seed, case=0, std_a=1.0, std_b=1.0):
+    """A ~ N(0, std_a), B ~ N(0, std_b) as fp16 bits: the paper's evaluation precision (Section V),
+    with the value distribution of the square bf16 workload."""
+    g = _rng(seed, case)
+    A = g.standard_normal(size=(M, K), dtype=np.float32) * np.float32(std_a)
+    B = g.standard_normal(size=(K, N), dtype=np.float32) * np.float32(std_b)
+    return f32_to_fp16_bits(A), f32_to_fp16_bits(B)
+
+
 def integer_bf16(M, N, K, seed, case=0, lo=-4, hi=4):
     """Integer-valued operands in [lo, hi] (exactly representable in bf16)."""
     g = _rng(seed, case)

@@ -123,7 +123,7 @@ SHAPES = [(512, 512, 512), (4096, 4096, 4096), (8192, 8192, 8192), (1, 28672, 81
 
 
 @pytest.mark.parametrize("b_layout", [0, 1])
-@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
 def test_shipped_model_terms_match_the_oracle(dtype, b_layout):
     from paper_2512_04226_amd import binding as g
     hw = _hw_dict(g)
