@@ -29,7 +29,7 @@
 extern "C" {
 #endif
 
-#define GEMM_ABI_VERSION 3u
+#define GEMM_ABI_VERSION 4u
 
 typedef enum gemm_dtype {
     GEMM_BF16 = 0,     /* A, B bf16; C bf16 */
@@ -126,6 +126,10 @@ typedef struct gemm_cfg {
     int32_t bottleneck;       /* gemm_bottleneck of the prediction */
     float beta;               /* default 0; C = alpha*A*B + beta*C (Section II-A).  0: C is written without being read */
     double predicted_us;      /* model's total latency for this cfg */
+    int32_t batch;            /* independent problems of this shape in one launch (default 1) */
+    int32_t reserved1;
+    int64_t stride_a, stride_b, stride_c; /* elements between consecutive problems' A, B, C; gemm_select_batched
+                                             sets the dense values M*lda, (K or N)*ldb, M*ldc */
 } gemm_cfg;
 
 /* Terms of the model for one cfg (clocks unless said otherwise), for tests and reports. */
@@ -164,6 +168,17 @@ const char *gemm_strerror(int status);
 int gemm_select(int64_t M, int64_t N, int64_t K, int dtype, gemm_cfg *out);
 /* The same for a given storage of B (gemm_select is b_layout = GEMM_B_ROW_MAJOR). */
 int gemm_select_ex(int64_t M, int64_t N, int64_t K, int dtype, int b_layout, gemm_cfg *out);
+/*
+ * Strided-batched selection: `batch` independent products of one shape, C_b = alpha*A_b*B_b +
+ * beta*C_b with X_b = X + b*stride_x (Sections II-B and V-C mention the batch dimension as a
+ * multiplier of the tuning cost; here it multiplies the tile count of Algorithm 4).  The
+ * whole batch is one launch (plus one reduction launch for split-K); Stream-K is not
+ * offered for batch > 1.  1 <= batch <= 65535 (else GEMM_ERR_SHAPE).  gemm_run reads
+ * batch and the strides from the cfg; strides must be multiples of 16 bytes (C: 8 elements).
+ */
+int gemm_select_batched(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int b_layout, gemm_cfg *out);
+int gemm_cfg_at_batched(int idx, int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int b_layout,
+                        gemm_cfg *out);
 
 /*
  * Enqueue C = alpha * A * B + beta * C on hip_stream (a hipStream_t; NULL = the default stream) with
@@ -174,7 +189,7 @@ int gemm_select_ex(int64_t M, int64_t N, int64_t K, int dtype, int b_layout, gem
  */
 int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void *C, void *hip_stream);
 
-/* fp32 partial sums: split_k * M * N * 4 bytes when split_k > 1; 2 * sk_workers * block_m *
+/* fp32 partial sums: batch * split_k * M * N * 4 bytes when split_k > 1; 2 * sk_workers * block_m *
  * block_n * 4 bytes (two partial tiles per stream-K workgroup) when stream_k = 1; else 0. */
 size_t gemm_workspace_bytes(const gemm_cfg *cfg);
 

@@ -130,6 +130,15 @@ def gemm_samples(A, B, rows, cols, dtype=BF16, alpha=1.0):
     return C16, C64
 
 
+def gemm_batched(A, B, dtype=BF16, alpha=1.0):
+    """`batch` independent products: A is batch x M x K, B is batch x K x N.  Each problem is one
+    call of gemm(); returns (16-bit codes batch x M x N, fp64 batch x M x N)."""
+    if A.ndim != 3 or B.ndim != 3 or A.shape[0] != B.shape[0]:
+        raise ValueError("A must be batch x M x K and B batch x K x N")
+    outs = [gemm(A[b], B[b], dtype, alpha) for b in range(A.shape[0])]
+    return np.stack([o[0] for o in outs]), np.stack([o[1] for o in outs])
+
+
 def accumulate(C64, beta, C_in_bits, dtype=BF16):
     """The full definition of Section II-A, C = alpha*A*B + beta*C: C64 is the fp64 value of
     alpha*A*B (from gemm / gemm_rows / gemm_samples), C_in_bits the 16-bit codes C held on

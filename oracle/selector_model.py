@@ -143,11 +143,14 @@ def stream_k_split(tiles, slots, slabs):
     return (tiles - sk) // slots, sk, sk * slabs / slots
 
 
-def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0):
+def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0, batch=1):
     """Model terms for variant v (dict: block_m/n/k, waves_m/n, mfma, stages, slab_clk) with the
     reduction split split_k ways; hw is a dict of the hardware descriptor's fields; b_layout 0 =
     B row-major K x N, 1 = B stored K-contiguous (then v["slab_clk"] is that layout's constant);
-    stream_k = 1 prices the hybrid Stream-K split of the last partial wave (needs split_k = 1).
+    stream_k = 1 prices the hybrid Stream-K split of the last partial wave (needs split_k = 1);
+    batch = number of independent problems of this shape in one launch (READING: Section II-B only
+    names the batch dimension; here it multiplies the tile count of Algorithm 4 and the reduction
+    pass's bytes).
     Returns a dict with the names of the C ABI's gemm_prediction plus group_m."""
     # dtype 0 bf16, 1 fp8 e4m3, 2 fp16.  READING: fp16 shares bf16's instruction shapes and rates.
     row = 1 if dtype == 1 else 0
@@ -167,7 +170,7 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0):
     # means a full last wave.
     _, _, t_out = alg4_occupancy(M, N, v["block_m"], v["block_n"], hw["n_cu"])
     tiles_m, tiles_n = _ceil_div(M, v["block_m"]), _ceil_div(N, v["block_n"])
-    tiles = t_out * split_k
+    tiles = t_out * split_k * batch
     occ = occupancy(hw, v, es)
     slots = hw["n_cu"] * occ
     waves = math.ceil(tiles / slots)
@@ -242,7 +245,7 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0):
 
     l_reduce = 0.0
     if split_k > 1:
-        nbytes = M * N * (4.0 * split_k + 2.0)
+        nbytes = M * N * (4.0 * split_k + 2.0) * batch
         rate = hw["mall_bytes_per_clk"] if nbytes <= hw["cache_eff_frac"] * hw["mall_bytes"] else hw["hbm_bytes_per_clk"]
         l_reduce = hw["reduce_launch_clk"] + nbytes / rate
     out["l_reduce"] = l_reduce

@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("GEMM355_LIB") or os.path.join(_PKG, "libgemm355.so") 
 GEMM_BF16 = 0
 GEMM_FP8_E4M3 = 1
 GEMM_FP16 = 2
-GEMM_ABI_VERSION = 3
+GEMM_ABI_VERSION = 4
 GEMM_B_ROW_MAJOR = 0
 GEMM_B_K_CONTIGUOUS = 1
 
@@ -59,13 +59,16 @@ class gemm_cfg(ctypes.Structure):
                 ("xcd_remap", ctypes.c_uint8), ("stages", ctypes.c_uint8),
                 ("slab_clk", ctypes.c_uint16), ("b_layout", ctypes.c_uint8), ("stream_k", ctypes.c_uint8),
                 ("sk_workers", ctypes.c_uint16), ("alpha", ctypes.c_float),
-                ("bottleneck", ctypes.c_int32), ("beta", ctypes.c_float), ("predicted_us", ctypes.c_double)]
+                ("bottleneck", ctypes.c_int32), ("beta", ctypes.c_float), ("predicted_us", ctypes.c_double),
+                ("batch", ctypes.c_int32), ("reserved1", ctypes.c_int32), ("stride_a", ctypes.c_int64),
+                ("stride_b", ctypes.c_int64), ("stride_c", ctypes.c_int64)]
 
     def describe(self):
         return ("%dx%dx%d w%dx%d mfma%d s%d %s g%d%s%s" % (
             self.block_m, self.block_n, self.block_k, self.waves_m, self.waves_n, self.mfma, self.stages,
             ("streamk%d" % self.sk_workers) if self.stream_k else ("split%d" % self.split_k), self.group_m,
-            "" if self.xcd_remap else " noxcd", " Bkc" if self.b_layout else ""))
+            "" if self.xcd_remap else " noxcd", " Bkc" if self.b_layout else "")
+                + (" batch%d" % self.batch if self.batch > 1 else ""))
 
     def copy(self):
         c = gemm_cfg()
@@ -182,6 +185,28 @@ def gemm_cfg_at_ex(idx, M, N, K, dtype, b_layout):
     return cfg
 
 
+_lib.gemm_select_batched.restype = _int
+_lib.gemm_select_batched.argtypes = [_i64, _i64, _i64, _i64, _int, _int, ctypes.POINTER(gemm_cfg)]
+_lib.gemm_cfg_at_batched.restype = _int
+_lib.gemm_cfg_at_batched.argtypes = [_int, _i64, _i64, _i64, _i64, _int, _int, ctypes.POINTER(gemm_cfg)]
+
+
+def gemm_select_batched(M, N, K, batch, dtype, b_layout=0):
+    cfg = gemm_cfg()
+    _check(_lib.gemm_select_batched(M, N, K, batch, dtype, b_layout, ctypes.byref(cfg)), "gemm_select_batched")
+    return cfg
+
+
+def gemm_cfg_at_batched(idx, M, N, K, batch, dtype, b_layout=0):
+    """Returns the cfg, or None when variant idx is not legal for the shape and batch."""
+    cfg = gemm_cfg()
+    rc = _lib.gemm_cfg_at_batched(idx, M, N, K, batch, dtype, b_layout, ctypes.byref(cfg))
+    if rc == -4:
+        return None
+    _check(rc, "gemm_cfg_at_batched")
+    return cfg
+
+
 def gemm_cfg_count(dtype):
     n = _lib.gemm_cfg_count(dtype)
     if n < 0:
@@ -283,7 +308,7 @@ def _ptr(t):
 
 
 def gemm_run(cfg, A, B, C, stream=None):
-    """Enqueue C = alpha * A * B.  stream: a torch.cuda.Stream, a raw hipStream_t int, or
+    """Enqueue C = alpha * A * B + beta * C (cfg.batch problems, cfg.stride_* apart).  stream: a torch.cuda.Stream, a raw hipStream_t int, or
     None for torch's current stream."""
     _check(_lib.gemm_run(ctypes.byref(cfg), _ptr(A), _ptr(B), _ptr(C), ctypes.c_void_p(_stream_handle(stream))),
            "gemm_run")

@@ -70,8 +70,15 @@ int gemm_cfg_at(int idx, int64_t M, int64_t N, int64_t K, int dtype, gemm_cfg *o
 
 int gemm_cfg_at_ex(int idx, int64_t M, int64_t N, int64_t K, int dtype, int b_layout, gemm_cfg *out)
 {
+    return gemm_cfg_at_batched(idx, M, N, K, 1, dtype, b_layout, out);
+}
+
+int gemm_cfg_at_batched(int idx, int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int b_layout, gemm_cfg *out)
+{
     if (!out)
         return GEMM_ERR_NULL;
+    if (batch < 1 || batch > 65535)
+        return GEMM_ERR_SHAPE;
     if (b_layout != GEMM_B_ROW_MAJOR && b_layout != GEMM_B_K_CONTIGUOUS)
         return GEMM_ERR_CFG_ILLEGAL;
     const int rc = check_problem(M, N, K, dtype);
@@ -81,9 +88,9 @@ int gemm_cfg_at_ex(int idx, int64_t M, int64_t N, int64_t K, int dtype, int b_la
         return GEMM_ERR_INDEX;
     const int id = idx / kNumSplits, split = split_k_of(idx % kNumSplits), sk = stream_k_of(idx % kNumSplits);
     const gemm_hw &hw = hw_current();
-    if (!variant_legal(hw, variant_at(dtype, id), dtype, M, N, K, split, sk))
+    if (!variant_legal(hw, variant_at(dtype, id), dtype, M, N, K, split, sk, batch))
         return GEMM_ERR_CFG_ILLEGAL;
-    fill_cfg(hw, dtype, b_layout, M, N, K, id, split, sk, out);
+    fill_cfg(hw, dtype, b_layout, M, N, K, id, split, sk, out, batch);
     return GEMM_OK;
 }
 
@@ -94,8 +101,15 @@ int gemm_select(int64_t M, int64_t N, int64_t K, int dtype, gemm_cfg *out)
 
 int gemm_select_ex(int64_t M, int64_t N, int64_t K, int dtype, int b_layout, gemm_cfg *out)
 {
+    return gemm_select_batched(M, N, K, 1, dtype, b_layout, out);
+}
+
+int gemm_select_batched(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int b_layout, gemm_cfg *out)
+{
     if (!out)
         return GEMM_ERR_NULL;
+    if (batch < 1 || batch > 65535)
+        return GEMM_ERR_SHAPE;
     if (b_layout != GEMM_B_ROW_MAJOR && b_layout != GEMM_B_K_CONTIGUOUS)
         return GEMM_ERR_CFG_ILLEGAL;
     const int rc = check_problem(M, N, K, dtype);
@@ -108,11 +122,11 @@ int gemm_select_ex(int64_t M, int64_t N, int64_t K, int dtype, int b_layout, gem
     for (int id = 0; id < variant_count(dtype); ++id) {
         const Variant &v = variant_at(dtype, id);
         for (int s = 0; s < kNumSplits; ++s) {
-            if (!variant_legal(hw, v, dtype, M, N, K, split_k_of(s), stream_k_of(s)))
+            if (!variant_legal(hw, v, dtype, M, N, K, split_k_of(s), stream_k_of(s), batch))
                 continue;
             gemm_prediction p;
             int gm, gn;
-            predict(hw, dtype, b_layout, M, N, K, v, split_k_of(s), stream_k_of(s), &p, &gm, &gn);
+            predict(hw, dtype, b_layout, M, N, K, v, split_k_of(s), stream_k_of(s), &p, &gm, &gn, batch);
             if (best_id < 0 || p.l_total < best) {
                 best = p.l_total;
                 best_id = id;
@@ -122,7 +136,7 @@ int gemm_select_ex(int64_t M, int64_t N, int64_t K, int dtype, int b_layout, gem
     }
     if (best_id < 0)
         return GEMM_ERR_CFG_ILLEGAL;
-    fill_cfg(hw, dtype, b_layout, M, N, K, best_id, split_k_of(best_mode), stream_k_of(best_mode), out);
+    fill_cfg(hw, dtype, b_layout, M, N, K, best_id, split_k_of(best_mode), stream_k_of(best_mode), out, batch);
     return GEMM_OK;
 }
 
@@ -139,12 +153,13 @@ int gemm_predict(const gemm_cfg *cfg, gemm_prediction *out)
         return GEMM_ERR_CFG_ILLEGAL;
     const gemm_hw &hw = hw_current();
     const Variant &v = variant_at(cfg->dtype, cfg->kernel_id);
-    if (!variant_legal(hw, v, cfg->dtype, cfg->M, cfg->N, cfg->K, cfg->split_k, cfg->stream_k))
+    if (!variant_legal(hw, v, cfg->dtype, cfg->M, cfg->N, cfg->K, cfg->split_k, cfg->stream_k, cfg->batch))
         return GEMM_ERR_CFG_ILLEGAL;
     int gm, gn;
     if (cfg->b_layout > 1 || cfg->stream_k > 1)
         return GEMM_ERR_CFG_ILLEGAL;
-    predict(hw, cfg->dtype, cfg->b_layout, cfg->M, cfg->N, cfg->K, v, cfg->split_k, cfg->stream_k, out, &gm, &gn);
+    predict(hw, cfg->dtype, cfg->b_layout, cfg->M, cfg->N, cfg->K, v, cfg->split_k, cfg->stream_k, out, &gm, &gn,
+            cfg->batch);
     return GEMM_OK;
 }
 
@@ -209,7 +224,7 @@ size_t gemm_workspace_bytes(const gemm_cfg *cfg)
         return (size_t)2 * cfg->sk_workers * cfg->block_m * cfg->block_n * sizeof(float);
     if (cfg->split_k <= 1)
         return 0;
-    return (size_t)cfg->split_k * (size_t)cfg->M * (size_t)cfg->N * sizeof(float);
+    return (size_t)(cfg->batch > 1 ? cfg->batch : 1) * cfg->split_k * (size_t)cfg->M * (size_t)cfg->N * sizeof(float);
 }
 
 int gemm_stream_k_plan(const gemm_cfg *cfg, int32_t plan4[4])

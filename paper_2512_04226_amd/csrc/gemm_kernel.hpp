@@ -39,6 +39,10 @@ struct KernelArgs {
     // the rest compute the sk.dp_tiles data-parallel tiles; ws then holds the workers' partial
     // tiles, [2 * workers][BLOCK_M][BLOCK_N] fp32.
     SkPlan sk;
+    // Strided batch: blockIdx.y selects the problem; strides in elements (the workspace of
+    // problem b starts at b * split_k * M * N floats).
+    long long stride_a, stride_b, stride_c;
+    int batch;
 };
 
 typedef short short4_t __attribute__((ext_vector_type(4)));
@@ -202,9 +206,11 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     // belongs in its slot.  Rows past the edge of the matrix (A: m >= M, B: k >= k_len) fall
     // outside the buffer window and arrive as zero; chunk columns past the edge (A: k >= k_len,
     // B: n >= N) are sent outside the window by replacing the offset.
-    const uint8_t *Abase = (const uint8_t *)args.A + ((size_t)m0 * args.lda + k_begin) * ES;
-    const uint8_t *Bbase = (T::BL == 0) ? (const uint8_t *)args.B + ((size_t)k_begin * args.ldb + n0) * ES
-                                        : (const uint8_t *)args.B + ((size_t)n0 * args.ldb + k_begin) * ES;
+    const size_t bz = blockIdx.y;     // problem of the batch
+    const uint8_t *Abase = (const uint8_t *)args.A + (bz * args.stride_a + (size_t)m0 * args.lda + k_begin) * ES;
+    const uint8_t *Bbase = (T::BL == 0)
+                               ? (const uint8_t *)args.B + (bz * args.stride_b + (size_t)k_begin * args.ldb + n0) * ES
+                               : (const uint8_t *)args.B + (bz * args.stride_b + (size_t)n0 * args.ldb + k_begin) * ES;
     const int a_rows_valid = (args.M - m0 < BM) ? (args.M - m0) : BM;
     const int b_rows_valid = (args.N - n0 < BN) ? (args.N - n0) : BN;      // K-contiguous B only
     const __amdgpu_buffer_rsrc_t rsA =
@@ -436,7 +442,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                 for (int r = 0; r < 4; ++r)
                     v[r] = acc[j][i][q * 4 + r];
                 if (out_mode == 1) {
-                    float *dst = args.ws + ((size_t)ks * args.M + m) * args.N + n;
+                    float *dst = args.ws + ((bz * args.split_k + ks) * args.M + m) * args.N + n;
                     *(f32x4 *)dst = v;
                 } else if (out_mode == 2) {
                     float *dst = args.ws + ((size_t)(2 * blockIdx.x + seg) * BM + (m - m0)) * BN + (n - n0);
@@ -444,7 +450,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                 } else {
                     typedef typename std::conditional<T::FT == 1, _Float16, __bf16>::type out_t;
                     typedef typename std::conditional<T::FT == 1, f16x4, bf16x4>::type out4_t;
-                    out_t *dst = (out_t *)args.C + (size_t)m * args.ldc + n;
+                    out_t *dst = (out_t *)args.C + bz * args.stride_c + (size_t)m * args.ldc + n;
                     out4_t o;
                     if (beta != 0.f) {
                         const out4_t c = *(const out4_t *)dst;

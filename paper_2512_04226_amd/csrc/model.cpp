@@ -125,9 +125,11 @@ static int occupancy(const gemm_hw &hw, const Variant &v, int dtype);
 int stream_k_workers(const gemm_hw &hw, const Variant &v, int dtype) { return hw.n_cu * occupancy(hw, v, dtype); }
 
 bool variant_legal(const gemm_hw &hw, const Variant &v, int dtype, int64_t M, int64_t N, int64_t K, int split_k,
-                   int stream_k)
+                   int stream_k, int64_t batch)
 {
     const int es = elem_bytes(dtype);
+    if (batch < 1 || batch > 65535 || (stream_k && batch != 1))
+        return false;
     if (stream_k) {
         // stream-K splits the last partial wave of tiles; it needs one, and work for every worker
         SkPlan plan;
@@ -289,7 +291,7 @@ static int label_of(const MemTerms &t, double l_comp, bool under, double fixed, 
 }
 
 void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, int64_t K, const Variant &v, int split_k,
-             int stream_k, gemm_prediction *p, int *group_m, int *group_n)
+             int stream_k, gemm_prediction *p, int *group_m, int *group_n, int64_t batch)
 {
     std::memset(p, 0, sizeof(*p));
     const int es = elem_bytes(dtype);
@@ -306,7 +308,8 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
 
     // Algorithm 4, with K slices counted as tiles and `occ` workgroups per CU as slots.
     const int64_t tiles_m = cdiv(M, v.block_m), tiles_n = cdiv(N, v.block_n);
-    const double tiles = (double)tiles_m * tiles_n * split_k;
+    // a batch is that many times the tiles, dispatched back to back in one launch
+    const double tiles = (double)tiles_m * tiles_n * split_k * (double)batch;
     const int occ = occupancy(hw, v, dtype);
     const double slots = (double)hw.n_cu * occ;
     const double waves = std::ceil(tiles / slots);
@@ -386,7 +389,7 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
     // Split-K: a second pass sums the fp32 slabs (read split_k * M * N * 4, write M * N * 2).
     double l_reduce = 0.0;
     if (split_k > 1) {
-        const double bytes = (double)M * N * (4.0 * split_k + 2.0);
+        const double bytes = (double)M * N * (4.0 * split_k + 2.0) * (double)batch;
         const double rate = (bytes <= hw.cache_eff_frac * hw.mall_bytes) ? hw.mall_bytes_per_clk : hw.hbm_bytes_per_clk;
         l_reduce = hw.reduce_launch_clk + bytes / rate;
     }
@@ -444,12 +447,12 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
 }
 
 void fill_cfg(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, int64_t K, int kernel_id, int split_k,
-              int stream_k, gemm_cfg *c)
+              int stream_k, gemm_cfg *c, int64_t batch)
 {
     const Variant &v = variant_at(dtype, kernel_id);
     gemm_prediction p;
     int gm, gn;
-    predict(hw, dtype, b_layout, M, N, K, v, split_k, stream_k, &p, &gm, &gn);
+    predict(hw, dtype, b_layout, M, N, K, v, split_k, stream_k, &p, &gm, &gn, batch);
     std::memset(c, 0, sizeof(*c));
     c->abi_version = GEMM_ABI_VERSION;
     c->dtype = dtype;
@@ -477,6 +480,10 @@ void fill_cfg(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, 
     c->stream_k = (uint8_t)(stream_k ? 1 : 0);
     c->sk_workers = (uint16_t)(stream_k ? stream_k_workers(hw, v, dtype) : 0);
     c->alpha = 1.0f;
+    c->batch = (int32_t)batch;
+    c->stride_a = M * c->lda;
+    c->stride_b = b_layout ? N * c->ldb : K * c->ldb;
+    c->stride_c = M * c->ldc;
     c->bottleneck = p.bottleneck;
     c->predicted_us = p.total_us;
 }

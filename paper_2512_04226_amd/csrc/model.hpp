@@ -16,13 +16,14 @@ int mfma_k(int dtype, int mfma);
 int64_t k_per_split(const Variant &v, int64_t K, int split_k);
 // stream_k != 0 (with split_k == 1): the last partial wave of tiles is split along K over
 // stream_k_workers() workgroups
+// batch > 1: that many independent problems of one shape in one launch (no stream-K then)
 bool variant_legal(const gemm_hw &hw, const Variant &v, int dtype, int64_t M, int64_t N, int64_t K, int split_k,
-                   int stream_k);
+                   int stream_k, int64_t batch = 1);
 int stream_k_workers(const gemm_hw &hw, const Variant &v, int dtype);
 void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, int64_t K, const Variant &v, int split_k,
-             int stream_k, gemm_prediction *p, int *group_m, int *group_n);
+             int stream_k, gemm_prediction *p, int *group_m, int *group_n, int64_t batch = 1);
 void fill_cfg(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, int64_t K, int kernel_id, int split_k,
-              int stream_k, gemm_cfg *c);
+              int stream_k, gemm_cfg *c, int64_t batch = 1);
 // 0 or a gemm_status for the shape / dtype / alignment rules shared by select, cfg_at and run
 int check_problem(int64_t M, int64_t N, int64_t K, int dtype);
 struct SkPlan;

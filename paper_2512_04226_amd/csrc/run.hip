@@ -34,8 +34,11 @@ __device__ inline void scale_round_store(f32x4 s, float alpha, float beta, void 
 }
 
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ ws, uint16_t *C, int M, int N, int ldc,
-                                                            int split_k, float alpha, float beta, int f16)
+                                                            int split_k, float alpha, float beta, int f16,
+                                                            long long stride_c)
 {
+    ws += (size_t)blockIdx.y * split_k * M * N;     // problem of the batch
+    C += (size_t)blockIdx.y * stride_c;
     const size_t quads = (size_t)M * (N / 4);
     const size_t slab = (size_t)M * N;
     for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += (size_t)gridDim.x * blockDim.x) {
@@ -187,6 +190,10 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
         return GEMM_ERR_CFG_ILLEGAL;
     if (cfg->b_layout > 1 || cfg->stream_k > 1)
         return GEMM_ERR_CFG_ILLEGAL;
+    if (cfg->batch < 1 || cfg->batch > 65535)
+        return GEMM_ERR_SHAPE;
+    if (cfg->batch > 1 && cfg->stream_k)
+        return GEMM_ERR_CFG_ILLEGAL;
     // stream-K: the plan is rebuilt from the cfg's own worker count and must exist
     SkPlan sk;
     std::memset(&sk, 0, sizeof(sk));
@@ -198,6 +205,18 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
     if (((uintptr_t)A & 15) || ((uintptr_t)B & 15) || ((uintptr_t)C & 15) || cfg->lda % per16 || cfg->ldb % per16 ||
         cfg->ldc % 8)
         return GEMM_ERR_ALIGN;
+    if (cfg->batch > 1) {
+        // problems must not overlap and must keep the 16-byte alignment of the first one
+        const int64_t a_min = (cfg->M - 1) * cfg->lda + cfg->K;
+        const int64_t b_min = cfg->b_layout ? (cfg->N - 1) * cfg->ldb + cfg->K : (cfg->K - 1) * cfg->ldb + cfg->N;
+        const int64_t c_min = (cfg->M - 1) * cfg->ldc + cfg->N;
+        if (cfg->stride_a < a_min || cfg->stride_b < b_min || cfg->stride_c < c_min)
+            return GEMM_ERR_SHAPE;
+        if (cfg->stride_a % per16 || cfg->stride_b % per16 || cfg->stride_c % 8)
+            return GEMM_ERR_ALIGN;
+        if (cfg->stride_a >= ((int64_t)1 << 40) || cfg->stride_b >= ((int64_t)1 << 40) || cfg->stride_c >= ((int64_t)1 << 40))
+            return GEMM_ERR_SHAPE;
+    }
     const int64_t kps = k_per_split(v, cfg->K, cfg->split_k);
     const int64_t tiles_m = cdiv64(cfg->M, v.block_m), tiles_n = cdiv64(cfg->N, v.block_n);
     // the kernel addresses a tile's operands with 32-bit byte offsets below 2 GiB
@@ -241,6 +260,10 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
     a.xcd_remap = cfg->xcd_remap ? 1 : 0;
     a.n_xcd = hw.n_xcd;
     a.sk = sk;   // workers == 0 unless stream-K
+    a.batch = cfg->batch;
+    a.stride_a = cfg->batch > 1 ? cfg->stride_a : 0;
+    a.stride_b = cfg->batch > 1 ? cfg->stride_b : 0;
+    a.stride_c = cfg->batch > 1 ? cfg->stride_c : 0;
 
     hipStream_t stream = (hipStream_t)hip_stream;
     const int f16 = (dtype == GEMM_FP16) ? 1 : 0;
@@ -274,8 +297,8 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
         if (blocks > 256 * 8)
             blocks = 256 * 8;
         (void)hipGetLastError();
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, ws, (uint16_t *)C, a.M,
-                           a.N, a.ldc, a.split_k, a.alpha, a.beta, f16);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks, (unsigned)a.batch), dim3(256), 0, stream, ws, (uint16_t *)C, a.M,
+                           a.N, a.ldc, a.split_k, a.alpha, a.beta, f16, a.stride_c);
         if (hipGetLastError() != hipSuccess)
             return GEMM_ERR_HIP;
     }

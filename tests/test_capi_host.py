@@ -29,11 +29,30 @@ def test_every_declared_symbol_is_exported():
     assert g.gemm_abi_version() == g.GEMM_ABI_VERSION
 
 
-def test_struct_sizes_match_header_layout():
-    # gemm_cfg: 4+4 + 6*8 + 4 + 3*2 + 4*1 + 3*2 + 1+1+2 + 4 + 4 (+pad) + 8
-    assert ctypes.sizeof(g.gemm_cfg) == 104
-    assert ctypes.sizeof(g.gemm_prediction) == 26 * 8 + 8
-    assert ctypes.sizeof(g.gemm_hw) == 16 + 18 * 8 + 4 * 8
+def test_struct_layouts_match_the_header(tmp_path):
+    """Compile the public header with gcc and compare sizeof / offsetof of every field with the
+    binding's ctypes structures."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    lines = ["#include <stdio.h>", "#include <stddef.h>", '#include "gemm.h"', "int main(void){"]
+    structs = {"gemm_cfg": g.gemm_cfg, "gemm_prediction": g.gemm_prediction, "gemm_hw": g.gemm_hw,
+               "gemm_sk_segment": g.gemm_sk_segment}
+    for name, cls in structs.items():
+        lines.append('printf("%s %%zu\\n", sizeof(%s));' % (name, name))
+        for field, _ in cls._fields_:
+            lines.append('printf("%s.%s %%zu\\n", offsetof(%s, %s));' % (name, field, name, field))
+    lines.append("return 0;}")
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-I", os.path.join(root, "include"), "-o", str(exe), str(src)])
+    got = dict(line.split() for line in subprocess.check_output([str(exe)], text=True).splitlines())
+    for name, cls in structs.items():
+        assert int(got[name]) == ctypes.sizeof(cls), name
+        for field, _ in cls._fields_:
+            assert int(got["%s.%s" % (name, field)]) == getattr(cls, field).offset, (name, field)
+    assert ctypes.sizeof(g.gemm_cfg) == 136
 
 
 def test_select_argument_errors():

@@ -221,3 +221,37 @@ def test_retargeting_to_a_304_cu_table_changes_waves_cache_tiles_and_candidates(
     with pytest.raises(g.GemmError):
         g.gemm_hw_preset(7)
     assert bytes(g.gemm_hw_preset(g.GEMM_HW_MI355X)) == base
+
+
+def test_batched_selection_matches_the_oracle_and_scales_the_tile_count():
+    """Algorithm 4 with a batch: `batch` times the tiles.  A batch of small problems fills the
+    device, so the selector stops splitting K and may take larger tiles."""
+    from paper_2512_04226_amd import binding as g
+    hw = _hw_dict(g)
+    M, N, K = 512, 512, 4096
+    for batch in (1, 3, 64):
+        best = None
+        for idx in range(g.gemm_cfg_count(0)):
+            c = g.gemm_cfg_at_batched(idx, M, N, K, batch, 0)
+            if c is None:
+                continue
+            assert c.batch == batch and (c.stride_a, c.stride_b, c.stride_c) == (M * K, K * N, M * N)
+            assert not (c.stream_k and batch > 1)
+            p = g.gemm_predict(c)
+            o = sm.predict(hw, 0, M, N, K, _variant_dict(c), c.split_k, 0, c.stream_k, batch)
+            for f in ("tiles", "waves", "active_cu", "l_reduce", "l_tile", "l_total", "total_us"):
+                assert getattr(p, f) == pytest.approx(o[f], rel=1e-9, abs=1e-9), (batch, c.describe(), f)
+            tiles_1 = -(-M // c.block_m) * -(-N // c.block_n) * c.split_k
+            assert p.tiles == tiles_1 * batch
+            if best is None or o["l_total"] < best[0] * (1 - 1e-12):
+                best = (o["l_total"], c.kernel_id, c.split_k, c.stream_k)
+        pick = g.gemm_select_batched(M, N, K, batch, 0)
+        assert (pick.kernel_id, pick.split_k, pick.stream_k) == best[1:]
+    one, many = g.gemm_select_batched(M, N, K, 1, 0), g.gemm_select_batched(M, N, K, 64, 0)
+    assert one.split_k > 1 and many.split_k == 1
+    assert many.block_m * many.block_n >= one.block_m * one.block_n
+    assert g.gemm_workspace_bytes(one) == one.split_k * M * N * 4
+    with pytest.raises(g.GemmError):
+        g.gemm_select_batched(M, N, K, 0, 0)
+    with pytest.raises(g.GemmError):
+        g.gemm_select_batched(M, N, K, 70000, 0)
