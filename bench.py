@@ -50,12 +50,70 @@ def cpu_baseline(A, B, rows):
             "sample": "%d evenly spaced rows of the 8192^3 product (%.1f s)" % (rows, dt)}
 
 
+def secondary(also, g, wl, np, torch, dev, sizes, timed_us):
+    """Figures outside the timed region: per-shape rates, the other layouts, precisions and the
+    bandwidth-bound path, and the measured ceilings the rooflines are also quoted against."""
+    for n in sizes:
+        us = timed_us(g.gemm_select(n, n, n, g.GEMM_BF16), *dev[n])
+        also["bf16_%d_tflops" % n] = 2.0 * n ** 3 / us * 1e-6
+    # the paper's own operand layout (both operands K-contiguous, Section V): same product, B stored N x K
+    n_big = sizes[-1]
+    dBt = dev[n_big][1].t().contiguous()
+    cfg_kc = g.gemm_select_ex(n_big, n_big, n_big, g.GEMM_BF16, g.GEMM_B_K_CONTIGUOUS)
+    us = timed_us(cfg_kc, dev[n_big][0], dBt, dev[n_big][2])
+    also["bf16_%d_b_k_contiguous" % n_big] = {"tflops": 2.0 * n_big ** 3 / us * 1e-6, "picked": cfg_kc.describe()}
+    del dBt
+    # the paper's own precision and layout (Section V): fp16 in / fp16 out, both operands K-contiguous
+    Ah, Bh = wl.normal_fp16(n_big, n_big, n_big, seed=1)
+    dAh = torch.from_numpy(Ah.view(np.int16)).cuda()
+    dBh = torch.from_numpy(np.ascontiguousarray(Bh.T).view(np.int16)).cuda()
+    cfg_h = g.gemm_select_ex(n_big, n_big, n_big, g.GEMM_FP16, g.GEMM_B_K_CONTIGUOUS)
+    us = timed_us(cfg_h, dAh, dBh, dev[n_big][2])
+    also["fp16_%d_b_k_contiguous" % n_big] = {"tflops": 2.0 * n_big ** 3 / us * 1e-6, "picked": cfg_h.describe()}
+    del Ah, Bh, dAh, dBh
+    scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
+    also["mfma_only_bf16_tflops"] = g.gemm_probe_mfma(g.GEMM_BF16, 32, scratch)
+    n8 = 8192
+    Aq, Bq, sa, sb = wl.config4(n8)
+    cfg8 = g.gemm_select(n8, n8, n8, g.GEMM_FP8_E4M3)
+    cfg8.alpha = float(sa) * float(sb)
+    us = timed_us(cfg8, torch.from_numpy(Aq).cuda(), torch.from_numpy(Bq).cuda(), dev[n8][2])
+    also["fp8_8192"] = {"tflops": 2.0 * n8 ** 3 / us * 1e-6, "frac_of_fp8_peak": 2.0 * n8 ** 3 / us * 1e-6 / PEAK_TFLOPS["fp8"],
+                        "picked": cfg8.describe()}
+    del Aq, Bq
+    Ms, Ns, Ks = 16, 28672, 8192
+    As, Bs = wl.config3(Ms, Ns, Ks)
+    cfgs = g.gemm_select(Ms, Ns, Ks, g.GEMM_BF16)
+    dBs = torch.from_numpy(Bs.view(np.int16)).cuda()
+    us = timed_us(cfgs, torch.from_numpy(As.view(np.int16)).cuda(), dBs,
+                  torch.empty((Ms, Ns), dtype=torch.int16, device="cuda"))
+    sk_bytes = (Ms * Ks + Ks * Ns + Ms * Ns) * 2.0
+    also["skinny_bf16_M16_N28672_K8192"] = {"us": us, "gbps": sk_bytes / us * 1e-3,
+                                            "frac_of_hbm_peak": sk_bytes / us * 1e-3 / PEAK_HBM_GBPS,
+                                            "picked": cfgs.describe()}
+    also["hbm_stream_gbps"] = g.gemm_probe_stream(dBs, scratch)
+
+    # the vendor library on the same box and operands (calibration of what this chip sustains on
+    # N(0,1) data under its power limit; not a baseline and not part of the product path)
+    a16, b16 = dev[n_big][0].view(torch.bfloat16), dev[n_big][1].view(torch.bfloat16)
+    for _ in range(3):
+        torch.matmul(a16, b16)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        torch.matmul(a16, b16)
+    e1.record()
+    e1.synchronize()
+    also["calibration_torch_matmul_bf16_%d_tflops" % n_big] = 2.0 * n_big ** 3 / (e0.elapsed_time(e1) * 1e-4) * 1e-12
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--brief", action="store_true", help="skip the secondary figures (for profiler runs)")
     ap.add_argument("--cpu-rows", type=int, default=4096)
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy, so that HBM byte counters "
@@ -149,45 +207,8 @@ def main():
         return e0.elapsed_time(e1) * 1e3 / reps
 
     also = {}
-    for n in sizes:
-        us = timed_us(g.gemm_select(n, n, n, g.GEMM_BF16), *dev[n])
-        also["bf16_%d_tflops" % n] = 2.0 * n ** 3 / us * 1e-6
-    # the paper's own operand layout (both operands K-contiguous, Section V): same product, B stored N x K
-    n_big = sizes[-1]
-    dBt = dev[n_big][1].t().contiguous()
-    cfg_kc = g.gemm_select_ex(n_big, n_big, n_big, g.GEMM_BF16, g.GEMM_B_K_CONTIGUOUS)
-    us = timed_us(cfg_kc, dev[n_big][0], dBt, dev[n_big][2])
-    also["bf16_%d_b_k_contiguous" % n_big] = {"tflops": 2.0 * n_big ** 3 / us * 1e-6, "picked": cfg_kc.describe()}
-    del dBt
-    # the paper's own precision and layout (Section V): fp16 in / fp16 out, both operands K-contiguous
-    Ah, Bh = wl.normal_fp16(n_big, n_big, n_big, seed=1)
-    dAh = torch.from_numpy(Ah.view(np.int16)).cuda()
-    dBh = torch.from_numpy(np.ascontiguousarray(Bh.T).view(np.int16)).cuda()
-    cfg_h = g.gemm_select_ex(n_big, n_big, n_big, g.GEMM_FP16, g.GEMM_B_K_CONTIGUOUS)
-    us = timed_us(cfg_h, dAh, dBh, dev[n_big][2])
-    also["fp16_%d_b_k_contiguous" % n_big] = {"tflops": 2.0 * n_big ** 3 / us * 1e-6, "picked": cfg_h.describe()}
-    del Ah, Bh, dAh, dBh
-    scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
-    also["mfma_only_bf16_tflops"] = g.gemm_probe_mfma(g.GEMM_BF16, 32, scratch)
-    n8 = 8192
-    Aq, Bq, sa, sb = wl.config4(n8)
-    cfg8 = g.gemm_select(n8, n8, n8, g.GEMM_FP8_E4M3)
-    cfg8.alpha = float(sa) * float(sb)
-    us = timed_us(cfg8, torch.from_numpy(Aq).cuda(), torch.from_numpy(Bq).cuda(), dev[n8][2])
-    also["fp8_8192"] = {"tflops": 2.0 * n8 ** 3 / us * 1e-6, "frac_of_fp8_peak": 2.0 * n8 ** 3 / us * 1e-6 / PEAK_TFLOPS["fp8"],
-                        "picked": cfg8.describe()}
-    del Aq, Bq
-    Ms, Ns, Ks = 16, 28672, 8192
-    As, Bs = wl.config3(Ms, Ns, Ks)
-    cfgs = g.gemm_select(Ms, Ns, Ks, g.GEMM_BF16)
-    dBs = torch.from_numpy(Bs.view(np.int16)).cuda()
-    us = timed_us(cfgs, torch.from_numpy(As.view(np.int16)).cuda(), dBs,
-                  torch.empty((Ms, Ns), dtype=torch.int16, device="cuda"))
-    sk_bytes = (Ms * Ks + Ks * Ns + Ms * Ns) * 2.0
-    also["skinny_bf16_M16_N28672_K8192"] = {"us": us, "gbps": sk_bytes / us * 1e-3,
-                                            "frac_of_hbm_peak": sk_bytes / us * 1e-3 / PEAK_HBM_GBPS,
-                                            "picked": cfgs.describe()}
-    also["hbm_stream_gbps"] = g.gemm_probe_stream(dBs, scratch)
+    if not args.brief:
+        secondary(also, g, wl, np, torch, dev, sizes, timed_us)
 
     out = {
         "metric": "GEMM TFLOP/s (bf16 in, fp32 accumulate, bf16 out; analytic kernel selection included)",
