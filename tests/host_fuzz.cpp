@@ -1,11 +1,95 @@
-// Host-only fuzz driver for the selector entry points; built with the address and
-// undefined-behaviour sanitizers by tests/test_host_sanitizers.py (no GPU code involved).
+// Host-only fuzz driver for the selector-side entry points of the C ABI; built with the
+// address and undefined-behaviour sanitizers by tests/test_host_sanitizers.py (no GPU code
+// involved).  Random shapes, all dtypes, both storages of B, batches; every enumerated cfg
+// goes through gemm_predict and gemm_workspace_bytes, every Stream-K cfg through the plan
+// functions with a check that the workers' segments cover each K slab exactly once.
 #include "gemm.h"
 #include <cstdio>
 #include <cstdlib>
-int main(){ gemm_cfg c; gemm_prediction p; long n=0; unsigned s=1;
-  for(int it=0; it<3000; ++it){ s=s*1664525u+1013904223u; long M=1+(s>>8)%16384; s=s*1664525u+1013904223u; long N=16*(1+(s>>8)%1024); s=s*1664525u+1013904223u; long K=16*(1+(s>>8)%1024); int dt=it&1;
-    if(gemm_select(M,N,K,dt,&c)!=0){printf("select failed %ld %ld %ld\n",M,N,K);return 1;} if(gemm_predict(&c,&p)!=0) return 2; n+=c.kernel_id;
-    for(int i=0;i<gemm_cfg_count(dt);i+=7){ gemm_cfg d; int rc=gemm_cfg_at(i,M,N,K,dt,&d); if(rc!=0&&rc!=GEMM_ERR_CFG_ILLEGAL) return 3; } }
-  gemm_hw h; gemm_hw_get(&h); h.n_cu=304; h.n_xcd=8; gemm_hw_set(&h); gemm_select(4096,4096,4096,0,&c); gemm_hw_reset();
-  printf("ok %ld\n",n); return 0; }
+#include <vector>
+
+static unsigned s = 1;
+static long rnd(long n) { s = s * 1664525u + 1013904223u; return (long)((s >> 8) % (unsigned long)n); }
+
+static int check_stream_k(const gemm_cfg &c)
+{
+    int32_t plan[4];
+    if (gemm_stream_k_plan(&c, plan) != GEMM_OK)
+        return 10;
+    const int G = plan[0], sk = plan[1], S = plan[3];
+    std::vector<int> cover((size_t)sk * S, 0);
+    for (int g = 0; g < G; ++g) {
+        gemm_sk_segment seg[2];
+        const int n = gemm_stream_k_segments(&c, g, seg);
+        if (n < 1 || n > 2)
+            return 11;
+        for (int i = 0; i < n; ++i) {
+            if (seg[i].sk_tile < 0 || seg[i].sk_tile >= sk || seg[i].slab0 < 0 || seg[i].count < 1 ||
+                seg[i].slab0 + seg[i].count > S)
+                return 12;
+            for (int k = 0; k < seg[i].count; ++k)
+                ++cover[(size_t)seg[i].sk_tile * S + seg[i].slab0 + k];
+        }
+    }
+    for (int v : cover)
+        if (v != 1)
+            return 13;
+    for (int j = 0; j < sk; j += 1 + sk / 16) {
+        int32_t out3[3];
+        if (gemm_stream_k_contributors(&c, j, out3) != GEMM_OK || out3[0] > out3[1] || out3[1] >= G)
+            return 14;
+    }
+    gemm_sk_segment seg[2];
+    if (gemm_stream_k_segments(&c, G, seg) != GEMM_ERR_INDEX || gemm_stream_k_contributors(&c, sk, plan) != GEMM_ERR_INDEX)
+        return 15;
+    return 0;
+}
+
+int main()
+{
+    gemm_cfg c;
+    gemm_prediction p;
+    long acc = 0, n_sk = 0;
+    for (int it = 0; it < 1500; ++it) {
+        const long M = 1 + rnd(16384), N = 16 * (1 + rnd(1024)), K = 16 * (1 + rnd(1024));
+        const int dt = it % 3, bl = (it / 3) & 1;
+        const long batch = (it % 5 == 0) ? 1 + rnd(64) : 1;
+        if (gemm_select_batched(M, N, K, batch, dt, bl, &c) != GEMM_OK) {
+            printf("select failed %ld %ld %ld\n", M, N, K);
+            return 1;
+        }
+        if (gemm_predict(&c, &p) != GEMM_OK || !(p.total_us > 0))
+            return 2;
+        acc += c.kernel_id + (long)gemm_workspace_bytes(&c) % 7;
+        for (int i = (int)rnd(5); i < gemm_cfg_count(dt); i += 5) {
+            gemm_cfg d;
+            const int rc = gemm_cfg_at_batched(i, M, N, K, batch, dt, bl, &d);
+            if (rc == GEMM_ERR_CFG_ILLEGAL)
+                continue;
+            if (rc != GEMM_OK || gemm_predict(&d, &p) != GEMM_OK)
+                return 3;
+            if (d.stream_k) {
+                if (batch != 1)
+                    return 4;
+                ++n_sk;
+                const int e = check_stream_k(d);
+                if (e)
+                    return e;
+            }
+        }
+    }
+    // every preset installs, selects and resets
+    for (int id = 0; id < 2; ++id) {
+        gemm_hw h;
+        if (gemm_hw_preset(id, &h) != GEMM_OK || gemm_hw_set(&h) != GEMM_OK)
+            return 5;
+        if (gemm_select(4096 + 256 * id, 4096, 4096, 0, &c) != GEMM_OK)
+            return 6;
+        gemm_hw_reset();
+    }
+    gemm_hw h;
+    if (gemm_hw_preset(9, &h) != GEMM_ERR_INDEX || gemm_select_batched(64, 64, 64, 0, 0, 0, &c) != GEMM_ERR_SHAPE)
+        return 7;
+    printf("ok %ld stream-k cfgs %ld\n", acc, n_sk);
+    return n_sk > 100 ? 0 : 8;
+}

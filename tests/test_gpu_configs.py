@@ -315,3 +315,45 @@ def test_beta_random_data_padded_ldc_within_tolerance(g, oracle):
     out = dC.cpu().numpy().view(np.uint16)
     assert np.abs(bf16_to_f64(out[:, :N]) - ref64).max() <= tol
     assert np.all(out[:, N:] == 0x1234)
+
+
+# ---------------- gemm_run under HIP graph capture ----------------
+
+def test_graph_replays_match_eager_on_every_path(g, oracle):
+    """gemm_run only enqueues kernels (no allocation, no memset), so it can be captured.  Each
+    replay runs on fresh inputs written between replays by ordinary eager work and is compared
+    with the oracle: data-parallel, split-K (two kernels) and Stream-K (two kernels)."""
+    from gpu_util import to_dev, workspace_for
+    M, N, K = 520, 776, 1024
+    picks = {}
+    for idx in range(g.gemm_cfg_count(BF16)):
+        c = g.gemm_cfg_at(idx, M, N, K, BF16)
+        if c is None:
+            continue
+        path = "streamk" if c.stream_k else ("splitk" if c.split_k == 4 else "dp" if c.split_k == 1 else None)
+        if path and path not in picks and (c.block_m, c.block_n) == (128, 128):
+            picks[path] = c
+    assert set(picks) == {"dp", "splitk", "streamk"}
+    cases = []
+    for r in range(3):
+        A, B = wl.integer_bf16(M, N, K, seed=81, case=r)
+        cases.append((A, B, oracle.gemm(A, B, BF16)[0]))
+    dA, dB = to_dev(cases[0][0]).clone(), to_dev(cases[0][1]).clone()
+    dC = torch.empty((M, N), dtype=torch.int16, device="cuda")
+    for path, c in picks.items():
+        workspace_for(c)
+        g.gemm_run(c, dA, dB, dC)                       # warm-up outside capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            g.gemm_run(c, dA, dB, dC)
+        for A, B, ref16 in cases:
+            dA.copy_(to_dev(A))
+            dB.copy_(to_dev(B))
+            dC.fill_(0x7FC0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            out = dC.cpu().numpy().view(np.uint16)
+            assert np.array_equal(out, ref16), (path, c.describe())
+        del graph
