@@ -11,67 +11,74 @@
 
 // bf16: BLOCK_K in elements; MFMA 32 -> v_mfma_f32_32x32x16_bf16, 16 -> v_mfma_f32_16x16x32_bf16
 #define G355_VARIANTS_BF16_0(X)    \
-    X(256, 256, 64, 2, 4, 32, 2, 5143, 4344) \
-    X(256, 256, 64, 2, 2, 32, 2, 5212, 4282) \
-    X(256, 256, 32, 2, 4, 32, 4, 2726, 2130) \
-    X(256, 256, 32, 2, 2, 32, 4, 2974, 2216) \
-    X(256, 256, 32, 2, 4, 32, 5, 2740, 2122) \
-    X(256, 128, 64, 2, 4, 32, 3, 3159, 2327) \
-    X(256, 128, 64, 2, 2, 32, 3, 3428, 2437) \
-    X(128, 256, 64, 2, 4, 32, 3, 3162, 2277)
+    X(256, 256, 64, 2, 4, 32, 2, 5074, 4299) \
+    X(256, 256, 64, 2, 2, 32, 2, 5704, 4705) \
+    X(256, 256, 32, 2, 4, 32, 4, 2655, 2216) \
+    X(256, 256, 32, 2, 2, 32, 4, 2935, 2472) \
+    X(256, 256, 32, 2, 4, 32, 5, 2638, 2219) \
+    X(256, 128, 64, 2, 4, 32, 3, 3160, 2441) \
+    X(256, 128, 64, 2, 2, 32, 3, 3490, 2479) \
+    X(128, 256, 64, 2, 4, 32, 3, 3186, 2336)
 #define G355_VARIANTS_BF16_1(X)    \
-    X(128, 256, 64, 2, 2, 32, 3, 3415, 2429) \
-    X(128, 128, 64, 2, 2, 32, 2, 1356, 1175) \
-    X(128, 128, 64, 2, 2, 32, 3, 2072, 1381) \
-    X(128, 128, 128, 2, 2, 32, 2, 3445, 2802) \
-    X(128, 128, 32, 2, 2, 32, 4, 913, 728) \
-    X(256, 64, 64, 4, 1, 32, 2, 1432, 1308) \
-    X(64, 256, 64, 1, 4, 32, 2, 1560, 1382) \
-    X(128, 64, 64, 2, 2, 32, 3, 894, 716) \
-    X(64, 128, 64, 2, 2, 32, 3, 890, 713)
+    X(128, 256, 64, 2, 2, 32, 3, 3635, 2490) \
+    X(128, 128, 64, 2, 2, 32, 2, 1391, 1192) \
+    X(128, 128, 64, 2, 2, 32, 3, 2086, 1387) \
+    X(128, 128, 128, 2, 2, 32, 2, 3405, 2893) \
+    X(128, 128, 32, 2, 2, 32, 4, 890, 756) \
+    X(256, 64, 64, 4, 1, 32, 2, 1458, 1307) \
+    X(64, 256, 64, 1, 4, 32, 2, 1567, 1432) \
+    X(128, 64, 64, 2, 2, 32, 3, 895, 741) \
+    X(64, 128, 64, 2, 2, 32, 3, 913, 742)
 #define G355_VARIANTS_BF16_2(X)    \
-    X(64, 64, 64, 2, 2, 32, 3, 545, 447) \
-    X(64, 64, 128, 2, 2, 32, 2, 1013, 872) \
-    X(128, 32, 64, 4, 1, 32, 3, 750, 523) \
-    X(32, 256, 64, 1, 4, 32, 2, 1057, 956) \
-    X(32, 128, 64, 1, 4, 32, 3, 746, 532) \
-    X(32, 128, 128, 1, 4, 32, 2, 1137, 1005) \
-    X(32, 64, 128, 1, 2, 32, 3, 870, 595) \
-    X(64, 32, 128, 2, 1, 32, 3, 887, 576) \
-    X(32, 32, 128, 1, 1, 32, 3, 586, 374)
+    X(64, 64, 64, 2, 2, 32, 3, 546, 459) \
+    X(64, 64, 128, 2, 2, 32, 2, 1034, 915) \
+    X(128, 32, 64, 4, 1, 32, 3, 725, 539) \
+    X(32, 256, 64, 1, 4, 32, 2, 1054, 978) \
+    X(32, 128, 64, 1, 4, 32, 3, 710, 546) \
+    X(32, 128, 128, 1, 4, 32, 2, 1138, 1077) \
+    X(32, 64, 128, 1, 2, 32, 3, 855, 641) \
+    X(64, 32, 128, 2, 1, 32, 3, 910, 624) \
+    X(32, 32, 128, 1, 1, 32, 3, 602, 397)
 #define G355_VARIANTS_BF16_3(X)    \
-    X(16, 256, 64, 1, 4, 16, 4, 1718, 896) \
-    X(16, 256, 128, 1, 4, 16, 2, 2854, 2083) \
-    X(16, 128, 128, 1, 4, 16, 4, 1868, 1113) \
-    X(16, 128, 256, 1, 4, 16, 2, 3277, 2333) \
-    X(16, 64, 128, 1, 4, 16, 4, 680, 461) \
-    X(16, 64, 256, 1, 4, 16, 3, 2194, 1270) \
-    X(16, 32, 256, 1, 2, 16, 3, 998, 579) \
-    X(16, 16, 256, 1, 1, 16, 3, 794, 356)
+    X(16, 256, 64, 1, 4, 16, 4, 1687, 879) \
+    X(16, 256, 128, 1, 4, 16, 2, 2735, 2199) \
+    X(16, 128, 128, 1, 4, 16, 4, 1729, 964) \
+    X(16, 128, 256, 1, 4, 16, 2, 2955, 2302) \
+    X(16, 64, 128, 1, 4, 16, 4, 665, 481) \
+    X(16, 64, 256, 1, 4, 16, 3, 2059, 1255) \
+    X(16, 32, 256, 1, 2, 16, 3, 998, 587) \
+    X(16, 16, 256, 1, 1, 16, 3, 865, 388) \
+    X(256, 256, 64, 2, 4, 16, 2, 4441, 4090) \
+    X(256, 256, 64, 4, 2, 16, 2, 4794, 4111) \
+    X(256, 128, 64, 2, 4, 16, 3, 2911, 2340) \
+    X(128, 256, 64, 2, 4, 16, 3, 3066, 2337) \
+    X(128, 128, 64, 2, 4, 16, 2, 1302, 1161) \
+    X(128, 64, 64, 2, 4, 16, 3, 887, 745) \
+    X(64, 128, 64, 2, 4, 16, 3, 873, 731)
 
 // fp8 e4m3: MFMA 32 -> v_mfma_f32_32x32x64_f8f6f4, 16 -> v_mfma_f32_16x16x128_f8f6f4
 #define G355_VARIANTS_FP8_0(X)     \
-    X(256, 256, 128, 2, 4, 32, 2, 4706, 4180) \
-    X(256, 256, 128, 2, 2, 32, 2, 4913, 4183) \
-    X(256, 128, 128, 2, 4, 32, 3, 2701, 2386) \
-    X(128, 256, 128, 2, 4, 32, 3, 2510, 2239) \
-    X(128, 128, 128, 2, 2, 32, 2, 1197, 1126) \
-    X(128, 128, 128, 2, 2, 32, 3, 1995, 1419) \
-    X(128, 128, 256, 2, 2, 32, 2, 3550, 2779) \
-    X(128, 64, 128, 2, 2, 32, 3, 907, 732) \
-    X(64, 128, 128, 2, 2, 32, 3, 845, 731)
+    X(256, 256, 128, 2, 4, 32, 2, 4770, 4306) \
+    X(256, 256, 128, 2, 2, 32, 2, 5767, 4395) \
+    X(256, 128, 128, 2, 4, 32, 3, 2758, 2451) \
+    X(128, 256, 128, 2, 4, 32, 3, 2545, 2307) \
+    X(128, 128, 128, 2, 2, 32, 2, 1233, 1122) \
+    X(128, 128, 128, 2, 2, 32, 3, 2024, 1459) \
+    X(128, 128, 256, 2, 2, 32, 2, 3489, 2893) \
+    X(128, 64, 128, 2, 2, 32, 3, 933, 756) \
+    X(64, 128, 128, 2, 2, 32, 3, 878, 754)
 #define G355_VARIANTS_FP8_1(X)     \
-    X(64, 128, 256, 2, 2, 32, 3, 2599, 1826) \
-    X(64, 64, 128, 2, 2, 32, 3, 604, 470) \
-    X(64, 64, 256, 2, 2, 32, 2, 1221, 922) \
-    X(64, 256, 128, 1, 4, 32, 2, 1308, 1245) \
-    X(32, 256, 128, 1, 4, 32, 2, 1043, 910) \
-    X(32, 128, 256, 1, 4, 32, 2, 1139, 1036) \
-    X(32, 32, 256, 1, 1, 32, 3, 823, 385) \
-    X(16, 256, 256, 1, 4, 16, 2, 3058, 2371) \
-    X(16, 128, 256, 1, 4, 16, 4, 1951, 1123) \
-    X(16, 64, 256, 1, 4, 16, 4, 944, 483) \
-    X(16, 16, 256, 1, 1, 16, 4, 675, 177)
+    X(64, 128, 256, 2, 2, 32, 3, 2625, 1838) \
+    X(64, 64, 128, 2, 2, 32, 3, 600, 490) \
+    X(64, 64, 256, 2, 2, 32, 2, 1259, 961) \
+    X(64, 256, 128, 1, 4, 32, 2, 1362, 1818) \
+    X(32, 256, 128, 1, 4, 32, 2, 1049, 967) \
+    X(32, 128, 256, 1, 4, 32, 2, 1165, 1119) \
+    X(32, 32, 256, 1, 1, 32, 3, 978, 411) \
+    X(16, 256, 256, 1, 4, 16, 2, 2924, 2545) \
+    X(16, 128, 256, 1, 4, 16, 4, 1866, 1115) \
+    X(16, 64, 256, 1, 4, 16, 4, 924, 506) \
+    X(16, 16, 256, 1, 1, 16, 4, 684, 195)
 
 #define G355_VARIANTS_BF16(X) G355_VARIANTS_BF16_0(X) G355_VARIANTS_BF16_1(X) G355_VARIANTS_BF16_2(X) G355_VARIANTS_BF16_3(X)
 #define G355_VARIANTS_FP8(X) G355_VARIANTS_FP8_0(X) G355_VARIANTS_FP8_1(X)
