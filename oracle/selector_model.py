@@ -183,6 +183,12 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0, batch=1):
     l2_scope = hw["n_cu"] // hw["n_xcd"] * occ
     c1 = choose_cache_tile(l2_scope, v, tiles_m, tiles_n)
     c2 = choose_cache_tile(hw["n_cu"] * occ, v, tiles_m, tiles_n)
+    # READING: rows and columns of a tile that lie outside the matrix are never fetched, so the
+    # bytes a tile loads and Algorithm 5's unique / requested counts use the mean valid extent of
+    # a tile, M / tiles_m by N / tiles_n, instead of the nominal M_T by N_T.
+    bm_e, bn_e = M / tiles_m, N / tiles_n
+    for c in (c1, c2):
+        c["h"] = min(1.0, max(0.0, alg5_hit_rate(c["fm"], c["fn"], bm_e, bn_e, v["block_k"])))
     fp1 = (c1["fm"] * v["block_m"] + c1["fn"] * v["block_n"]) * v["block_k"] * es * 2.0
     fp2 = (c2["fm"] * v["block_m"] + c2["fn"] * v["block_n"]) * v["block_k"] * es * 2.0
     h1 = c1["h"] * min(1.0, hw["cache_eff_frac"] * hw["l2_bytes"] / fp1)
@@ -195,15 +201,17 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0, batch=1):
     out["iters"] = slabs - 1
     out_bytes = 4.0 if split_k > 1 else 2.0
 
-    def memory(per_cu, act, h_l2=None):
+    def memory(per_cu, act, h_l2=None, per_cu_mem=None):
         # Algorithm 7 in bytes and clocks.  READING: Ld_CU = (BM + BN) * BK bytes per tile; an LDS
         # fragment-read term is added; the HBM term carries the row-segment efficiency and the
         # latency is shared by the slabs in flight.
         hit1 = h1 if h_l2 is None else h_l2
-        a_bytes = v["block_m"] * v["block_k"] * es * per_cu
-        b_bytes = v["block_n"] * v["block_k"] * es * per_cu
+        # every load instruction of the nominal tile is issued; only the valid extent moves bytes
+        l_issue = (v["block_m"] + v["block_n"]) * v["block_k"] * es * per_cu / hw["vmem_bytes_per_clk"]
+        pcm = per_cu if per_cu_mem is None else per_cu_mem
+        a_bytes = bm_e * v["block_k"] * es * pcm
+        b_bytes = bn_e * v["block_k"] * es * pcm
         ld_cu = a_bytes + b_bytes
-        l_issue = ld_cu / hw["vmem_bytes_per_clk"]
         # READING: K-contiguous B is read with ds_read_b128 like A, row-major B with transpose reads
         b_rate = hw["lds_bytes_per_clk"] if b_layout else hw["lds_tr_bytes_per_clk"]
         l_lds = (v["block_m"] * v["waves_n"] * v["block_k"] * es / hw["lds_bytes_per_clk"]
@@ -219,13 +227,13 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0, batch=1):
         return dict(l_issue=l_issue, l_lds=l_lds, l_l2=l_l2, l_mall=l_mall, l_hbm=l_hbm,
                     l_mem=max(l_issue, l_lds, l_l2, l_mall, l_hbm))
 
-    def tile(per_cu, act):
+    def tile(per_cu, act, per_cu_mem=None):
         # READING of Algorithm 3's "high utilisation" assumption: the compute latency of a slab is
         # the variant's measured slab cost, scaled when the CU holds fewer tiles than fit.
         l_comp = v["slab_clk"] * per_cu
         if per_cu < occ:
             l_comp *= hw["under_occ_frac"] + (1.0 - hw["under_occ_frac"]) * per_cu / occ
-        m = memory(per_cu, act)
+        m = memory(per_cu, act, per_cu_mem=per_cu_mem)
         # Algorithm 8.  READING: fixed latency and per-workgroup cost in the prologue, output bytes
         # through the HBM rate plus a fixed cost in the epilogue, one exposed compute drain.
         l_pro = m["l_mem"] + hw["mem_latency_clk"] + hw["wg_overhead_clk"]
@@ -235,7 +243,9 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0, batch=1):
         return dict(m, l_compute=l_comp, l_prologue=l_pro, l_epilogue=l_epi, l_iter=l_iter, l_tile=l_tile)
 
     full = tile(float(occ), float(hw["n_cu"]))
-    tail = tile(float(tail_per_cu), float(active))
+    # READING: in the last wave a CU computes ceil(tail / active) tiles, but the bytes that wave moves
+    # are those of the tiles that exist: tail / active per CU.
+    tail = tile(float(tail_per_cu), float(active), tail_tiles / active)
     shown = full if waves > 1 else tail
     for k in ("l_compute", "l_issue", "l_lds", "l_l2", "l_mall", "l_hbm", "l_mem", "l_prologue", "l_epilogue",
               "l_iter", "l_tile"):

@@ -8,5 +8,6 @@ typedef hipError_t (*LaunchFn)(const KernelArgs &, hipStream_t);
 // (variant index inside the translation unit's list, storage of B: 0 row-major K x N, 1 K-contiguous N x K)
 LaunchFn kLaunchBf16_0(int, int), kLaunchBf16_1(int, int), kLaunchBf16_2(int, int), kLaunchBf16_3(int, int),
     kLaunchFp8_0(int, int), kLaunchFp8_1(int, int), kLaunchFp16_0(int, int), kLaunchFp16_1(int, int),
-    kLaunchFp16_2(int, int), kLaunchFp16_3(int, int);   // fp16 shares the bf16 variant lists
+    kLaunchFp16_2(int, int), kLaunchFp16_3(int, int), kLaunchBf16_4(int, int),
+    kLaunchFp16_4(int, int);   // fp16 shares the bf16 variant lists
 }  // namespace g355

@@ -246,14 +246,17 @@ static double segment_efficiency(const gemm_hw &hw, double seg)
 // Algorithm 7 for one K iteration.  `per_cu` = tiles a CU works on at once, `active` = CUs
 // busy.  Terms: per-CU vector-memory issue, LDS fragment reads (the software-managed-memory
 // bound of Section IV-D, which the printed algorithm leaves out), L2 (per XCD), MALL and HBM.
+// `bm_e` x `bn_e`: mean valid extent of a tile (rows and columns outside the matrix are never
+// fetched); `per_cu_mem`: tiles per CU whose bytes move (fractional in the last wave).
 static MemTerms memory_latency(const gemm_hw &hw, const Variant &v, int es, int b_layout, double per_cu, double active,
-                               double h1, double h2)
+                               double h1, double h2, double bm_e, double bn_e, double per_cu_mem)
 {
     MemTerms t;
-    const double a_bytes = (double)v.block_m * v.block_k * es * per_cu;   // per CU and iteration
-    const double b_bytes = (double)v.block_n * v.block_k * es * per_cu;
+    // every load instruction of the nominal tile is issued; only the valid extent moves bytes
+    t.l_issue = (double)(v.block_m + v.block_n) * v.block_k * es * per_cu / hw.vmem_bytes_per_clk;
+    const double a_bytes = bm_e * v.block_k * es * per_cu_mem;   // per CU and iteration
+    const double b_bytes = bn_e * v.block_k * es * per_cu_mem;
     const double ld_cu = a_bytes + b_bytes;
-    t.l_issue = ld_cu / hw.vmem_bytes_per_clk;
     // every wave reads its A rows (ds_read_b128) and its B columns (transpose reads, or
     // ds_read_b128 when B is K-contiguous) of the slab
     const double b_lds_rate = b_layout ? hw.lds_bytes_per_clk : hw.lds_tr_bytes_per_clk;
@@ -326,8 +329,10 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
     int fm_raw, fm2_raw;
     best_factor_pair(l2_scope, v, tiles_m, tiles_n, &fm, &fn, &fm_raw);
     best_factor_pair(hw.n_cu * occ, v, tiles_m, tiles_n, &fm2, &fn2, &fm2_raw);
-    double h1 = hit_rate(fm, fn, v.block_m, v.block_n);
-    double h2 = hit_rate(fm2, fn2, v.block_m, v.block_n);
+    // unique / requested counts of Algorithm 5 on the mean valid extent of a tile
+    const double bm_e = (double)M / tiles_m, bn_e = (double)N / tiles_n;
+    double h1 = hit_rate(fm, fn, bm_e, bn_e);
+    double h2 = hit_rate(fm2, fn2, bm_e, bn_e);
     // Capacity derate: the working set of one K step of the cache tile (two slabs in flight)
     // against the usable share of the cache; beyond it the hit rate shrinks in proportion.
     const double fp1 = (fm * v.block_m + fn * v.block_n) * v.block_k * es * 2.0;
@@ -346,13 +351,13 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
     p->iters = slabs - 1.0;
     const double out_bytes = (split_k > 1) ? 4.0 : 2.0;
 
-    auto tile_latency = [&](double per_cu, double act, MemTerms *mt_out, double *l_comp_out, double *pro, double *epi,
-                            double *iter) {
+    auto tile_latency = [&](double per_cu, double act, double per_cu_mem, MemTerms *mt_out, double *l_comp_out,
+                            double *pro, double *epi, double *iter) {
         // per_cu tiles share the CU; fewer than fit run a little faster each, but not in proportion
         double l_comp = (double)(b_layout ? v.slab_clk_kc : v.slab_clk) * per_cu;
         if (per_cu < occ)
             l_comp *= hw.under_occ_frac + (1.0 - hw.under_occ_frac) * per_cu / occ;
-        const MemTerms mt = memory_latency(hw, v, es, b_layout, per_cu, act, h1, h2);
+        const MemTerms mt = memory_latency(hw, v, es, b_layout, per_cu, act, h1, h2, bm_e, bn_e, per_cu_mem);
         const double l_pro = mt.l_mem + hw.mem_latency_clk + hw.wg_overhead_clk;
         // the store stage scales with the output tile only; results leave through HBM
         const double l_epi = act * per_cu * v.block_m * v.block_n * out_bytes / hw.hbm_bytes_per_clk + hw.epilogue_clk;
@@ -368,8 +373,10 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
 
     MemTerms mt_full, mt_tail;
     double lc_full, lc_tail, pro, epi, iter, pro_t, epi_t, iter_t;
-    const double l_tile_full = tile_latency((double)occ, (double)hw.n_cu, &mt_full, &lc_full, &pro, &epi, &iter);
-    const double l_tile_tail = tile_latency(tail_per_cu, active, &mt_tail, &lc_tail, &pro_t, &epi_t, &iter_t);
+    const double l_tile_full = tile_latency((double)occ, (double)hw.n_cu, (double)occ, &mt_full, &lc_full, &pro, &epi, &iter);
+    // the last wave moves the bytes of the tiles that exist: tail / active per CU
+    const double l_tile_tail =
+        tile_latency(tail_per_cu, active, tail_tiles / active, &mt_tail, &lc_tail, &pro_t, &epi_t, &iter_t);
     const bool has_full = waves > 1.0;
     const MemTerms &mt = has_full ? mt_full : mt_tail;
     p->l_compute = has_full ? lc_full : lc_tail;
@@ -409,7 +416,8 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
         const double w = sk * slabs / slots;
         const double tile_elems = (double)v.block_m * v.block_n;
         // workers that share an L2 are at different K offsets of different tiles: no L2 reuse
-        const MemTerms mt_sk = memory_latency(hw, v, es, b_layout, (double)occ, (double)hw.n_cu, 0.0, h2);
+        const MemTerms mt_sk =
+            memory_latency(hw, v, es, b_layout, (double)occ, (double)hw.n_cu, 0.0, h2, bm_e, bn_e, (double)occ);
         const double iter_sk = std::max(lc_full, mt_sk.l_mem);
         const double pro_sk = mt_sk.l_mem + hw.mem_latency_clk + hw.wg_overhead_clk;
         const double l_epi_sk = hw.n_cu * occ * tile_elems * 4.0 / hw.hbm_bytes_per_clk + hw.epilogue_clk;

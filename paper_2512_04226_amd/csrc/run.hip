@@ -123,6 +123,7 @@ LaunchFn launcher_of(int dtype, int id, int bl)
     constexpr int n_b0 = 0 G355_VARIANTS_BF16_0(G355_COUNT);
     constexpr int n_b1 = 0 G355_VARIANTS_BF16_1(G355_COUNT);
     constexpr int n_b2 = 0 G355_VARIANTS_BF16_2(G355_COUNT);
+    constexpr int n_b3 = 0 G355_VARIANTS_BF16_3(G355_COUNT);
     constexpr int n_f0 = 0 G355_VARIANTS_FP8_0(G355_COUNT);
 #undef G355_COUNT
     if (dtype == GEMM_FP16) {
@@ -132,7 +133,9 @@ LaunchFn launcher_of(int dtype, int id, int bl)
             return kLaunchFp16_1(id - n_b0, bl);
         if (id < n_b0 + n_b1 + n_b2)
             return kLaunchFp16_2(id - n_b0 - n_b1, bl);
-        return kLaunchFp16_3(id - n_b0 - n_b1 - n_b2, bl);
+        if (id < n_b0 + n_b1 + n_b2 + n_b3)
+            return kLaunchFp16_3(id - n_b0 - n_b1 - n_b2, bl);
+        return kLaunchFp16_4(id - n_b0 - n_b1 - n_b2 - n_b3, bl);
     }
     if (dtype == GEMM_BF16) {
         if (id < n_b0)
@@ -141,7 +144,9 @@ LaunchFn launcher_of(int dtype, int id, int bl)
             return kLaunchBf16_1(id - n_b0, bl);
         if (id < n_b0 + n_b1 + n_b2)
             return kLaunchBf16_2(id - n_b0 - n_b1, bl);
-        return kLaunchBf16_3(id - n_b0 - n_b1 - n_b2, bl);
+        if (id < n_b0 + n_b1 + n_b2 + n_b3)
+            return kLaunchBf16_3(id - n_b0 - n_b1 - n_b2, bl);
+        return kLaunchBf16_4(id - n_b0 - n_b1 - n_b2 - n_b3, bl);
     }
     if (id < n_f0)
         return kLaunchFp8_0(id, bl);

@@ -11,76 +11,86 @@
 
 // bf16: BLOCK_K in elements; MFMA 32 -> v_mfma_f32_32x32x16_bf16, 16 -> v_mfma_f32_16x16x32_bf16
 #define G355_VARIANTS_BF16_0(X)    \
-    X(256, 256, 64, 2, 4, 32, 2, 5074, 4299) \
-    X(256, 256, 64, 2, 2, 32, 2, 5704, 4705) \
-    X(256, 256, 32, 2, 4, 32, 4, 2655, 2216) \
-    X(256, 256, 32, 2, 2, 32, 4, 2935, 2472) \
-    X(256, 256, 32, 2, 4, 32, 5, 2638, 2219) \
-    X(256, 128, 64, 2, 4, 32, 3, 3160, 2441) \
-    X(256, 128, 64, 2, 2, 32, 3, 3490, 2479) \
-    X(128, 256, 64, 2, 4, 32, 3, 3186, 2336)
+    X(256, 256, 64, 2, 4, 32, 2, 5020, 4286) \
+    X(256, 256, 64, 2, 2, 32, 2, 5610, 4390) \
+    X(256, 256, 32, 2, 4, 32, 4, 2606, 2018) \
+    X(256, 256, 32, 2, 2, 32, 4, 2912, 2267) \
+    X(256, 256, 32, 2, 4, 32, 5, 2611, 2023) \
+    X(256, 128, 64, 2, 4, 32, 3, 3114, 2343) \
+    X(256, 128, 64, 2, 2, 32, 3, 3474, 2367) \
+    X(128, 256, 64, 2, 4, 32, 3, 3152, 2212)
 #define G355_VARIANTS_BF16_1(X)    \
-    X(128, 256, 64, 2, 2, 32, 3, 3635, 2490) \
-    X(128, 128, 64, 2, 2, 32, 2, 1391, 1192) \
-    X(128, 128, 64, 2, 2, 32, 3, 2086, 1387) \
-    X(128, 128, 128, 2, 2, 32, 2, 3405, 2893) \
-    X(128, 128, 32, 2, 2, 32, 4, 890, 756) \
-    X(256, 64, 64, 4, 1, 32, 2, 1458, 1307) \
-    X(64, 256, 64, 1, 4, 32, 2, 1567, 1432) \
-    X(128, 64, 64, 2, 2, 32, 3, 895, 741) \
-    X(64, 128, 64, 2, 2, 32, 3, 913, 742)
+    X(128, 256, 64, 2, 2, 32, 3, 3637, 2370) \
+    X(128, 128, 64, 2, 2, 32, 2, 1370, 1112) \
+    X(128, 128, 64, 2, 2, 32, 3, 2080, 1327) \
+    X(128, 128, 128, 2, 2, 32, 2, 3381, 2705) \
+    X(128, 128, 32, 2, 2, 32, 4, 885, 729) \
+    X(256, 64, 64, 4, 1, 32, 2, 1447, 1263) \
+    X(64, 256, 64, 1, 4, 32, 2, 1559, 1390) \
+    X(128, 64, 64, 2, 2, 32, 3, 874, 716) \
+    X(64, 128, 64, 2, 2, 32, 3, 886, 711)
 #define G355_VARIANTS_BF16_2(X)    \
-    X(64, 64, 64, 2, 2, 32, 3, 546, 459) \
-    X(64, 64, 128, 2, 2, 32, 2, 1034, 915) \
-    X(128, 32, 64, 4, 1, 32, 3, 725, 539) \
-    X(32, 256, 64, 1, 4, 32, 2, 1054, 978) \
-    X(32, 128, 64, 1, 4, 32, 3, 710, 546) \
-    X(32, 128, 128, 1, 4, 32, 2, 1138, 1077) \
-    X(32, 64, 128, 1, 2, 32, 3, 855, 641) \
-    X(64, 32, 128, 2, 1, 32, 3, 910, 624) \
-    X(32, 32, 128, 1, 1, 32, 3, 602, 397)
+    X(64, 64, 64, 2, 2, 32, 3, 531, 444) \
+    X(64, 64, 128, 2, 2, 32, 2, 1003, 878) \
+    X(128, 32, 64, 4, 1, 32, 3, 725, 530) \
+    X(32, 256, 64, 1, 4, 32, 2, 1033, 929) \
+    X(32, 128, 64, 1, 4, 32, 3, 710, 526) \
+    X(32, 128, 128, 1, 4, 32, 2, 1092, 1056) \
+    X(32, 64, 128, 1, 2, 32, 3, 855, 615) \
+    X(64, 32, 128, 2, 1, 32, 3, 909, 593) \
+    X(32, 32, 128, 1, 1, 32, 3, 603, 383)
 #define G355_VARIANTS_BF16_3(X)    \
-    X(16, 256, 64, 1, 4, 16, 4, 1687, 879) \
-    X(16, 256, 128, 1, 4, 16, 2, 2735, 2199) \
-    X(16, 128, 128, 1, 4, 16, 4, 1729, 964) \
-    X(16, 128, 256, 1, 4, 16, 2, 2955, 2302) \
-    X(16, 64, 128, 1, 4, 16, 4, 665, 481) \
-    X(16, 64, 256, 1, 4, 16, 3, 2059, 1255) \
-    X(16, 32, 256, 1, 2, 16, 3, 998, 587) \
-    X(16, 16, 256, 1, 1, 16, 3, 865, 388) \
-    X(256, 256, 64, 2, 4, 16, 2, 4441, 4090) \
-    X(256, 256, 64, 4, 2, 16, 2, 4794, 4111) \
-    X(256, 128, 64, 2, 4, 16, 3, 2911, 2340) \
-    X(128, 256, 64, 2, 4, 16, 3, 3066, 2337) \
-    X(128, 128, 64, 2, 4, 16, 2, 1302, 1161) \
-    X(128, 64, 64, 2, 4, 16, 3, 887, 745) \
-    X(64, 128, 64, 2, 4, 16, 3, 873, 731)
+    X(16, 256, 64, 1, 4, 16, 4, 1688, 879) \
+    X(16, 256, 128, 1, 4, 16, 2, 2733, 2198) \
+    X(16, 128, 128, 1, 4, 16, 4, 1728, 963) \
+    X(16, 128, 256, 1, 4, 16, 2, 2954, 2303) \
+    X(16, 64, 128, 1, 4, 16, 4, 664, 467) \
+    X(16, 64, 256, 1, 4, 16, 3, 2056, 1257) \
+    X(16, 32, 256, 1, 2, 16, 3, 997, 587) \
+    X(16, 16, 256, 1, 1, 16, 3, 847, 389)
+// 16x16x32 MFMA on the larger tiles, eight waves: fewer accumulator register bytes per flop than
+// 32x32x16, which is what counts once the chip is power-limited
+#define G355_VARIANTS_BF16_4(X)    \
+    X(256, 256, 64, 2, 4, 16, 2, 4300, 3964) \
+    X(256, 256, 64, 4, 2, 16, 2, 4689, 3978) \
+    X(256, 128, 64, 2, 4, 16, 3, 2890, 2239) \
+    X(128, 256, 64, 2, 4, 16, 3, 3065, 2163) \
+    X(128, 128, 64, 2, 4, 16, 2, 1265, 1128) \
+    X(128, 64, 64, 2, 4, 16, 3, 872, 737) \
+    X(64, 128, 64, 2, 4, 16, 3, 849, 705) \
+    X(128, 64, 64, 2, 4, 16, 2, 824, 817) \
+    X(64, 128, 64, 2, 4, 16, 2, 784, 729) \
+    X(64, 64, 64, 2, 4, 16, 3, 536, 447) \
+    X(64, 64, 128, 2, 4, 16, 2, 1017, 915) \
+    X(128, 128, 64, 4, 2, 16, 2, 1294, 1115) \
+    X(32, 64, 128, 1, 4, 16, 3, 781, 598)
 
 // fp8 e4m3: MFMA 32 -> v_mfma_f32_32x32x64_f8f6f4, 16 -> v_mfma_f32_16x16x128_f8f6f4
 #define G355_VARIANTS_FP8_0(X)     \
-    X(256, 256, 128, 2, 4, 32, 2, 4770, 4306) \
-    X(256, 256, 128, 2, 2, 32, 2, 5767, 4395) \
-    X(256, 128, 128, 2, 4, 32, 3, 2758, 2451) \
-    X(128, 256, 128, 2, 4, 32, 3, 2545, 2307) \
-    X(128, 128, 128, 2, 2, 32, 2, 1233, 1122) \
-    X(128, 128, 128, 2, 2, 32, 3, 2024, 1459) \
-    X(128, 128, 256, 2, 2, 32, 2, 3489, 2893) \
-    X(128, 64, 128, 2, 2, 32, 3, 933, 756) \
-    X(64, 128, 128, 2, 2, 32, 3, 878, 754)
+    X(256, 256, 128, 2, 4, 32, 2, 4601, 4238) \
+    X(256, 256, 128, 2, 2, 32, 2, 5758, 4236) \
+    X(256, 128, 128, 2, 4, 32, 3, 2669, 2322) \
+    X(128, 256, 128, 2, 4, 32, 3, 2504, 2217) \
+    X(128, 128, 128, 2, 2, 32, 2, 1168, 1084) \
+    X(128, 128, 128, 2, 2, 32, 3, 2020, 1365) \
+    X(128, 128, 256, 2, 2, 32, 2, 3471, 2845) \
+    X(128, 64, 128, 2, 2, 32, 3, 909, 741) \
+    X(64, 128, 128, 2, 2, 32, 3, 854, 743)
 #define G355_VARIANTS_FP8_1(X)     \
-    X(64, 128, 256, 2, 2, 32, 3, 2625, 1838) \
-    X(64, 64, 128, 2, 2, 32, 3, 600, 490) \
-    X(64, 64, 256, 2, 2, 32, 2, 1259, 961) \
-    X(64, 256, 128, 1, 4, 32, 2, 1362, 1818) \
-    X(32, 256, 128, 1, 4, 32, 2, 1049, 967) \
-    X(32, 128, 256, 1, 4, 32, 2, 1165, 1119) \
-    X(32, 32, 256, 1, 1, 32, 3, 978, 411) \
-    X(16, 256, 256, 1, 4, 16, 2, 2924, 2545) \
-    X(16, 128, 256, 1, 4, 16, 4, 1866, 1115) \
-    X(16, 64, 256, 1, 4, 16, 4, 924, 506) \
-    X(16, 16, 256, 1, 1, 16, 4, 684, 195)
+    X(64, 128, 256, 2, 2, 32, 3, 2622, 1772) \
+    X(64, 64, 128, 2, 2, 32, 3, 576, 470) \
+    X(64, 64, 256, 2, 2, 32, 2, 1229, 933) \
+    X(64, 256, 128, 1, 4, 32, 2, 1317, 1766) \
+    X(32, 256, 128, 1, 4, 32, 2, 1025, 928) \
+    X(32, 128, 256, 1, 4, 32, 2, 1144, 1075) \
+    X(32, 32, 256, 1, 1, 32, 3, 979, 412) \
+    X(16, 256, 256, 1, 4, 16, 2, 2926, 2548) \
+    X(16, 128, 256, 1, 4, 16, 4, 1863, 1114) \
+    X(16, 64, 256, 1, 4, 16, 4, 921, 493) \
+    X(16, 16, 256, 1, 1, 16, 4, 684, 196)
 
-#define G355_VARIANTS_BF16(X) G355_VARIANTS_BF16_0(X) G355_VARIANTS_BF16_1(X) G355_VARIANTS_BF16_2(X) G355_VARIANTS_BF16_3(X)
+#define G355_VARIANTS_BF16(X) \
+    G355_VARIANTS_BF16_0(X) G355_VARIANTS_BF16_1(X) G355_VARIANTS_BF16_2(X) G355_VARIANTS_BF16_3(X) G355_VARIANTS_BF16_4(X)
 #define G355_VARIANTS_FP8(X) G355_VARIANTS_FP8_0(X) G355_VARIANTS_FP8_1(X)
 
 namespace g355 {
