@@ -114,14 +114,21 @@ struct Tile {
     __device__ static inline int a_off(int row, int chunk) { return row * RA + ((chunk ^ a_key(row)) << 4); }
     // B rows are N-contiguous; a transpose read touches SEG bytes of each of several
     // consecutive k rows, so the SEG-sized block index inside a row is XORed with a key of k
-    // that spreads consecutive rows over 256 bytes of banks.
+    // that spreads consecutive rows over 256 bytes of banks.  With the 16x16 MFMA the two
+    // 16-lane groups that are served together read the same 32 bytes of k rows 8 apart, so
+    // for 16-bit types the 32-byte half inside a segment is flipped by bit 3 of k as well
+    // (a no-op for the 32x32 pattern, whose paired groups already differ by 32 bytes of n).
     static constexpr int SEG_BITS = (ES == 2) ? 6 : 5;
     static constexpr int SEG = 1 << SEG_BITS;
     static constexpr int B_SPREAD = 256 / SEG;
     static constexpr int B_ROW_DIV = (RB >= 256) ? 1 : 256 / RB;
     static constexpr int B_KEY_MASK = (((RB / SEG) < B_SPREAD) ? ((RB / SEG) > 0 ? (RB / SEG) : 1) : B_SPREAD) - 1;
-    __device__ static inline int b_key(int krow) { return (krow / B_ROW_DIV) & B_KEY_MASK; }
-    __device__ static inline int b_off(int krow, int nbyte) { return krow * RB + (nbyte ^ (b_key(krow) << SEG_BITS)); }
+    static constexpr int B_HALF_FLIP = (ES == 2 && RB >= 64) ? 32 : 0;
+    __device__ static inline int b_key(int krow)
+    {
+        return (((krow / B_ROW_DIV) & B_KEY_MASK) << SEG_BITS) ^ (((krow >> 3) & 1) * B_HALF_FLIP);
+    }
+    __device__ static inline int b_off(int krow, int nbyte) { return krow * RB + (nbyte ^ b_key(krow)); }
 };
 
 // Workgroup id -> (tile_m, tile_n, k_slice).  Hardware deals consecutive workgroup ids
@@ -233,7 +240,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         const int c = (i * T::NW + wave) * 64 + lane;
         const int row = c / T::CB;
         if constexpr (T::BL == 0) {
-            const int lbyte = ((c % T::CB) * 16) ^ (T::b_key(row) << T::SEG_BITS);
+            const int lbyte = ((c % T::CB) * 16) ^ T::b_key(row);
             const bool ok = n0 + lbyte / ES < args.N;
             b_voff[i] = ok ? (unsigned)(row * args.ldb * ES + lbyte) : OOB_OFFSET;
             b_kcol[i] = 0;
