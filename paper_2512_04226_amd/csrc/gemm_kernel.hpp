@@ -3,15 +3,20 @@
 // MFMA k-steps in time).  One template covers the whole variant table.
 //
 //   A  M x K row-major, B  K x N row-major (or N x K row-major, K-contiguous), C  M x N
-//   row-major bf16 (or fp32 partial slabs when the reduction is split across workgroups).
+//   row-major bf16 (fp16 for fp16 inputs), or fp32 partials when the reduction of a tile is
+//   shared between workgroups (split-K slabs, Stream-K partial tiles).  blockIdx.y selects
+//   the problem of a strided batch.
 //
-// Data path per K slab: 128-bit buffer loads straight into LDS (A along K, B along N,
+// Data path per K slab: 128-bit buffer loads straight into LDS (A along K, B along N or K,
 // out-of-range chunks arrive as zero; no register staging) -> swizzled LDS ring of NS
-// stages -> MFMA fragments.  A is read from LDS with ds_read_b128 (K-contiguous); B is
-// N-contiguous in LDS and is read with the
-// gfx950 transpose loads (ds_read_b64_tr_b16 / _tr_b8) so that each lane receives
-// K-contiguous values.  The MFMA's row operand is fed from B and its column operand from
-// A, so that a lane ends up with 4 consecutive n of one output row (8- or 16-byte stores).
+// stages -> MFMA fragments.  A is read from LDS with ds_read_b128 (K-contiguous); row-major
+// B is N-contiguous in LDS and is read with the gfx950 transpose loads (ds_read_b64_tr_b16 /
+// _tr_b8) so that each lane receives K-contiguous values; K-contiguous B is read like A.
+// The MFMA's row operand is fed from B and its column operand from A, so that a lane ends
+// up with 4 consecutive n of one output row (8- or 16-byte stores).
+//
+// A workgroup computes one (tile, K slice), or -- as a Stream-K worker -- up to two
+// (tile, slab range) segments, with the same prologue / K loop / epilogue body.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
