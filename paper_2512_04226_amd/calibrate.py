@@ -71,6 +71,9 @@ def main():
         rows = measure_slab_clk(dtype, args.n, 0)
         rows_kc = measure_slab_clk(dtype, args.n, 1)
         for (cfg, us, tau), (_, us_kc, tau_kc) in zip(rows, rows_kc):
+            # the K-contiguous gain of a small tile on this huge problem (L2-resident panels, hundreds of
+            # waves) is larger than what the small problems that pick such tiles see: floor it
+            tau_kc = max(tau_kc, 0.9 * tau)
             print("    X(%d, %d, %d, %d, %d, %d, %d, %d, %d)   // %.1f us %.0f TFLOP/s | K-contiguous B %.1f us %.0f TFLOP/s" % (
                 cfg.block_m, cfg.block_n, cfg.block_k, cfg.waves_m, cfg.waves_n, cfg.mfma, cfg.stages, round(tau),
                 round(tau_kc), us, 2.0 * args.n ** 3 / us * 1e-6, us_kc, 2.0 * args.n ** 3 / us_kc * 1e-6), flush=True)

@@ -47,13 +47,13 @@ static gemm_hw make_default_hw()
     h.l2_bytes = 4.0 * 1024 * 1024;
     h.mall_bytes = 256.0 * 1024 * 1024;
     h.clk_ghz = 2.4;
-    h.hbm_bytes_per_clk = 2500.0;    // 6.0 TB/s sustained of the 8 TB/s pins
+    h.hbm_bytes_per_clk = 2700.0;    // 6.5 TB/s: the streaming-read probe's rate, of the 8 TB/s pins
     h.mall_bytes_per_clk = 4000.0;   // what L2 misses are served at when the MALL holds the data (fitted; a streaming read sees 6.5 TB/s)
     h.l2_bytes_per_clk = 2048.0;     // 16 channels x 128 B per XCD
     h.lds_bytes_per_clk = 118.0;     // ds_read_b128 fragments
     h.lds_tr_bytes_per_clk = 62.0;   // ds_read_b64_tr_* fragments
     h.vmem_bytes_per_clk = 64.0;
-    h.mem_latency_clk = 3060.0;
+    h.mem_latency_clk = 2500.0;
     h.cache_eff_frac = 0.5;
     h.launch_clk = 1137.5;
     h.wg_overhead_clk = 666.4;
