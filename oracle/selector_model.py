@@ -222,7 +222,11 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0, batch=1):
         l_mall = (1.0 - hit1) * total / hw["mall_bytes_per_clk"]
         ea = segment_efficiency(hw, v["block_k"] * es)
         eb = segment_efficiency(hw, (v["block_k"] if b_layout else v["block_n"]) * es)
-        t_m = (1.0 - h2) * (1.0 - hit1) * (a_bytes / ea + b_bytes / eb) * act
+        # READING: Algorithm 7 multiplies (1 - H1)(1 - H2), but both rates come from Algorithm 5 on
+        # nested scopes, so H2 already contains the reuse H1 counts; the product would let fewer
+        # bytes reach HBM than the matrices hold.  The share of requested bytes that reaches HBM is
+        # what neither scope can serve: min(1 - H1, 1 - H2).
+        t_m = min(1.0 - h2, 1.0 - hit1) * (a_bytes / ea + b_bytes / eb) * act
         l_hbm = t_m / hw["hbm_bytes_per_clk"] + hw["mem_latency_clk"] / max(1.0, per_cu * (v["stages"] - 1))
         return dict(l_issue=l_issue, l_lds=l_lds, l_l2=l_l2, l_mall=l_mall, l_hbm=l_hbm,
                     l_mem=max(l_issue, l_lds, l_l2, l_mall, l_hbm))

@@ -270,7 +270,10 @@ static MemTerms memory_latency(const gemm_hw &hw, const Variant &v, int es, int 
     // what misses both caches, inflated by the row-segment efficiency of each operand
     const double ea = segment_efficiency(hw, (double)v.block_k * es);
     const double eb = segment_efficiency(hw, (double)(b_layout ? v.block_k : v.block_n) * es);
-    const double tm = (1.0 - h2) * (1.0 - h1) * (a_bytes / ea + b_bytes / eb) * active;
+    // Both hit rates come from Algorithm 5 on nested scopes, so h2 already contains the reuse h1
+    // counts: the share of requested bytes that reaches HBM is what neither scope can serve,
+    // min(1 - h1, 1 - h2), not the product (which could fall below the bytes the matrices hold).
+    const double tm = std::min(1.0 - h2, 1.0 - h1) * (a_bytes / ea + b_bytes / eb) * active;
     t.l_hbm = tm / hw.hbm_bytes_per_clk + hw.mem_latency_clk / std::max(1.0, per_cu * (v.stages - 1));
     t.l_mem = std::max(std::max(t.l_issue, t.l_lds), std::max(std::max(t.l_l2, t.l_mall), t.l_hbm));
     return t;
