@@ -167,3 +167,21 @@ def test_small_and_skinny_problems_do_not_get_one_giant_tile():
         assert c.block_m <= 64, c.describe()
     c = g.gemm_select(512, 512, 512, g.GEMM_BF16)
     assert not (c.block_m == 256 and c.block_n == 256 and c.split_k == 1)
+
+
+def test_run_rejects_operand_windows_of_2_gib_and_more():
+    """The kernel addresses a tile's operands with 32-bit byte offsets: leading dimensions that put a
+    tile's A rows, or B's K extent, 2 GiB apart must be refused before any launch."""
+    run = g._lib.gemm_run
+    p = ctypes.c_void_p(0x1000)
+    cfg = g.gemm_select(256, 8192, 8192, g.GEMM_BF16)
+    # only rejected configurations are passed to gemm_run here: nothing may reach a launch with these pointers
+    bad = cfg.copy(); bad.lda = (1 << 31) // (2 * bad.block_m)       # block_m rows * lda * 2 bytes = 2 GiB
+    assert run(ctypes.byref(bad), p, p, p, None) == -2
+    k_slice = -(-8192 // cfg.split_k)                                 # B's window spans one K slice
+    bad = cfg.copy(); bad.ldb = ((1 << 31) // (2 * k_slice) + 7) // 8 * 8  # K-slice rows * ldb * 2 bytes >= 2 GiB
+    assert run(ctypes.byref(bad), p, p, p, None) == -2
+    kc = g.gemm_select_ex(256, 8192, 8192, g.GEMM_BF16, g.GEMM_B_K_CONTIGUOUS)
+    bad = kc.copy(); bad.ldb = (1 << 31) // (2 * bad.block_n)
+    assert run(ctypes.byref(bad), p, p, p, None) == -2
+    assert g._lib.gemm_select((1 << 30) + 8, 8, 8, 0, ctypes.byref(cfg)) == -2

@@ -357,3 +357,24 @@ def test_graph_replays_match_eager_on_every_path(g, oracle):
             out = dC.cpu().numpy().view(np.uint16)
             assert np.array_equal(out, ref16), (path, c.describe())
         del graph
+
+
+def test_very_deep_reduction_bit_exact(g, oracle):
+    """K = 131072 with a 64 x 64 output: 2048 slabs per tile, split-K up to 32 and Stream-K; integer
+    operands keep every fp32 partial sum exact (|sum| <= 16 K < 2^24)."""
+    from gpu_util import run_cfg, to_dev
+    M, N, K = 64, 64, 131072
+    A, B = wl.integer_bf16(M, N, K, seed=91)
+    ref16, _ = oracle.gemm(A, B, BF16)
+    dA, dB = to_dev(A), to_dev(B)
+    kinds = set()
+    cfgs = [g.gemm_select(M, N, K, BF16)]
+    for idx in range(g.gemm_cfg_count(BF16)):
+        c = g.gemm_cfg_at(idx, M, N, K, BF16)
+        if c is not None and (c.block_m, c.block_n) in ((64, 64), (16, 16), (32, 32)) and (c.split_k in (1, 32) or c.stream_k):
+            cfgs.append(c)
+    for c in cfgs:
+        out = run_cfg(c, dA, dB, M, N)
+        assert np.array_equal(out, ref16), (c.describe(), int((out != ref16).sum()))
+        kinds.add("streamk" if c.stream_k else "split%d" % c.split_k)
+    assert {"split1", "split32", "streamk"} <= kinds
