@@ -95,16 +95,20 @@ def secondary(also, g, wl, np, torch, dev, sizes, timed_us):
 
     # the vendor library on the same box and operands (calibration of what this chip sustains on
     # N(0,1) data under its power limit; not a baseline and not part of the product path)
-    a16, b16 = dev[n_big][0].view(torch.bfloat16), dev[n_big][1].view(torch.bfloat16)
-    for _ in range(3):
-        torch.matmul(a16, b16)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(10):
-        torch.matmul(a16, b16)
-    e1.record()
-    e1.synchronize()
-    also["calibration_torch_matmul_bf16_%d_tflops" % n_big] = 2.0 * n_big ** 3 / (e0.elapsed_time(e1) * 1e-4) * 1e-12
+    try:
+        a16, b16 = dev[n_big][0].view(torch.bfloat16), dev[n_big][1].view(torch.bfloat16)
+        for _ in range(3):
+            torch.matmul(a16, b16)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            torch.matmul(a16, b16)
+        e1.record()
+        e1.synchronize()
+        also["calibration_torch_matmul_bf16_%d_tflops" % n_big] = 2.0 * n_big ** 3 / (e0.elapsed_time(e1) * 1e-4) * 1e-12
+    except Exception as exc:   # the calibration figure is optional; the product figures above are not
+        also["calibration_torch_matmul_bf16_%d_tflops" % n_big] = None
+        print("bench.py: vendor calibration skipped (%s)" % exc, file=sys.stderr)
 
 
 def main():
