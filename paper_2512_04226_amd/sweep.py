@@ -23,9 +23,10 @@ from . import workloads as wl
 def make_operands(M, N, K, dtype, seed=0):
     """Random device operands of the right type (values do not affect timing)."""
     gen = torch.Generator(device="cuda").manual_seed(seed)
-    if dtype == g.GEMM_BF16:
-        A = (torch.rand((M, K), device="cuda", generator=gen) * 2 - 1).to(torch.bfloat16)
-        B = (torch.rand((K, N), device="cuda", generator=gen) * 2 - 1).to(torch.bfloat16)
+    if dtype in (g.GEMM_BF16, g.GEMM_FP16):
+        t = torch.bfloat16 if dtype == g.GEMM_BF16 else torch.float16
+        A = (torch.rand((M, K), device="cuda", generator=gen) * 2 - 1).to(t)
+        B = (torch.rand((K, N), device="cuda", generator=gen) * 2 - 1).to(t)
     else:
         A = torch.randint(0, 0x78, (M, K), device="cuda", generator=gen, dtype=torch.uint8)
         B = torch.randint(0, 0x78, (K, N), device="cuda", generator=gen, dtype=torch.uint8)
@@ -109,6 +110,8 @@ def shape_set(name):
         return [(m, n, k, g.GEMM_BF16) for (n, k) in wl.SKINNY_NK for m in wl.SKINNY_M]
     if name == "fp8":
         return [(n, n, n, g.GEMM_FP8_E4M3) for n in (1024, 4096, 8192)]
+    if name == "fp16":      # the paper's precision; run with --b-layout 1 for its operand layout too
+        return [(n, n, n, g.GEMM_FP16) for n in (1024, 2048, 4096, 8192)] + [(4864, 4096, 4096, g.GEMM_FP16)]
     raise SystemExit("unknown shape set " + name)
 
 
