@@ -26,6 +26,7 @@ def test_every_declared_symbol_is_exported():
     lib = ctypes.CDLL(g.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
+        assert callable(getattr(g, n, None)), "the binding has no function named %s" % n
     assert g.gemm_abi_version() == g.GEMM_ABI_VERSION
 
 
