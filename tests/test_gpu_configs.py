@@ -89,6 +89,25 @@ def test_config5_irregular_shapes(g, oracle):
         _check_rows(g, oracle, A, B, BF16, cfg, 1.0, 1.0, 1.0, rows=rows)
 
 
+def test_config5_irregular_shapes_k_contiguous_b(g, oracle):
+    """The same 64 shapes with B stored N x K: the K-contiguous selector's picks (other tiles, other
+    split and Stream-K choices than above) against sampled oracle rows."""
+    from gpu_util import bf16_to_f64, run_cfg, to_dev
+    shapes = wl.config5_shapes()
+    n_sk = 0
+    for i, (M, N, K) in enumerate(shapes):
+        A, B = wl.config5(i, shapes)
+        cfg = g.gemm_select_ex(M, N, K, BF16, g.GEMM_B_K_CONTIGUOUS)
+        n_sk += cfg.stream_k
+        rows = _rows_to_check(M, cfg.block_m, n_random=1, seed=100 + i)
+        out = run_cfg(cfg, to_dev(A), to_dev(np.ascontiguousarray(B.T)), M, N)
+        _, ref64 = oracle.gemm_rows(A, B, rows, BF16)
+        err = float(np.max(np.abs(bf16_to_f64(out[rows]) - ref64)))
+        assert err <= oracle.tolerance(K, 1.0, 1.0, BF16), (cfg.describe(), err)
+        assert not np.any((out & 0x7FFF) > 0x7F80), "NaN left in the output"
+    assert n_sk >= 1
+
+
 def test_fp8_random_every_variant_within_tolerance(g, oracle):
     """Random e4m3 data (not exact in fp32): every variant against the full oracle product."""
     from gpu_util import bf16_to_f64, run_cfg, to_dev
