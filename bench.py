@@ -119,6 +119,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--brief", action="store_true", help="skip the secondary figures (for profiler runs)")
     ap.add_argument("--cpu-rows", type=int, default=4096)
+    ap.add_argument("--ordering", choices=("default", "no-xcd-remap", "ungrouped", "neither"), default="default",
+                    help="diagnostic: run the timed steps with the XCD renumbering and / or the grouped tile order "
+                         "switched off in the cfg (for counter runs that show what the rasterisation buys)")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy, so that HBM byte counters "
                          "collected around this command can be scaled against a transfer of known size")
@@ -152,6 +155,10 @@ def main():
     def step(events=None):
         for n in sizes:
             cfg = g.gemm_select(n, n, n, g.GEMM_BF16)
+            if args.ordering in ("no-xcd-remap", "neither"):
+                cfg.xcd_remap = 0
+            if args.ordering in ("ungrouped", "neither"):
+                cfg.group_m = 1
             dA, dB, dC = dev[n]
             if events is not None and n == sizes[-1]:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -220,7 +227,7 @@ def main():
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "square bf16 GEMM M=N=K=4096 then 8192, row-major A and B, N(0,1) seed 1",
-                   "picked_4096": cfg_small.describe(), "picked_8192": cfg_big.describe(),
+                   "picked_4096": cfg_small.describe(), "picked_8192": cfg_big.describe(), "ordering": args.ordering,
                    "select_us": select_us},
         "frac_of_mfma_peak": value / PEAK_TFLOPS["bf16"],
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
