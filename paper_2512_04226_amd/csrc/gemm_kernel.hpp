@@ -167,7 +167,7 @@ constexpr unsigned OOB_OFFSET = 0x80000000u;
 template <class T>
 __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
 {
-    constexpr int ES = T::ES, BM = T::BM, BN = T::BN, BK = T::BK, MI = T::MI, NT = T::NT;
+    constexpr int ES = T::ES, BM = T::BM, BN = T::BN, BK = T::BK, MI = T::MI;
     __shared__ __attribute__((aligned(1024))) uint8_t smem[T::NS * T::STAGE];
 
     // Work of this workgroup: one (tile, K slice) for a data-parallel or split-K launch, up to
