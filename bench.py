@@ -50,7 +50,7 @@ def cpu_baseline(A, B, rows):
             "sample": "%d evenly spaced rows of the 8192^3 product (%.1f s)" % (rows, dt)}
 
 
-def secondary(also, g, wl, np, torch, dev, sizes, timed_us):
+def secondary(also, g, wl, np, torch, dev, sizes, timed_us, ensure_ws):
     """Figures outside the timed region: per-shape rates, the other layouts, precisions and the
     bandwidth-bound path, and the measured ceilings the rooflines are also quoted against."""
     for n in sizes:
@@ -92,6 +92,46 @@ def secondary(also, g, wl, np, torch, dev, sizes, timed_us):
                                             "frac_of_hbm_peak": sk_bytes / us * 1e-3 / PEAK_HBM_GBPS,
                                             "picked": cfgs.describe()}
     also["hbm_stream_gbps"] = g.gemm_probe_stream(dBs, scratch)
+    del dBs
+
+    # grouped launch: 16 groups of routing-like row counts (16384 rows in all) against one 4096 x 4096
+    # weight each, in one launch; beside it the same products as 16 separately selected launches
+    rows = wl.routed_rows(16, 16384, seed=6)
+    Ng = Kg = 4096
+    shapes = [(m, Ng, Kg) for m in rows]
+    Ag, Bg = wl.normal_bf16(sum(rows), Ng * 2, Kg, seed=6)          # two weights, shared alternately
+    dAg = torch.from_numpy(Ag.view(np.int16)).cuda()
+    dBg = [torch.from_numpy(np.ascontiguousarray(Bg[:, i * Ng:(i + 1) * Ng]).view(np.int16)).cuda() for i in range(2)]
+    dCg = torch.empty((sum(rows), Ng), dtype=torch.int16, device="cuda")
+    tensors, r0 = [], 0
+    for i, m in enumerate(rows):
+        tensors.append((dAg[r0:r0 + m], dBg[i % 2], dCg[r0:r0 + m]) if m else (None, None, None))
+        r0 += m
+    probs = g.make_problems(shapes, 0, tensors)
+    cfg_g = g.gemm_select_grouped(probs, g.GEMM_BF16)
+    table, _ = g.gemm_grouped_plan(cfg_g, probs)
+    dtab = g.table_to_device(table)
+    singles = [(g.gemm_select(m, Ng, Kg, g.GEMM_BF16), t) for m, t in zip(rows, tensors) if m]
+    ensure_ws(max(g.gemm_workspace_bytes(c1) for c1, _ in singles))   # a single pick may split K
+
+    def time_loop(fn, reps=10):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
+    flops_g = 2.0 * sum(rows) * Ng * Kg
+    us_g = time_loop(lambda: g.gemm_run_grouped(cfg_g, table, dtab))
+    us_s = time_loop(lambda: [g.gemm_run(c1, *t) for c1, t in singles])
+    also["grouped_bf16_16x(m,4096,4096)_16384_rows"] = {
+        "tflops": flops_g / us_g * 1e-6, "us": us_g, "picked": cfg_g.describe(),
+        "separate_launches_tflops": flops_g / us_s * 1e-6, "rows": rows}
+    del Ag, Bg, dAg, dBg, dCg
 
     # the vendor library on the same box and operands (calibration of what this chip sustains on
     # N(0,1) data under its power limit; not a baseline and not part of the product path)
@@ -201,12 +241,14 @@ def main():
 
     # ---- secondary figures (outside the timed region above): per-shape rates, the fp8 and the
     # bandwidth-bound paths, and the measured ceilings both rooflines are also quoted against
-    def timed_us(cfg, dA, dB, dC, reps=10):
-        need = g.gemm_workspace_bytes(cfg)
+    def ensure_ws(need):
         nonlocal ws
         if need and (ws is None or ws.numel() * 4 < need):
             ws = torch.empty(need // 4, dtype=torch.float32, device="cuda")
             g.gemm_set_workspace(ws)
+
+    def timed_us(cfg, dA, dB, dC, reps=10):
+        ensure_ws(g.gemm_workspace_bytes(cfg))
         for _ in range(2):
             g.gemm_run(cfg, dA, dB, dC)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -219,7 +261,7 @@ def main():
 
     also = {}
     if not args.brief:
-        secondary(also, g, wl, np, torch, dev, sizes, timed_us)
+        secondary(also, g, wl, np, torch, dev, sizes, timed_us, ensure_ws)
 
     out = {
         "metric": "GEMM TFLOP/s (bf16 in, fp32 accumulate, bf16 out; analytic kernel selection included)",

@@ -29,7 +29,7 @@
 extern "C" {
 #endif
 
-#define GEMM_ABI_VERSION 4u
+#define GEMM_ABI_VERSION 5u
 
 typedef enum gemm_dtype {
     GEMM_BF16 = 0,     /* A, B bf16; C bf16 */
@@ -127,7 +127,8 @@ typedef struct gemm_cfg {
     float beta;               /* default 0; C = alpha*A*B + beta*C (Section II-A).  0: C is written without being read */
     double predicted_us;      /* model's total latency for this cfg */
     int32_t batch;            /* independent problems of this shape in one launch (default 1) */
-    int32_t reserved1;
+    int32_t groups;           /* 0, or the number of groups of a grouped cfg (gemm_select_grouped): M, N, K then hold
+                                 the largest extents over the groups and the cfg runs through gemm_run_grouped only */
     int64_t stride_a, stride_b, stride_c; /* elements between consecutive problems' A, B, C; gemm_select_batched
                                              sets the dense values M*lda, (K or N)*ldb, M*ldc */
 } gemm_cfg;
@@ -179,6 +180,55 @@ int gemm_select_ex(int64_t M, int64_t N, int64_t K, int dtype, int b_layout, gem
 int gemm_select_batched(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int b_layout, gemm_cfg *out);
 int gemm_cfg_at_batched(int idx, int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int b_layout,
                         gemm_cfg *out);
+
+/*
+ * Grouped GEMM: n_groups independent products C_g = alpha*A_g*B_g + beta*C_g of DIFFERENT shapes
+ * (one dtype, one storage of B, one alpha and beta) in ONE launch of one kernel variant -- the
+ * grouped dimension that Sections II-B and V-C name as a further multiplier of a tuning search
+ * and that costs the analytical selector one more pass of the model over the groups.
+ *
+ *   gemm_problem      host-side description of one group.  M may be 0 (an empty group: nothing is
+ *                     read or written, its pointers may be NULL); N, K >= 1 and aligned as for
+ *                     gemm_select.  A, B, C: device pointers, 16-byte aligned; ld* in elements.
+ *                     gemm_select_grouped / gemm_cfg_at_grouped read M, N, K only.
+ *   gemm_select_grouped  arg-min over the variants that are legal for every non-empty group (no
+ *                     split-K, no Stream-K).  Model: Algorithm 4 counts the tiles of all groups
+ *                     together, T = sum T_g, omega = ceil(T / workgroup slots); Algorithm 8 gives each
+ *                     group its own tile latency L_tile(g) on a full device (its own cache tile,
+ *                     hit rates and K loop); Algorithm 9 becomes omega * sum_g T_g L_tile(g) / T.
+ *   gemm_cfg_at_grouped  the same for variant `variant` in [0, gemm_variant_count(dtype)), for sweeps.
+ *   gemm_grouped_plan validates cfg and problems and writes n_groups table records (HOST memory,
+ *                     caller-owned) and the launch's tile count.  The caller copies the records,
+ *                     unchanged, to 16-byte aligned device memory.
+ *   gemm_run_grouped  enqueues the launch.  host_table: the records gemm_grouped_plan wrote (checked
+ *                     again); dev_table: their copy in device memory, which must stay unchanged
+ *                     until the launch has finished.  Groups must not overlap in C.
+ * 1 <= n_groups <= 4096.  Errors as for gemm_select / gemm_run; GEMM_ERR_CFG_ILLEGAL also when cfg
+ * is not a grouped cfg for n_groups groups or a record does not belong to it.
+ */
+typedef struct gemm_problem {
+    int64_t M, N, K;
+    int64_t lda, ldb, ldc;
+    const void *A;
+    const void *B;
+    void *C;
+} gemm_problem;
+typedef struct gemm_group_rec {
+    uint64_t A, B, C;            /* device addresses */
+    int32_t M, N, K;
+    int32_t lda, ldb, ldc;
+    int32_t tiles_m, tiles_n;    /* ceil(M / block_m), ceil(N / block_n) */
+    int32_t tile_start;          /* first logical workgroup id of the group = tiles of the groups before it */
+    int32_t group_m;             /* band height of the group's rasterisation (Algorithm 6's f_m for its shape) */
+} gemm_group_rec;                /* 64 bytes */
+int gemm_select_grouped(int n_groups, const gemm_problem *problems, int dtype, int b_layout, gemm_cfg *out);
+int gemm_cfg_at_grouped(int variant, int n_groups, const gemm_problem *problems, int dtype, int b_layout,
+                        gemm_cfg *out);
+int gemm_variant_count(int dtype);
+int gemm_grouped_plan(const gemm_cfg *cfg, int n_groups, const gemm_problem *problems, gemm_group_rec *table_out,
+                      int64_t *total_tiles_out);
+int gemm_run_grouped(const gemm_cfg *cfg, int n_groups, const gemm_group_rec *host_table, const void *dev_table,
+                     void *hip_stream);
 
 /*
  * Enqueue C = alpha * A * B + beta * C on hip_stream (a hipStream_t; NULL = the default stream) with

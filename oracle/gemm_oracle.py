@@ -139,6 +139,19 @@ def gemm_batched(A, B, dtype=BF16, alpha=1.0):
     return np.stack([o[0] for o in outs]), np.stack([o[1] for o in outs])
 
 
+def gemm_grouped(problems, dtype=BF16, alpha=1.0):
+    """Grouped product: problems = [(A_g, B_g), ...] of different shapes, each C_g = alpha * A_g * B_g by
+    the plain definition (one gemm() per group; an A with no rows gives an empty result).
+    Returns a list of (bits, fp64) pairs."""
+    out = []
+    for A, B in problems:
+        if A.shape[0] == 0:
+            out.append((np.zeros((0, B.shape[1]), dtype=np.uint16), np.zeros((0, B.shape[1]))))
+        else:
+            out.append(gemm(A, B, dtype, alpha))
+    return out
+
+
 def accumulate(C64, beta, C_in_bits, dtype=BF16):
     """The full definition of Section II-A, C = alpha*A*B + beta*C: C64 is the fp64 value of
     alpha*A*B (from gemm / gemm_rows / gemm_samples), C_in_bits the 16-bit codes C held on

@@ -256,6 +256,7 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0, batch=1):
         out[k] = shown[k]
     out["l_mem_tail"] = tail["l_mem"]
     out["l_tile_tail"] = tail["l_tile"]
+    out["l_tile_full"] = full["l_tile"]      # Algorithm 8 on a full device, whatever this problem's own wave count
 
     l_reduce = 0.0
     if split_k > 1:
@@ -296,3 +297,26 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0, batch=1):
                    l_reduce=l_sum, l_total=hw["launch_clk"] + whole * full["l_tile"] + l_sk + l_sum)
     out["total_us"] = out["l_total"] / (hw["clk_ghz"] * 1e3)
     return out
+
+
+def predict_grouped(hw, dtype, shapes, v, b_layout=0):
+    """Total latency in clocks of ONE launch that computes several products of different shapes
+    [(M, N, K), ...] (M = 0: an empty group) with variant v, no K splitting.
+    READING (Sections II-B and V-C only name the grouped dimension): Algorithm 4 counts the tiles
+    of all groups together, T = sum T_g, omega = ceil(T / slots); Algorithm 8 prices each group's
+    tile on a full device (the other groups' tiles keep the CUs busy) with that group's own cache
+    tile, hit rates and K loop; Algorithm 9 becomes omega times the tile-weighted mean of the
+    groups' tile latencies, plus one launch.  Returns (l_total, [group_m per group])."""
+    es = 1 if dtype == 1 else 2
+    tiles, weighted, group_m = 0, 0.0, []
+    for (M, N, K) in shapes:
+        if M == 0:
+            group_m.append(1)
+            continue
+        p = predict(hw, dtype, M, N, K, v, 1, b_layout=b_layout)
+        t = _ceil_div(M, v["block_m"]) * _ceil_div(N, v["block_n"])
+        tiles += t
+        weighted += t * p["l_tile_full"]
+        group_m.append(p["group_m"])
+    slots = hw["n_cu"] * occupancy(hw, v, es)
+    return hw["launch_clk"] + math.ceil(tiles / slots) * weighted / tiles, group_m

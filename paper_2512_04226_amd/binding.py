@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("GEMM355_LIB") or os.path.join(_PKG, "libgemm355.so") 
 GEMM_BF16 = 0
 GEMM_FP8_E4M3 = 1
 GEMM_FP16 = 2
-GEMM_ABI_VERSION = 4
+GEMM_ABI_VERSION = 5
 GEMM_B_ROW_MAJOR = 0
 GEMM_B_K_CONTIGUOUS = 1
 
@@ -60,7 +60,7 @@ class gemm_cfg(ctypes.Structure):
                 ("slab_clk", ctypes.c_uint16), ("b_layout", ctypes.c_uint8), ("stream_k", ctypes.c_uint8),
                 ("sk_workers", ctypes.c_uint16), ("alpha", ctypes.c_float),
                 ("bottleneck", ctypes.c_int32), ("beta", ctypes.c_float), ("predicted_us", ctypes.c_double),
-                ("batch", ctypes.c_int32), ("reserved1", ctypes.c_int32), ("stride_a", ctypes.c_int64),
+                ("batch", ctypes.c_int32), ("groups", ctypes.c_int32), ("stride_a", ctypes.c_int64),
                 ("stride_b", ctypes.c_int64), ("stride_c", ctypes.c_int64)]
 
     def describe(self):
@@ -68,7 +68,8 @@ class gemm_cfg(ctypes.Structure):
             self.block_m, self.block_n, self.block_k, self.waves_m, self.waves_n, self.mfma, self.stages,
             ("streamk%d" % self.sk_workers) if self.stream_k else ("split%d" % self.split_k), self.group_m,
             "" if self.xcd_remap else " noxcd", " Bkc" if self.b_layout else "")
-                + (" batch%d" % self.batch if self.batch > 1 else ""))
+                + (" batch%d" % self.batch if self.batch > 1 else "")
+                + (" groups%d" % self.groups if self.groups else ""))
 
     def copy(self):
         c = gemm_cfg()
@@ -312,3 +313,85 @@ def gemm_run(cfg, A, B, C, stream=None):
     None for torch's current stream."""
     _check(_lib.gemm_run(ctypes.byref(cfg), _ptr(A), _ptr(B), _ptr(C), ctypes.c_void_p(_stream_handle(stream))),
            "gemm_run")
+
+
+class gemm_problem(ctypes.Structure):
+    _fields_ = [("M", _i64), ("N", _i64), ("K", _i64), ("lda", _i64), ("ldb", _i64), ("ldc", _i64),
+                ("A", _vp), ("B", _vp), ("C", _vp)]
+
+
+class gemm_group_rec(ctypes.Structure):
+    _fields_ = [("A", ctypes.c_uint64), ("B", ctypes.c_uint64), ("C", ctypes.c_uint64)] + [
+        (n, ctypes.c_int32) for n in ("M", "N", "K", "lda", "ldb", "ldc", "tiles_m", "tiles_n", "tile_start", "group_m")]
+
+
+_lib.gemm_variant_count.restype = _int
+_lib.gemm_variant_count.argtypes = [_int]
+_lib.gemm_select_grouped.restype = _int
+_lib.gemm_select_grouped.argtypes = [_int, ctypes.POINTER(gemm_problem), _int, _int, ctypes.POINTER(gemm_cfg)]
+_lib.gemm_cfg_at_grouped.restype = _int
+_lib.gemm_cfg_at_grouped.argtypes = [_int, _int, ctypes.POINTER(gemm_problem), _int, _int, ctypes.POINTER(gemm_cfg)]
+_lib.gemm_grouped_plan.restype = _int
+_lib.gemm_grouped_plan.argtypes = [ctypes.POINTER(gemm_cfg), _int, ctypes.POINTER(gemm_problem),
+                                   ctypes.POINTER(gemm_group_rec), ctypes.POINTER(_i64)]
+_lib.gemm_run_grouped.restype = _int
+_lib.gemm_run_grouped.argtypes = [ctypes.POINTER(gemm_cfg), _int, ctypes.POINTER(gemm_group_rec), _vp, _vp]
+
+
+def gemm_variant_count(dtype):
+    n = _lib.gemm_variant_count(dtype)
+    if n < 0:
+        raise GemmError(n, "gemm_variant_count")
+    return n
+
+
+def make_problems(shapes, b_layout=0, tensors=None):
+    """ctypes array of gemm_problem from [(M, N, K), ...] with dense leading dimensions; tensors:
+    optional [(A, B, C), ...] of device tensors (None entries allowed for empty groups)."""
+    arr = (gemm_problem * len(shapes))()
+    for i, (M, N, K) in enumerate(shapes):
+        arr[i].M, arr[i].N, arr[i].K = M, N, K
+        arr[i].lda, arr[i].ldb, arr[i].ldc = K, (K if b_layout else N), N
+        if tensors is not None:
+            A, B, C = tensors[i]
+            arr[i].A = A.data_ptr() if A is not None else None
+            arr[i].B = B.data_ptr() if B is not None else None
+            arr[i].C = C.data_ptr() if C is not None else None
+    return arr
+
+
+def gemm_select_grouped(problems, dtype, b_layout=0):
+    cfg = gemm_cfg()
+    _check(_lib.gemm_select_grouped(len(problems), problems, dtype, b_layout, ctypes.byref(cfg)), "gemm_select_grouped")
+    return cfg
+
+
+def gemm_cfg_at_grouped(variant, problems, dtype, b_layout=0):
+    """Returns the grouped cfg of a variant, or None when it cannot run every group."""
+    cfg = gemm_cfg()
+    rc = _lib.gemm_cfg_at_grouped(variant, len(problems), problems, dtype, b_layout, ctypes.byref(cfg))
+    if rc == -4:
+        return None
+    _check(rc, "gemm_cfg_at_grouped")
+    return cfg
+
+
+def gemm_grouped_plan(cfg, problems):
+    """(host table as a ctypes array of gemm_group_rec, total tiles)."""
+    table = (gemm_group_rec * len(problems))()
+    total = _i64()
+    _check(_lib.gemm_grouped_plan(ctypes.byref(cfg), len(problems), problems, table, ctypes.byref(total)),
+           "gemm_grouped_plan")
+    return table, total.value
+
+
+def table_to_device(table, device="cuda"):
+    """The plan's records, byte for byte, in a device tensor (the caller keeps it alive)."""
+    raw = bytes(table)
+    return torch.frombuffer(bytearray(raw), dtype=torch.uint8).to(device)
+
+
+def gemm_run_grouped(cfg, table, dev_table, stream=None):
+    """Enqueue the grouped launch: table from gemm_grouped_plan, dev_table its copy in device memory."""
+    _check(_lib.gemm_run_grouped(ctypes.byref(cfg), len(table), table, _ptr(dev_table),
+                                 ctypes.c_void_p(_stream_handle(stream))), "gemm_run_grouped")

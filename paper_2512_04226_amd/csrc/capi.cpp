@@ -33,9 +33,218 @@ bool cfg_stream_k_plan(const gemm_cfg *cfg, SkPlan *p)
     const int64_t tiles_m = (cfg->M + cfg->block_m - 1) / cfg->block_m, tiles_n = (cfg->N + cfg->block_n - 1) / cfg->block_n;
     return sk_make_plan(tiles_m * tiles_n, cfg->sk_workers, (cfg->K + cfg->block_k - 1) / cfg->block_k, p);
 }
+
+int check_grouped_cfg(const gemm_cfg *cfg, int n_groups)
+{
+    if (cfg->abi_version != GEMM_ABI_VERSION)
+        return GEMM_ERR_ABI;
+    if (n_groups < 1 || n_groups > kMaxGroups)
+        return GEMM_ERR_SHAPE;
+    if (cfg->dtype != GEMM_BF16 && cfg->dtype != GEMM_FP8_E4M3 && cfg->dtype != GEMM_FP16)
+        return GEMM_ERR_DTYPE;
+    if (cfg->groups != n_groups || cfg->kernel_id < 0 || cfg->kernel_id >= variant_count(cfg->dtype))
+        return GEMM_ERR_CFG_ILLEGAL;
+    const Variant &v = variant_at(cfg->dtype, cfg->kernel_id);
+    if (cfg->block_m != v.block_m || cfg->block_n != v.block_n || cfg->block_k != v.block_k ||
+        cfg->waves_m != v.waves_m || cfg->waves_n != v.waves_n || cfg->mfma != v.mfma || cfg->stages != v.stages)
+        return GEMM_ERR_CFG_ILLEGAL;
+    if (cfg->split_k != 1 || cfg->stream_k || cfg->batch != 1 || cfg->b_layout > 1)
+        return GEMM_ERR_CFG_ILLEGAL;
+    return GEMM_OK;
+}
+
+int check_group_rec(const gemm_cfg *cfg, const gemm_group_rec *r, int64_t tile_start)
+{
+    const Variant &v = variant_at(cfg->dtype, cfg->kernel_id);
+    if (r->tile_start != tile_start || r->group_m < 1)
+        return GEMM_ERR_CFG_ILLEGAL;
+    if (r->M == 0)
+        return r->tiles_m == 0 ? GEMM_OK : GEMM_ERR_CFG_ILLEGAL;   // owns no tile: nothing else is read
+    if (r->M < 0)
+        return GEMM_ERR_SHAPE;
+    const int rc = check_problem(r->M, r->N, r->K, cfg->dtype);
+    if (rc)
+        return rc;
+    if (!variant_legal(hw_current(), v, cfg->dtype, r->M, r->N, r->K, 1, 0, 1))
+        return GEMM_ERR_CFG_ILLEGAL;
+    if (r->tiles_m != (r->M + v.block_m - 1) / v.block_m || r->tiles_n != (r->N + v.block_n - 1) / v.block_n)
+        return GEMM_ERR_CFG_ILLEGAL;
+    if (!r->A || !r->B || !r->C)
+        return GEMM_ERR_NULL;
+    if (r->lda < r->K || r->ldb < (cfg->b_layout ? r->K : r->N) || r->ldc < r->N)
+        return GEMM_ERR_SHAPE;
+    const int es = elem_bytes(cfg->dtype), per16 = 16 / es;
+    if ((r->A & 15) || (r->B & 15) || (r->C & 15) || r->lda % per16 || r->ldb % per16 || r->ldc % 8)
+        return GEMM_ERR_ALIGN;
+    // the kernel addresses a tile's operands with 32-bit byte offsets below 2 GiB
+    const int64_t lim = (int64_t)1 << 31;
+    const int64_t b_window = cfg->b_layout ? (int64_t)v.block_n * r->ldb * es
+                                           : (k_per_split(v, r->K, 1) + (int64_t)v.stages * v.block_k) * r->ldb * es;
+    if ((int64_t)v.block_m * r->lda * es >= lim || b_window >= lim)
+        return GEMM_ERR_SHAPE;
+    return GEMM_OK;
+}
 }  // namespace g355
 
+namespace {
+// shapes of the problems, or a gemm_status for the first one that is not a legal group
+int group_shapes(int n_groups, const gemm_problem *problems, int dtype, int b_layout, GroupShape *shapes,
+                 int64_t *m_max, int64_t *n_max, int64_t *k_max, bool all_empty_ok = false)
+{
+    if (!problems)
+        return GEMM_ERR_NULL;
+    if (n_groups < 1 || n_groups > kMaxGroups)
+        return GEMM_ERR_SHAPE;
+    if (b_layout != GEMM_B_ROW_MAJOR && b_layout != GEMM_B_K_CONTIGUOUS)
+        return GEMM_ERR_CFG_ILLEGAL;
+    if (dtype != GEMM_BF16 && dtype != GEMM_FP8_E4M3 && dtype != GEMM_FP16)
+        return GEMM_ERR_DTYPE;
+    *m_max = *n_max = *k_max = 0;
+    for (int i = 0; i < n_groups; ++i) {
+        if (problems[i].M < 0)
+            return GEMM_ERR_SHAPE;
+        // an empty group still names a well-formed N and K
+        const int rc = check_problem(problems[i].M > 0 ? problems[i].M : 1, problems[i].N, problems[i].K, dtype);
+        if (rc)
+            return rc;
+        shapes[i].M = problems[i].M;
+        shapes[i].N = problems[i].N;
+        shapes[i].K = problems[i].K;
+        if (problems[i].M > 0) {
+            *m_max = problems[i].M > *m_max ? problems[i].M : *m_max;
+            *n_max = problems[i].N > *n_max ? problems[i].N : *n_max;
+            *k_max = problems[i].K > *k_max ? problems[i].K : *k_max;
+        }
+    }
+    if (*m_max == 0 && !all_empty_ok)
+        return GEMM_ERR_SHAPE;   // every group is empty: nothing to select for
+    return GEMM_OK;
+}
+
+void fill_grouped_cfg(const gemm_hw &hw, int dtype, int b_layout, int id, int n_groups, int64_t m_max, int64_t n_max,
+                      int64_t k_max, double l_total, int bottleneck, gemm_cfg *out)
+{
+    fill_cfg(hw, dtype, b_layout, m_max, n_max, k_max, id, 1, 0, out, 1);
+    out->groups = n_groups;
+    out->bottleneck = bottleneck;
+    out->predicted_us = l_total / (hw.clk_ghz * 1e3);
+}
+}  // namespace
+
 extern "C" {
+
+int gemm_variant_count(int dtype)
+{
+    if (dtype != GEMM_BF16 && dtype != GEMM_FP8_E4M3 && dtype != GEMM_FP16)
+        return GEMM_ERR_DTYPE;
+    return variant_count(dtype);
+}
+
+int gemm_cfg_at_grouped(int variant, int n_groups, const gemm_problem *problems, int dtype, int b_layout, gemm_cfg *out)
+{
+    if (!out)
+        return GEMM_ERR_NULL;
+    GroupShape shapes[kMaxGroups];
+    int64_t mm, nm, km;
+    const int rc = group_shapes(n_groups, problems, dtype, b_layout, shapes, &mm, &nm, &km);
+    if (rc)
+        return rc;
+    if (variant < 0 || variant >= variant_count(dtype))
+        return GEMM_ERR_INDEX;
+    const gemm_hw &hw = hw_current();
+    double l_total;
+    int label;
+    if (!predict_grouped(hw, dtype, b_layout, n_groups, shapes, variant_at(dtype, variant), &l_total, &label, nullptr))
+        return GEMM_ERR_CFG_ILLEGAL;
+    fill_grouped_cfg(hw, dtype, b_layout, variant, n_groups, mm, nm, km, l_total, label, out);
+    return GEMM_OK;
+}
+
+int gemm_select_grouped(int n_groups, const gemm_problem *problems, int dtype, int b_layout, gemm_cfg *out)
+{
+    if (!out)
+        return GEMM_ERR_NULL;
+    GroupShape shapes[kMaxGroups];
+    int64_t mm, nm, km;
+    const int rc = group_shapes(n_groups, problems, dtype, b_layout, shapes, &mm, &nm, &km);
+    if (rc)
+        return rc;
+    const gemm_hw &hw = hw_current();
+    int best_id = -1, best_label = 0;
+    double best = 0.0;
+    // fixed enumeration order and a strict '<': the first of equal predictions wins
+    for (int id = 0; id < variant_count(dtype); ++id) {
+        double l_total;
+        int label;
+        if (!predict_grouped(hw, dtype, b_layout, n_groups, shapes, variant_at(dtype, id), &l_total, &label, nullptr))
+            continue;
+        if (best_id < 0 || l_total < best) {
+            best = l_total;
+            best_id = id;
+            best_label = label;
+        }
+    }
+    if (best_id < 0)
+        return GEMM_ERR_CFG_ILLEGAL;
+    fill_grouped_cfg(hw, dtype, b_layout, best_id, n_groups, mm, nm, km, best, best_label, out);
+    return GEMM_OK;
+}
+
+int gemm_grouped_plan(const gemm_cfg *cfg, int n_groups, const gemm_problem *problems, gemm_group_rec *table_out,
+                      int64_t *total_tiles_out)
+{
+    if (!cfg || !problems || !table_out || !total_tiles_out)
+        return GEMM_ERR_NULL;
+    int rc = check_grouped_cfg(cfg, n_groups);
+    if (rc)
+        return rc;
+    GroupShape shapes[kMaxGroups];
+    int64_t mm, nm, km;
+    rc = group_shapes(n_groups, problems, cfg->dtype, cfg->b_layout, shapes, &mm, &nm, &km, true);
+    if (rc)
+        return rc;
+    const Variant &v = variant_at(cfg->dtype, cfg->kernel_id);
+    int group_m[kMaxGroups];
+    double l_total;
+    int label;
+    if (mm == 0) {
+        for (int i = 0; i < n_groups; ++i)
+            group_m[i] = 1;   // every group is empty: a plan without tiles
+    } else if (!predict_grouped(hw_current(), cfg->dtype, cfg->b_layout, n_groups, shapes, v, &l_total, &label, group_m)) {
+        return GEMM_ERR_CFG_ILLEGAL;
+    }
+    const int64_t lim = (int64_t)1 << 31;
+    int64_t start = 0;
+    for (int i = 0; i < n_groups; ++i) {
+        const gemm_problem &p = problems[i];
+        gemm_group_rec r;
+        std::memset(&r, 0, sizeof(r));
+        if (p.lda >= lim || p.ldb >= lim || p.ldc >= lim || p.lda < 0 || p.ldb < 0 || p.ldc < 0)
+            return GEMM_ERR_SHAPE;
+        r.A = (uint64_t)(uintptr_t)p.A;
+        r.B = (uint64_t)(uintptr_t)p.B;
+        r.C = (uint64_t)(uintptr_t)p.C;
+        r.M = (int32_t)p.M;
+        r.N = (int32_t)p.N;
+        r.K = (int32_t)p.K;
+        r.lda = (int32_t)p.lda;
+        r.ldb = (int32_t)p.ldb;
+        r.ldc = (int32_t)p.ldc;
+        r.tiles_m = (int32_t)((p.M + v.block_m - 1) / v.block_m);
+        r.tiles_n = (int32_t)((p.N + v.block_n - 1) / v.block_n);
+        r.tile_start = (int32_t)start;
+        r.group_m = group_m[i];
+        rc = check_group_rec(cfg, &r, start);
+        if (rc)
+            return rc;
+        start += (int64_t)r.tiles_m * r.tiles_n;
+        if (start >= lim)
+            return GEMM_ERR_SHAPE;
+        table_out[i] = r;
+    }
+    *total_tiles_out = start;
+    return GEMM_OK;
+}
 
 uint32_t gemm_abi_version(void) { return GEMM_ABI_VERSION; }
 

@@ -22,6 +22,7 @@
 #include <stdint.h>
 #include <type_traits>
 
+#include "grouped.hpp"
 #include "stream_k.hpp"
 
 namespace g355 {
@@ -48,6 +49,10 @@ struct KernelArgs {
     // problem b starts at b * split_k * M * N floats).
     long long stride_a, stride_b, stride_c;
     int batch;
+    // Grouped launch (n_groups > 0; split_k == 1, no stream-K, batch == 1): the problem fields
+    // above are unused and each workgroup reads its group's record from this device table.
+    const GroupRec *groups;
+    int n_groups;
 };
 
 typedef short short4_t __attribute__((ext_vector_type(4)));
@@ -141,16 +146,21 @@ struct Tile {
 // and inside the tile grid the ids run column-major through bands of group_m tile rows,
 // so the workgroups that share an L2 at one time form a compact group_m x (CUs/group_m)
 // block of output tiles (the cache tile of Algorithms 5 and 6).
-// pid in [0, grid), grid = data-parallel tiles * split_k.
+// pid in [0, grid), grid = data-parallel tiles * split_k (the tiles of all groups in a
+// grouped launch).
+__device__ inline int logical_id(const KernelArgs &a, int pid, int grid)
+{
+    if (!a.xcd_remap)
+        return pid;
+    const int per = grid / a.n_xcd, rem = grid % a.n_xcd;
+    const int x = pid % a.n_xcd, q = pid / a.n_xcd;
+    return x * per + (x < rem ? x : rem) + q;
+}
+
 __device__ inline void tile_coords(const KernelArgs &a, int pid, int grid, int &tm, int &tn, int &ks)
 {
     const int tiles = a.tiles_m * a.tiles_n;
-    int l = pid;
-    if (a.xcd_remap) {
-        const int per = grid / a.n_xcd, rem = grid % a.n_xcd;
-        const int x = pid % a.n_xcd, q = pid / a.n_xcd;
-        l = x * per + (x < rem ? x : rem) + q;
-    }
+    const int l = logical_id(a, pid, grid);
     ks = l / tiles;
     logical_tile(a.tiles_m, a.tiles_n, a.group_m, l - ks * tiles, tm, tn);
 }
@@ -178,6 +188,28 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     if (sk_worker)
         nseg = sk_segments(args.sk, (int)blockIdx.x, segs);
 
+    // The problem this workgroup works on: the launch's own, or its group's in a grouped launch.
+    const void *pA = args.A, *pB = args.B;
+    void *pC = args.C;
+    int pM = args.M, pN = args.N, pK = args.K, plda = args.lda, pldb = args.ldb, pldc = args.ldc;
+    int g_tm = 0, g_tn = 0;
+    const bool grouped = args.n_groups > 0;
+    if (grouped) {
+        const int l = logical_id(args, (int)blockIdx.x, (int)gridDim.x);
+        const GroupRec *r = args.groups + group_of(args.groups, args.n_groups, l);
+        pA = uniform_ptr(r->A);
+        pB = uniform_ptr(r->B);
+        pC = uniform_ptr(r->C);
+        pM = uniform_i32(r->M);
+        pN = uniform_i32(r->N);
+        pK = uniform_i32(r->K);
+        plda = uniform_i32(r->lda);
+        pldb = uniform_i32(r->ldb);
+        pldc = uniform_i32(r->ldc);
+        logical_tile(uniform_i32(r->tiles_m), uniform_i32(r->tiles_n), uniform_i32(r->group_m),
+                     l - uniform_i32(r->tile_start), g_tm, g_tn);
+    }
+
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept scalar
@@ -191,19 +223,25 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         logical_tile(args.tiles_m, args.tiles_n, args.group_m, args.sk.dp_tiles + sg.tile, tm, tn);
         k_begin = sg.slab0 * BK;
         k_len = sg.count * BK;
-        if (k_len > args.K - k_begin)
-            k_len = args.K - k_begin;
+        if (k_len > pK - k_begin)
+            k_len = pK - k_begin;
         out_mode = sg.complete ? 0 : 2;
         if (seg) {
             // the previous segment's stores have left and every wave is done with its LDS stages
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
         }
+    } else if (grouped) {
+        tm = g_tm;
+        tn = g_tn;
+        k_begin = 0;
+        k_len = pK;
+        out_mode = 0;
     } else {
         const int grid = (args.sk.workers > 0) ? args.sk.dp_tiles : args.tiles_m * args.tiles_n * args.split_k;
         tile_coords(args, (int)blockIdx.x - args.sk.workers, grid, tm, tn, ks);
         k_begin = ks * args.k_per_split;
-        k_len = args.K - k_begin;
+        k_len = pK - k_begin;
         if (k_len > args.k_per_split)
             k_len = args.k_per_split;
         out_mode = (args.split_k > 1) ? 1 : 0;
@@ -219,17 +257,17 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     // outside the buffer window and arrive as zero; chunk columns past the edge (A: k >= k_len,
     // B: n >= N) are sent outside the window by replacing the offset.
     const size_t bz = blockIdx.y;     // problem of the batch
-    const uint8_t *Abase = (const uint8_t *)args.A + (bz * args.stride_a + (size_t)m0 * args.lda + k_begin) * ES;
+    const uint8_t *Abase = (const uint8_t *)pA + (bz * args.stride_a + (size_t)m0 * plda + k_begin) * ES;
     const uint8_t *Bbase = (T::BL == 0)
-                               ? (const uint8_t *)args.B + (bz * args.stride_b + (size_t)k_begin * args.ldb + n0) * ES
-                               : (const uint8_t *)args.B + (bz * args.stride_b + (size_t)n0 * args.ldb + k_begin) * ES;
-    const int a_rows_valid = (args.M - m0 < BM) ? (args.M - m0) : BM;
-    const int b_rows_valid = (args.N - n0 < BN) ? (args.N - n0) : BN;      // K-contiguous B only
+                               ? (const uint8_t *)pB + (bz * args.stride_b + (size_t)k_begin * pldb + n0) * ES
+                               : (const uint8_t *)pB + (bz * args.stride_b + (size_t)n0 * pldb + k_begin) * ES;
+    const int a_rows_valid = (pM - m0 < BM) ? (pM - m0) : BM;
+    const int b_rows_valid = (pN - n0 < BN) ? (pN - n0) : BN;      // K-contiguous B only
     const __amdgpu_buffer_rsrc_t rsA =
-        make_rsrc(Abase, (unsigned)((a_rows_valid - 1) * args.lda + k_len) * ES);
+        make_rsrc(Abase, (unsigned)((a_rows_valid - 1) * plda + k_len) * ES);
     const __amdgpu_buffer_rsrc_t rsB =
-        make_rsrc(Bbase, (T::BL == 0) ? (unsigned)(k_len * args.ldb) * ES
-                                      : (unsigned)((b_rows_valid - 1) * args.ldb + k_len) * ES);
+        make_rsrc(Bbase, (T::BL == 0) ? (unsigned)(k_len * pldb) * ES
+                                      : (unsigned)((b_rows_valid - 1) * pldb + k_len) * ES);
 
     unsigned a_voff[T::A_LOADS], b_voff[T::B_LOADS];
     int a_kcol[T::A_LOADS], b_kcol[T::B_LOADS];
@@ -238,7 +276,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         const int c = (i * T::NW + wave) * 64 + lane;
         const int row = c / T::CA, lch = (c % T::CA) ^ T::a_key(row);
         a_kcol[i] = lch * (16 / ES);
-        a_voff[i] = (unsigned)(row * args.lda * ES + lch * 16);
+        a_voff[i] = (unsigned)(row * plda * ES + lch * 16);
     }
 #pragma unroll
     for (int i = 0; i < T::B_LOADS; ++i) {
@@ -246,13 +284,13 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         const int row = c / T::CB;
         if constexpr (T::BL == 0) {
             const int lbyte = ((c % T::CB) * 16) ^ T::b_key(row);
-            const bool ok = n0 + lbyte / ES < args.N;
-            b_voff[i] = ok ? (unsigned)(row * args.ldb * ES + lbyte) : OOB_OFFSET;
+            const bool ok = n0 + lbyte / ES < pN;
+            b_voff[i] = ok ? (unsigned)(row * pldb * ES + lbyte) : OOB_OFFSET;
             b_kcol[i] = 0;
         } else {
             const int lch = (c % T::CB) ^ T::a_key(row);      // same row bytes as A: same key
             b_kcol[i] = lch * (16 / ES);
-            b_voff[i] = (unsigned)(row * args.ldb * ES + lch * 16);
+            b_voff[i] = (unsigned)(row * pldb * ES + lch * 16);
         }
     }
     // Load instruction l of a slab request (A units first, then B units): asynchronous,
@@ -271,7 +309,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             if (T::B_UNITS % T::NW == 0 || u < T::B_UNITS) {
                 unsigned off;
                 if constexpr (T::BL == 0)
-                    off = b_voff[i] + (unsigned)kk * (unsigned)(args.ldb * ES);
+                    off = b_voff[i] + (unsigned)kk * (unsigned)(pldb * ES);
                 else
                     off = (b_kcol[i] + kk < k_len) ? b_voff[i] + (unsigned)(kk * ES) : OOB_OFFSET;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (G355_LDS void *)(sbase + T::A_BYTES + u * 1024), 16, off,
@@ -440,21 +478,21 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
 #pragma unroll
     for (int i = 0; i < T::TM; ++i) {
         const int m = out_m + i * MI;
-        if (m >= args.M)
+        if (m >= pM)
             continue;
 #pragma unroll
         for (int j = 0; j < T::TN; ++j) {
 #pragma unroll
             for (int q = 0; q < T::ACC / 4; ++q) {
                 const int n = out_nl + j * MI + q * 8;
-                if (n >= args.N)
+                if (n >= pN)
                     continue;
                 f32x4 v;
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     v[r] = acc[j][i][q * 4 + r];
                 if (out_mode == 1) {
-                    float *dst = args.ws + ((bz * args.split_k + ks) * args.M + m) * args.N + n;
+                    float *dst = args.ws + ((bz * args.split_k + ks) * pM + m) * pN + n;
                     *(f32x4 *)dst = v;
                 } else if (out_mode == 2) {
                     float *dst = args.ws + ((size_t)(2 * blockIdx.x + seg) * BM + (m - m0)) * BN + (n - n0);
@@ -462,7 +500,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                 } else {
                     typedef typename std::conditional<T::FT == 1, _Float16, __bf16>::type out_t;
                     typedef typename std::conditional<T::FT == 1, f16x4, bf16x4>::type out4_t;
-                    out_t *dst = (out_t *)args.C + bz * args.stride_c + (size_t)m * args.ldc + n;
+                    out_t *dst = (out_t *)pC + bz * args.stride_c + (size_t)m * pldc + n;
                     out4_t o;
                     if (beta != 0.f) {
                         const out4_t c = *(const out4_t *)dst;

@@ -297,7 +297,7 @@ static int label_of(const MemTerms &t, double l_comp, bool under, double fixed, 
 }
 
 void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, int64_t K, const Variant &v, int split_k,
-             int stream_k, gemm_prediction *p, int *group_m, int *group_n, int64_t batch)
+             int stream_k, gemm_prediction *p, int *group_m, int *group_n, int64_t batch, double *l_tile_full_out)
 {
     std::memset(p, 0, sizeof(*p));
     const int es = elem_bytes(dtype);
@@ -380,6 +380,8 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
     // the last wave moves the bytes of the tiles that exist: tail / active per CU
     const double l_tile_tail =
         tile_latency(tail_per_cu, active, tail_tiles / active, &mt_tail, &lc_tail, &pro_t, &epi_t, &iter_t);
+    if (l_tile_full_out)
+        *l_tile_full_out = l_tile_full;
     const bool has_full = waves > 1.0;
     const MemTerms &mt = has_full ? mt_full : mt_tail;
     p->l_compute = has_full ? lc_full : lc_tail;
@@ -455,6 +457,44 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
     const double fixed = hw.launch_clk + l_reduce + waves * (p->l_prologue + p->l_epilogue);
     p->bottleneck = label_of(stream_k ? mt_full : mt, p->l_compute, !stream_k && active < hw.n_cu && waves == 1.0, fixed,
                              p->l_total - fixed);
+}
+
+// Grouped launch.  Algorithm 4 on the tiles of all groups together (the launch is one grid);
+// Algorithm 8 per group on a full device (other groups' tiles fill the CUs a small group leaves
+// free); Algorithm 9 as waves times the tile-weighted mean of the groups' tile latencies.
+bool predict_grouped(const gemm_hw &hw, int dtype, int b_layout, int n, const GroupShape *g, const Variant &v,
+                     double *l_total_out, int *bottleneck_out, int *group_m_out)
+{
+    double tiles = 0.0, weighted = 0.0, heaviest = -1.0;
+    int label = GEMM_BOUND_LAUNCH;
+    for (int i = 0; i < n; ++i) {
+        if (group_m_out)
+            group_m_out[i] = 1;
+        if (g[i].M == 0)
+            continue;
+        if (!variant_legal(hw, v, dtype, g[i].M, g[i].N, g[i].K, 1, 0, 1))
+            return false;
+        gemm_prediction p;
+        int gm, gn;
+        double l_tile = 0.0;
+        predict(hw, dtype, b_layout, g[i].M, g[i].N, g[i].K, v, 1, 0, &p, &gm, &gn, 1, &l_tile);
+        const double t = (double)cdiv(g[i].M, v.block_m) * (double)cdiv(g[i].N, v.block_n);
+        tiles += t;
+        weighted += t * l_tile;
+        if (t * l_tile > heaviest) {
+            heaviest = t * l_tile;
+            label = p.bottleneck;
+        }
+        if (group_m_out)
+            group_m_out[i] = gm;
+    }
+    if (tiles <= 0.0)
+        return false;
+    const double slots = (double)hw.n_cu * occupancy(hw, v, dtype);
+    *l_total_out = hw.launch_clk + std::ceil(tiles / slots) * weighted / tiles;
+    if (bottleneck_out)
+        *bottleneck_out = label;
+    return true;
 }
 
 void fill_cfg(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, int64_t K, int kernel_id, int split_k,

@@ -1,6 +1,7 @@
 // gemm_run and the split-K workspace: the only entry points that touch the GPU.
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <cstring>
 
 #include "../../include/gemm.h"
@@ -195,6 +196,8 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
         return GEMM_ERR_CFG_ILLEGAL;
     if (cfg->b_layout > 1 || cfg->stream_k > 1)
         return GEMM_ERR_CFG_ILLEGAL;
+    if (cfg->groups != 0)
+        return GEMM_ERR_CFG_ILLEGAL;   // a grouped cfg runs through gemm_run_grouped
     if (cfg->batch < 1 || cfg->batch > 65535)
         return GEMM_ERR_SHAPE;
     if (cfg->batch > 1 && cfg->stream_k)
@@ -269,6 +272,8 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
     a.stride_a = cfg->batch > 1 ? cfg->stride_a : 0;
     a.stride_b = cfg->batch > 1 ? cfg->stride_b : 0;
     a.stride_c = cfg->batch > 1 ? cfg->stride_c : 0;
+    a.groups = nullptr;
+    a.n_groups = 0;
 
     hipStream_t stream = (hipStream_t)hip_stream;
     const int f16 = (dtype == GEMM_FP16) ? 1 : 0;
@@ -306,6 +311,53 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
                            a.N, a.ldc, a.split_k, a.alpha, a.beta, f16, a.stride_c);
         if (hipGetLastError() != hipSuccess)
             return GEMM_ERR_HIP;
+    }
+    return GEMM_OK;
+}
+
+static_assert(sizeof(gemm_group_rec) == sizeof(GroupRec) && offsetof(gemm_group_rec, M) == offsetof(GroupRec, M) &&
+                  offsetof(gemm_group_rec, tile_start) == offsetof(GroupRec, tile_start) &&
+                  offsetof(gemm_group_rec, group_m) == offsetof(GroupRec, group_m),
+              "the public record is the kernel's record");
+
+extern "C" int gemm_run_grouped(const gemm_cfg *cfg, int n_groups, const gemm_group_rec *host_table, const void *dev_table,
+                                void *hip_stream)
+{
+    if (!cfg || !host_table || !dev_table)
+        return GEMM_ERR_NULL;
+    int rc = check_grouped_cfg(cfg, n_groups);
+    if (rc)
+        return rc;
+    if ((uintptr_t)dev_table & 15)
+        return GEMM_ERR_ALIGN;
+    int64_t total = 0;
+    for (int i = 0; i < n_groups; ++i) {
+        rc = check_group_rec(cfg, &host_table[i], total);
+        if (rc)
+            return rc;
+        total += (int64_t)host_table[i].tiles_m * host_table[i].tiles_n;
+        if (total >= ((int64_t)1 << 31))
+            return GEMM_ERR_SHAPE;
+    }
+    if (total == 0)
+        return GEMM_OK;   // every group is empty
+    const gemm_hw &hw = hw_current();
+    KernelArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.alpha = cfg->alpha;
+    a.beta = cfg->beta;
+    a.tiles_m = (int)total;   // the grid: one workgroup per tile of any group
+    a.tiles_n = 1;
+    a.split_k = 1;
+    a.group_m = 1;
+    a.xcd_remap = cfg->xcd_remap ? 1 : 0;
+    a.n_xcd = hw.n_xcd;
+    a.batch = 1;
+    a.groups = (const GroupRec *)dev_table;
+    a.n_groups = n_groups;
+    if (launcher_of(cfg->dtype, cfg->kernel_id, cfg->b_layout)(a, (hipStream_t)hip_stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return GEMM_ERR_HIP;
     }
     return GEMM_OK;
 }

@@ -151,3 +151,11 @@ def config5(index, shapes=None):
     shapes = shapes or config5_shapes()
     M, N, K = shapes[index]
     return uniform_bf16(M, N, K, seed=4, case=index + 1)
+
+
+def routed_rows(groups, total_rows, seed, skew=1.0):
+    """Rows per group of a grouped launch shaped like expert routing: Dirichlet(skew) shares of
+    total_rows, multinomial counts -- ragged, and a group may get no row at all."""
+    rng = _rng(seed, groups)
+    shares = rng.dirichlet(np.full(groups, skew))
+    return [int(x) for x in rng.multinomial(total_rows, shares)]

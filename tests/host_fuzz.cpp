@@ -78,6 +78,51 @@ int main()
             }
         }
     }
+    // grouped selection and plans over random group lists (with empty groups); every record's tile
+    // range must tile [0, total) in order
+    for (int it = 0; it < 200; ++it) {
+        const int n = 1 + (int)rnd(it % 10 == 0 ? 4096 : 40), dt = it % 3, bl = (it / 3) & 1;
+        static gemm_problem probs[4096];
+        static gemm_group_rec table[4096];
+        const long N = 16 * (1 + rnd(256)), K = 16 * (1 + rnd(256));
+        bool any = false;
+        for (int i = 0; i < n; ++i) {
+            const long M = rnd(4) == 0 ? 0 : 1 + rnd(700);
+            any = any || M > 0;
+            probs[i].M = M;
+            probs[i].N = (it & 1) ? N : 16 * (1 + rnd(256));
+            probs[i].K = (it & 1) ? K : 16 * (1 + rnd(256));
+            probs[i].lda = probs[i].K;
+            probs[i].ldb = bl ? probs[i].K : probs[i].N;
+            probs[i].ldc = probs[i].N;
+            probs[i].A = probs[i].B = (const void *)(uintptr_t)(0x1000 * (i + 1));
+            probs[i].C = (void *)(uintptr_t)(0x1000 * (i + 1));
+        }
+        const int rc = gemm_select_grouped(n, probs, dt, bl, &c);
+        if (!any) {
+            if (rc != GEMM_ERR_SHAPE)
+                return 20;
+            continue;
+        }
+        if (rc != GEMM_OK || c.groups != n || !(c.predicted_us > 0))
+            return 21;
+        int64_t total = 0, start = 0;
+        if (gemm_grouped_plan(&c, n, probs, table, &total) != GEMM_OK)
+            return 22;
+        for (int i = 0; i < n; ++i) {
+            if (table[i].tile_start != start || table[i].group_m < 1)
+                return 23;
+            start += (int64_t)table[i].tiles_m * table[i].tiles_n;
+        }
+        if (start != total || total < 1)
+            return 24;
+        gemm_cfg d;
+        const int v = (int)rnd(gemm_variant_count(dt));
+        const int rc2 = gemm_cfg_at_grouped(v, n, probs, dt, bl, &d);
+        if (rc2 != GEMM_OK && rc2 != GEMM_ERR_CFG_ILLEGAL)
+            return 25;
+        acc += c.kernel_id;
+    }
     // every preset installs, selects and resets
     for (int id = 0; id < 2; ++id) {
         gemm_hw h;

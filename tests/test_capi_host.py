@@ -38,7 +38,8 @@ def test_struct_layouts_match_the_header(tmp_path):
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     lines = ["#include <stdio.h>", "#include <stddef.h>", '#include "gemm.h"', "int main(void){"]
     structs = {"gemm_cfg": g.gemm_cfg, "gemm_prediction": g.gemm_prediction, "gemm_hw": g.gemm_hw,
-               "gemm_sk_segment": g.gemm_sk_segment}
+               "gemm_sk_segment": g.gemm_sk_segment, "gemm_problem": g.gemm_problem,
+               "gemm_group_rec": g.gemm_group_rec}
     for name, cls in structs.items():
         lines.append('printf("%s %%zu\\n", sizeof(%s));' % (name, name))
         for field, _ in cls._fields_:
@@ -53,7 +54,7 @@ def test_struct_layouts_match_the_header(tmp_path):
         assert int(got[name]) == ctypes.sizeof(cls), name
         for field, _ in cls._fields_:
             assert int(got["%s.%s" % (name, field)]) == getattr(cls, field).offset, (name, field)
-    assert ctypes.sizeof(g.gemm_cfg) == 136
+    assert ctypes.sizeof(g.gemm_cfg) == 136 and ctypes.sizeof(g.gemm_group_rec) == 64
 
 
 def test_select_argument_errors():
