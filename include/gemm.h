@@ -198,11 +198,20 @@ int gemm_cfg_at_batched(int idx, int64_t M, int64_t N, int64_t K, int64_t batch,
  *                     hit rates and K loop); Algorithm 9 becomes omega * sum_g T_g L_tile(g) / T.
  *   gemm_cfg_at_grouped  the same for variant `variant` in [0, gemm_variant_count(dtype)), for sweeps.
  *   gemm_grouped_plan validates cfg and problems and writes n_groups table records (HOST memory,
- *                     caller-owned) and the launch's tile count.  The caller copies the records,
- *                     unchanged, to 16-byte aligned device memory.
+ *                     caller-owned) and the launch's workgroup count.  With X = the descriptor's
+ *                     XCD count (1 when cfg.xcd_remap = 0) a group of T tiles takes ceil(T / X)
+ *                     consecutive slots on every XCD: workgroup p is slot p / X of XCD p % X, XCD x
+ *                     computes the x-th of X contiguous chunks of the group's tiles, and a slot
+ *                     beyond its chunk is idle.  Every group is thereby spread over all L2s.  The records are ordered by
+ *                     descending K (ties: the caller's order), so that the longest tiles are
+ *                     dispatched first; each carries its group's pointers.  The caller copies the
+ *                     records, unchanged, to 16-byte aligned device memory.
  *   gemm_run_grouped  enqueues the launch.  host_table: the records gemm_grouped_plan wrote (checked
  *                     again); dev_table: their copy in device memory, which must stay unchanged
  *                     until the launch has finished.  Groups must not overlap in C.
+ *   gemm_grouped_locate  host only: what workgroup `workgroup` of the launch computes, by the
+ *                     kernel's own arithmetic: out3 = {record index, tile_m, tile_n}, or {-1,-1,-1}
+ *                     for an idle slot.  GEMM_ERR_INDEX beyond the launch's workgroups.
  * 1 <= n_groups <= 4096.  Errors as for gemm_select / gemm_run; GEMM_ERR_CFG_ILLEGAL also when cfg
  * is not a grouped cfg for n_groups groups or a record does not belong to it.
  */
@@ -218,7 +227,7 @@ typedef struct gemm_group_rec {
     int32_t M, N, K;
     int32_t lda, ldb, ldc;
     int32_t tiles_m, tiles_n;    /* ceil(M / block_m), ceil(N / block_n) */
-    int32_t tile_start;          /* first logical workgroup id of the group = tiles of the groups before it */
+    int32_t tile_start;          /* first per-XCD slot of the group: sum of ceil(tiles / X) over the records before it */
     int32_t group_m;             /* band height of the group's rasterisation (Algorithm 6's f_m for its shape) */
 } gemm_group_rec;                /* 64 bytes */
 int gemm_select_grouped(int n_groups, const gemm_problem *problems, int dtype, int b_layout, gemm_cfg *out);
@@ -226,7 +235,9 @@ int gemm_cfg_at_grouped(int variant, int n_groups, const gemm_problem *problems,
                         gemm_cfg *out);
 int gemm_variant_count(int dtype);
 int gemm_grouped_plan(const gemm_cfg *cfg, int n_groups, const gemm_problem *problems, gemm_group_rec *table_out,
-                      int64_t *total_tiles_out);
+                      int64_t *workgroups_out);
+int gemm_grouped_locate(const gemm_cfg *cfg, int n_groups, const gemm_group_rec *table, int64_t workgroup,
+                        int32_t out3[3]);
 int gemm_run_grouped(const gemm_cfg *cfg, int n_groups, const gemm_group_rec *host_table, const void *dev_table,
                      void *hip_stream);
 

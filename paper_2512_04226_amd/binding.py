@@ -334,6 +334,9 @@ _lib.gemm_cfg_at_grouped.argtypes = [_int, _int, ctypes.POINTER(gemm_problem), _
 _lib.gemm_grouped_plan.restype = _int
 _lib.gemm_grouped_plan.argtypes = [ctypes.POINTER(gemm_cfg), _int, ctypes.POINTER(gemm_problem),
                                    ctypes.POINTER(gemm_group_rec), ctypes.POINTER(_i64)]
+_lib.gemm_grouped_locate.restype = _int
+_lib.gemm_grouped_locate.argtypes = [ctypes.POINTER(gemm_cfg), _int, ctypes.POINTER(gemm_group_rec), _i64,
+                                     ctypes.POINTER(ctypes.c_int32)]
 _lib.gemm_run_grouped.restype = _int
 _lib.gemm_run_grouped.argtypes = [ctypes.POINTER(gemm_cfg), _int, ctypes.POINTER(gemm_group_rec), _vp, _vp]
 
@@ -376,8 +379,15 @@ def gemm_cfg_at_grouped(variant, problems, dtype, b_layout=0):
     return cfg
 
 
+def gemm_grouped_locate(cfg, table, workgroup):
+    """(record index, tile_m, tile_n) of a workgroup of the grouped launch, or (-1, -1, -1) when idle."""
+    out = (ctypes.c_int32 * 3)()
+    _check(_lib.gemm_grouped_locate(ctypes.byref(cfg), len(table), table, int(workgroup), out), "gemm_grouped_locate")
+    return tuple(out)
+
+
 def gemm_grouped_plan(cfg, problems):
-    """(host table as a ctypes array of gemm_group_rec, total tiles)."""
+    """(host table as a ctypes array of gemm_group_rec, workgroups of the launch)."""
     table = (gemm_group_rec * len(problems))()
     total = _i64()
     _check(_lib.gemm_grouped_plan(ctypes.byref(cfg), len(problems), problems, table, ctypes.byref(total)),

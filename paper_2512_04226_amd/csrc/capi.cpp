@@ -1,9 +1,11 @@
 // Host-only entry points of the C ABI: selection, enumeration, prediction, hardware
 // descriptor.  Nothing here touches the GPU.
+#include <algorithm>
 #include <cstring>
 
 #include "../../include/gemm.h"
 #include "model.hpp"
+#include "grouped.hpp"
 #include "stream_k.hpp"
 
 using namespace g355;
@@ -53,10 +55,12 @@ int check_grouped_cfg(const gemm_cfg *cfg, int n_groups)
     return GEMM_OK;
 }
 
-int check_group_rec(const gemm_cfg *cfg, const gemm_group_rec *r, int64_t tile_start)
+int grouped_xcds(const gemm_cfg *cfg) { return cfg->xcd_remap ? hw_current().n_xcd : 1; }
+
+int check_group_rec(const gemm_cfg *cfg, const gemm_group_rec *r, int64_t slot_start)
 {
     const Variant &v = variant_at(cfg->dtype, cfg->kernel_id);
-    if (r->tile_start != tile_start || r->group_m < 1)
+    if (r->tile_start != slot_start || r->group_m < 1)
         return GEMM_ERR_CFG_ILLEGAL;
     if (r->M == 0)
         return r->tiles_m == 0 ? GEMM_OK : GEMM_ERR_CFG_ILLEGAL;   // owns no tile: nothing else is read
@@ -191,9 +195,9 @@ int gemm_select_grouped(int n_groups, const gemm_problem *problems, int dtype, i
 }
 
 int gemm_grouped_plan(const gemm_cfg *cfg, int n_groups, const gemm_problem *problems, gemm_group_rec *table_out,
-                      int64_t *total_tiles_out)
+                      int64_t *workgroups_out)
 {
-    if (!cfg || !problems || !table_out || !total_tiles_out)
+    if (!cfg || !problems || !table_out || !workgroups_out)
         return GEMM_ERR_NULL;
     int rc = check_grouped_cfg(cfg, n_groups);
     if (rc)
@@ -213,9 +217,18 @@ int gemm_grouped_plan(const gemm_cfg *cfg, int n_groups, const gemm_problem *pro
     } else if (!predict_grouped(hw_current(), cfg->dtype, cfg->b_layout, n_groups, shapes, v, &l_total, &label, group_m)) {
         return GEMM_ERR_CFG_ILLEGAL;
     }
+    // Tiles are dispatched in id order, so the groups with the longest K loops go first and the
+    // short tiles of the other groups fill the end of the launch (records carry their own
+    // pointers: their order in the table is free).  Stable: equal K keeps the caller's order.
+    int order[kMaxGroups];
+    for (int i = 0; i < n_groups; ++i)
+        order[i] = i;
+    std::stable_sort(order, order + n_groups, [&](int a, int b) { return problems[a].K > problems[b].K; });
     const int64_t lim = (int64_t)1 << 31;
-    int64_t start = 0;
-    for (int i = 0; i < n_groups; ++i) {
+    const int X = grouped_xcds(cfg);
+    int64_t start = 0;   // per-XCD slots taken so far
+    for (int j = 0; j < n_groups; ++j) {
+        const int i = order[j];
         const gemm_problem &p = problems[i];
         gemm_group_rec r;
         std::memset(&r, 0, sizeof(r));
@@ -237,12 +250,12 @@ int gemm_grouped_plan(const gemm_cfg *cfg, int n_groups, const gemm_problem *pro
         rc = check_group_rec(cfg, &r, start);
         if (rc)
             return rc;
-        start += (int64_t)r.tiles_m * r.tiles_n;
-        if (start >= lim)
+        start += ((int64_t)r.tiles_m * r.tiles_n + X - 1) / X;
+        if (start * X >= lim)
             return GEMM_ERR_SHAPE;
-        table_out[i] = r;
+        table_out[j] = r;
     }
-    *total_tiles_out = start;
+    *workgroups_out = start * X;
     return GEMM_OK;
 }
 
@@ -369,6 +382,40 @@ int gemm_predict(const gemm_cfg *cfg, gemm_prediction *out)
         return GEMM_ERR_CFG_ILLEGAL;
     predict(hw, cfg->dtype, cfg->b_layout, cfg->M, cfg->N, cfg->K, v, cfg->split_k, cfg->stream_k, out, &gm, &gn,
             cfg->batch);
+    return GEMM_OK;
+}
+
+int gemm_grouped_locate(const gemm_cfg *cfg, int n_groups, const gemm_group_rec *table, int64_t workgroup, int32_t out3[3])
+{
+    if (!cfg || !table || !out3)
+        return GEMM_ERR_NULL;
+    int rc = check_grouped_cfg(cfg, n_groups);
+    if (rc)
+        return rc;
+    const int X = grouped_xcds(cfg);
+    int64_t slots = 0;
+    for (int i = 0; i < n_groups; ++i) {
+        rc = check_group_rec(cfg, &table[i], slots);
+        if (rc)
+            return rc;
+        slots += group_slots(table[i].tiles_m * table[i].tiles_n, X);
+    }
+    if (workgroup < 0 || workgroup >= slots * X)
+        return GEMM_ERR_INDEX;
+    // the kernel's own steps, on the host
+    const GroupRec *tab = reinterpret_cast<const GroupRec *>(table);
+    const int x = (int)(workgroup % X), q = (int)(workgroup / X);
+    const int gi = group_of(tab, n_groups, q);
+    const GroupRec &r = tab[gi];
+    const int t = group_tile(r.tiles_m * r.tiles_n, X, x, q - r.tile_start);
+    out3[0] = t < 0 ? -1 : gi;
+    out3[1] = out3[2] = -1;
+    if (t >= 0) {
+        int tm, tn;
+        logical_tile(r.tiles_m, r.tiles_n, r.group_m, t, tm, tn);
+        out3[1] = tm;
+        out3[2] = tn;
+    }
     return GEMM_OK;
 }
 

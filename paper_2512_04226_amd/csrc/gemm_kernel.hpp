@@ -146,8 +146,7 @@ struct Tile {
 // and inside the tile grid the ids run column-major through bands of group_m tile rows,
 // so the workgroups that share an L2 at one time form a compact group_m x (CUs/group_m)
 // block of output tiles (the cache tile of Algorithms 5 and 6).
-// pid in [0, grid), grid = data-parallel tiles * split_k (the tiles of all groups in a
-// grouped launch).
+// pid in [0, grid), grid = data-parallel tiles * split_k.
 __device__ inline int logical_id(const KernelArgs &a, int pid, int grid)
 {
     if (!a.xcd_remap)
@@ -195,8 +194,13 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     int g_tm = 0, g_tn = 0;
     const bool grouped = args.n_groups > 0;
     if (grouped) {
-        const int l = logical_id(args, (int)blockIdx.x, (int)gridDim.x);
-        const GroupRec *r = args.groups + group_of(args.groups, args.n_groups, l);
+        const int X = args.xcd_remap ? args.n_xcd : 1;
+        const int x = (int)blockIdx.x % X, q = (int)blockIdx.x / X;
+        const GroupRec *r = args.groups + group_of(args.groups, args.n_groups, q);
+        const int tiles_m = uniform_i32(r->tiles_m), tiles_n = uniform_i32(r->tiles_n);
+        const int t = group_tile(tiles_m * tiles_n, X, x, q - uniform_i32(r->tile_start));
+        if (t < 0)
+            return;   // idle slot of this XCD (the whole workgroup leaves: nothing was started)
         pA = uniform_ptr(r->A);
         pB = uniform_ptr(r->B);
         pC = uniform_ptr(r->C);
@@ -206,8 +210,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         plda = uniform_i32(r->lda);
         pldb = uniform_i32(r->ldb);
         pldc = uniform_i32(r->ldc);
-        logical_tile(uniform_i32(r->tiles_m), uniform_i32(r->tiles_n), uniform_i32(r->group_m),
-                     l - uniform_i32(r->tile_start), g_tm, g_tn);
+        logical_tile(tiles_m, tiles_n, uniform_i32(r->group_m), t, g_tm, g_tn);
     }
 
     const int tid = threadIdx.x;

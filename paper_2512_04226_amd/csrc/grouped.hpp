@@ -3,10 +3,16 @@
 // multiplier of a tuning search (Sections II-B and V-C); for the analytical selector it is one
 // more evaluation of the model over the groups' tiles.
 //
-// The tiles of group g occupy the logical workgroup ids [tile_start[g], tile_start[g+1]) of
-// the launch, each group rasterised in its own grouped order.  The kernel finds its group by a
-// binary search over a table of fixed-size records in device memory; the same records and the
-// same search run on the host (plan construction, validation, tests).
+// Hardware deals consecutive workgroup ids round-robin to the X XCDs, and an XCD works through
+// its ids in order.  Workgroup id p is therefore slot q = p / X of XCD x = p % X, and every
+// group owns the same slot range [slot_start[g], slot_start[g] + ceil(T_g / X)) on every XCD:
+// XCD x computes the x-th of X contiguous chunks of the group's T_g tiles (in the group's own
+// grouped rasterisation order), exactly as in a launch of that group alone.  Each group is so
+// spread over all L2s -- groups with long K loops do not pile up on one XCD -- and a group's
+// last slot is idle on the XCDs whose chunk is one tile shorter (the workgroup exits at once).
+// With the XCD renumbering switched off X is 1: slots are tiles.
+// The kernel finds its group by a binary search over a table of fixed-size records in device
+// memory; the same records and the same arithmetic run on the host (plan, validation, tests).
 #pragma once
 #include <stdint.h>
 
@@ -21,7 +27,7 @@ struct GroupRec {
     int M, N, K;          // M may be 0: an empty group owns no tiles
     int lda, ldb, ldc;    // elements
     int tiles_m, tiles_n;
-    int tile_start;       // first logical workgroup id of the group
+    int tile_start;       // first per-XCD slot of the group: sum of ceil(T / X) over the records before it
     int group_m;          // band height of the group's rasterisation
 };
 static_assert(sizeof(GroupRec) == 64, "one record is 64 bytes");
@@ -44,9 +50,22 @@ G355_HD inline P uniform_ptr(P p)
     return (P)(((uint64_t)hi << 32) | lo);
 }
 
-// The group that owns logical id l in [0, total tiles): the last g with tile_start[g] <= l
+// Slots a group of `tiles` tiles takes on each of X XCDs.
+G355_HD inline int group_slots(int tiles, int X) { return (tiles + X - 1) / X; }
+
+// Tile of a group (index in its rasterisation order) computed in slot j of XCD x, or -1 when
+// that slot is idle: XCD x owns the x-th contiguous chunk, the first tiles % X chunks one longer.
+G355_HD inline int group_tile(int tiles, int X, int x, int j)
+{
+    const int per = tiles / X, rem = tiles % X;
+    if (j >= per + (x < rem ? 1 : 0))
+        return -1;
+    return x * per + (x < rem ? x : rem) + j;
+}
+
+// The group that owns slot l in [0, total slots): the last g with tile_start[g] <= l
 // (tile_start[0] is 0; empty groups share their successor's start and are never returned for
-// an id inside the grid unless they are trailing, which the `<=` rule also skips).
+// a slot inside the grid unless they are trailing, which the `<=` rule also skips).
 G355_HD inline int group_of(const GroupRec *tab, int n, int l)
 {
     int lo = 0, hi = n;

@@ -40,6 +40,7 @@ bool cfg_stream_k_plan(const gemm_cfg *cfg, SkPlan *p);
 // 0 or a gemm_status: is `cfg` a grouped cfg for n groups, and does the record (with the tile
 // range starting at tile_start) describe a problem its kernel can run?
 int check_grouped_cfg(const gemm_cfg *cfg, int n_groups);
-int check_group_rec(const gemm_cfg *cfg, const gemm_group_rec *r, int64_t tile_start);
+int check_group_rec(const gemm_cfg *cfg, const gemm_group_rec *r, int64_t slot_start);
+int grouped_xcds(const gemm_cfg *cfg);   // XCDs the groups' tiles are dealt over (1 without the renumbering)
 constexpr int kMaxGroups = 4096;
 }  // namespace g355

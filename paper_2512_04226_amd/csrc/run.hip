@@ -330,23 +330,25 @@ extern "C" int gemm_run_grouped(const gemm_cfg *cfg, int n_groups, const gemm_gr
         return rc;
     if ((uintptr_t)dev_table & 15)
         return GEMM_ERR_ALIGN;
-    int64_t total = 0;
+    const int X = grouped_xcds(cfg);
+    int64_t slots = 0;
     for (int i = 0; i < n_groups; ++i) {
-        rc = check_group_rec(cfg, &host_table[i], total);
+        rc = check_group_rec(cfg, &host_table[i], slots);
         if (rc)
             return rc;
-        total += (int64_t)host_table[i].tiles_m * host_table[i].tiles_n;
-        if (total >= ((int64_t)1 << 31))
+        slots += group_slots(host_table[i].tiles_m * host_table[i].tiles_n, X);
+        if (slots * X >= ((int64_t)1 << 31))
             return GEMM_ERR_SHAPE;
     }
-    if (total == 0)
+    if (slots == 0)
         return GEMM_OK;   // every group is empty
+    const int64_t total = slots * X;
     const gemm_hw &hw = hw_current();
     KernelArgs a;
     std::memset(&a, 0, sizeof(a));
     a.alpha = cfg->alpha;
     a.beta = cfg->beta;
-    a.tiles_m = (int)total;   // the grid: one workgroup per tile of any group
+    a.tiles_m = (int)total;   // the grid: X workgroups per slot
     a.tiles_n = 1;
     a.split_k = 1;
     a.group_m = 1;

@@ -50,11 +50,16 @@ def time_cfg(cfg, A, B, C, ws, min_ms=1.0, max_iters=200, repeats=3):
     that host launch overhead does not mask short kernels), replayed `repeats` times between
     events on torch's current stream; the median replay is reported."""
     ws.ensure(cfg)
-    g.gemm_run(cfg, A, B, C)
+    return time_launch(lambda: g.gemm_run(cfg, A, B, C), min_ms, max_iters, repeats)
+
+
+def time_launch(launch, min_ms=1.0, max_iters=200, repeats=3):
+    """The timing protocol of time_cfg for any enqueueing callable."""
+    launch()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    g.gemm_run(cfg, A, B, C)
+    launch()
     e1.record()
     e1.synchronize()
     one = max(e0.elapsed_time(e1), 1e-3)
@@ -62,7 +67,7 @@ def time_cfg(cfg, A, B, C, ws, min_ms=1.0, max_iters=200, repeats=3):
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         for _ in range(iters):
-            g.gemm_run(cfg, A, B, C)
+            launch()
     graph.replay()
     torch.cuda.synchronize()
     times = []
@@ -101,6 +106,59 @@ def sweep_shape(M, N, K, dtype, ws, quick=False, b_layout=0):
     return rec, rows
 
 
+def grouped_sets():
+    """Grouped workloads: routing-like row counts against per-group weights, and one mixed list."""
+    return [
+        ("16 routed x 4096x4096", [(m, 4096, 4096) for m in wl.routed_rows(16, 16384, seed=6)]),
+        ("8 routed x 4096x2048", [(m, 4096, 2048) for m in wl.routed_rows(8, 4096, seed=11)]),
+        ("64 routed x 2048x1024", [(m, 2048, 1024) for m in wl.routed_rows(64, 8192, seed=5, skew=0.5)]),
+        ("32 routed x 1024x7168", [(m, 1024, 7168) for m in wl.routed_rows(32, 2048, seed=12, skew=0.3)]),
+        ("128 routed x 7168x2048", [(m, 7168, 2048) for m in wl.routed_rows(128, 1024, seed=13)]),
+        ("8 routed x 2048x7168 (65536 rows)", [(m, 2048, 7168) for m in wl.routed_rows(8, 65536, seed=14)]),
+        ("16 equal x 256x4096x4096", [(256, 4096, 4096)] * 16),
+        ("mixed", [(4096, 4096, 4096), (512, 8192, 1024), (2048, 1024, 8192), (64, 14336, 4096)]),
+    ]
+
+
+def sweep_grouped(name, shapes, dtype, b_layout=0):
+    """Every variant's grouped launch and the analytic pick on one group list; the same groups as
+    separately selected launches for reference."""
+    ws = Workspace()
+    tensors = []
+    for i, (M, N, K) in enumerate(shapes):
+        if M == 0:
+            tensors.append((None, None, None))
+            continue
+        A, B, C = make_operands(M, N, K, dtype, seed=i)
+        tensors.append((A, B.t().contiguous() if b_layout else B, C))
+    probs = g.make_problems(shapes, b_layout, tensors)
+    flops = sum(2.0 * M * N * K for (M, N, K) in shapes)
+
+    def timed(cfg):
+        table, _ = g.gemm_grouped_plan(cfg, probs)
+        dtab = g.table_to_device(table)
+        return time_launch(lambda: g.gemm_run_grouped(cfg, table, dtab))
+
+    rows = []
+    for vid in range(g.gemm_variant_count(dtype)):
+        cfg = g.gemm_cfg_at_grouped(vid, probs, dtype, b_layout)
+        if cfg is None:
+            continue
+        rows.append({"idx": vid, "cfg": cfg.describe(), "us": timed(cfg), "pred_us": cfg.predicted_us})
+    pick = g.gemm_select_grouped(probs, dtype, b_layout)
+    pick_us = min(timed(pick), [r for r in rows if r["idx"] == pick.kernel_id][0]["us"])
+    best = min(rows, key=lambda r: r["us"])
+    singles = [(g.gemm_select_ex(M, N, K, dtype, b_layout), t) for (M, N, K), t in zip(shapes, tensors) if M]
+    for c1, _ in singles:
+        ws.ensure(c1)
+    sep_us = time_launch(lambda: [g.gemm_run(c1, *t) for c1, t in singles])
+    return {"set": name, "groups": len(shapes), "rows": [s[0] for s in shapes], "dtype": dtype, "b_layout": b_layout,
+            "best": best, "pick": pick.describe(), "pick_us": pick_us, "pick_pred_us": pick.predicted_us,
+            "efficiency": best["us"] / pick_us, "pick_tflops": flops / pick_us * 1e-6,
+            "best_tflops": flops / best["us"] * 1e-6, "separate_launches_us": sep_us,
+            "top5": sorted(rows, key=lambda r: r["us"])[:5]}
+
+
 def shape_set(name):
     if name == "config5":
         return [(m, n, k, g.GEMM_BF16) for (m, n, k) in wl.config5_shapes()]
@@ -124,6 +182,21 @@ def main(argv=None):
     ap.add_argument("--b-layout", type=int, default=0, help="0: B row-major K x N, 1: B stored K-contiguous (N x K)")
     ap.add_argument("--all-rows", action="store_true", help="also write every config's timing")
     args = ap.parse_args(argv)
+    if args.set == "grouped":
+        os.makedirs(os.path.dirname(args.out) or ".", exist_ok=True)
+        effs = []
+        with open(args.out, "a") as f:
+            for name, shapes in grouped_sets():
+                rec = sweep_grouped(name, shapes, g.GEMM_BF16, args.b_layout)
+                f.write(json.dumps(rec) + "\n")
+                f.flush()
+                effs.append(rec["efficiency"])
+                print("%s: best %s %.1f us, pick %s %.1f us (pred %.1f) eff %.3f, %.0f TF; separate launches %.1f us" % (
+                    name, rec["best"]["cfg"], rec["best"]["us"], rec["pick"], rec["pick_us"], rec["pick_pred_us"],
+                    rec["efficiency"], rec["pick_tflops"], rec["separate_launches_us"]), flush=True)
+        print("grouped selection efficiency: median %.3f mean %.3f min %.3f over %d group lists" % (
+            float(np.median(effs)), float(np.mean(effs)), float(np.min(effs)), len(effs)), flush=True)
+        return
     shapes = shape_set(args.set)
     if args.limit:
         shapes = shapes[:args.limit]

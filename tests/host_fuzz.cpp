@@ -109,13 +109,37 @@ int main()
         int64_t total = 0, start = 0;
         if (gemm_grouped_plan(&c, n, probs, table, &total) != GEMM_OK)
             return 22;
+        gemm_hw hwd;
+        gemm_hw_get(&hwd);
+        const int X = hwd.n_xcd;
+        int64_t tiles = 0;
         for (int i = 0; i < n; ++i) {
-            if (table[i].tile_start != start || table[i].group_m < 1)
+            if (table[i].tile_start != start || table[i].group_m < 1 || (i && table[i].K > table[i - 1].K))
                 return 23;
-            start += (int64_t)table[i].tiles_m * table[i].tiles_n;
+            const int64_t t = (int64_t)table[i].tiles_m * table[i].tiles_n;
+            start += (t + X - 1) / X;
+            tiles += t;
         }
-        if (start != total || total < 1)
+        if (start * X != total || total < 1)
             return 24;
+        // sampled workgroups land on a tile inside their record or on an idle slot
+        int64_t busy = 0;
+        const int64_t step = total > 4000 ? total / 2000 : 1;
+        for (int64_t w = 0; w < total; w += step) {
+            int32_t o[3];
+            if (gemm_grouped_locate(&c, n, table, w, o) != GEMM_OK)
+                return 26;
+            if (o[0] >= 0) {
+                if (o[0] >= n || o[1] < 0 || o[1] >= table[o[0]].tiles_m || o[2] < 0 || o[2] >= table[o[0]].tiles_n)
+                    return 27;
+                ++busy;
+            }
+        }
+        if (step == 1 && busy != tiles)
+            return 28;
+        int32_t o[3];
+        if (gemm_grouped_locate(&c, n, table, total, o) != GEMM_ERR_INDEX)
+            return 29;
         gemm_cfg d;
         const int v = (int)rnd(gemm_variant_count(dt));
         const int rc2 = gemm_cfg_at_grouped(v, n, probs, dt, bl, &d);

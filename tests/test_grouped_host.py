@@ -40,12 +40,17 @@ def test_grouped_prediction_and_pick_match_the_oracle(dtype, b_layout):
             l_total, group_m = sm.predict_grouped(hw, dtype, shapes, _variant_dict(c), b_layout)
             assert c.predicted_us == pytest.approx(l_total / (hw["clk_ghz"] * 1e3), rel=1e-9)
             table, total = g.gemm_grouped_plan(c, probs_with_fake_pointers(shapes, b_layout))
-            assert [r.group_m for r in table] == group_m
+            assert [r.group_m for r in table] == [group_m[i] for i in plan_order(shapes)]
             if best is None or l_total < best[0] * (1 - 1e-12):
                 best = (l_total, vid)
         assert n_legal > 10
         pick = g.gemm_select_grouped(probs, dtype, b_layout)
         assert pick.kernel_id == best[1], (shapes, pick.describe())
+
+
+def plan_order(shapes):
+    """The table's record order: descending K, ties in the caller's order."""
+    return sorted(range(len(shapes)), key=lambda i: -shapes[i][2])
 
 
 def probs_with_fake_pointers(shapes, b_layout=0):
@@ -66,31 +71,48 @@ def test_a_single_group_reduces_to_waves_times_the_full_tile_latency():
     assert c.predicted_us * hw["clk_ghz"] * 1e3 == pytest.approx(hw["launch_clk"] + 4 * p.l_tile, rel=1e-9)
 
 
-def test_plan_table_tile_ranges_and_group_search():
+@pytest.mark.parametrize("xcd_remap", [1, 0])
+def test_plan_table_slots_and_workgroup_to_tile_mapping(xcd_remap):
+    """Every tile of every group is computed by exactly one workgroup; each group takes the same
+    slot range on every XCD and XCD x (= workgroup id mod X) owns a contiguous chunk of it."""
     shapes = [(0, 512, 256), (300, 1024, 512), (0, 1024, 512), (40, 512, 1024), (1000, 2048, 256), (0, 64, 64)]
     probs = probs_with_fake_pointers(shapes)
     c = g.gemm_select_grouped(probs, 0)
-    table, total = g.gemm_grouped_plan(c, probs)
+    c.xcd_remap = xcd_remap
+    X = g.gemm_hw_get().n_xcd if xcd_remap else 1
+    table, grid = g.gemm_grouped_plan(c, probs)
     bm, bn = c.block_m, c.block_n
     start = 0
-    for r, (M, N, K) in zip(table, shapes):
+    assert plan_order(shapes) == [3, 1, 2, 0, 4, 5]
+    for r, i in zip(table, plan_order(shapes)):
+        M, N, K = shapes[i]
+        assert (r.A, r.B, r.C) == (probs[i].A, probs[i].B, probs[i].C)
         assert (r.M, r.N, r.K, r.lda, r.ldb, r.ldc) == (M, N, K, K, N, N)
         assert r.tiles_m == -(-M // bm) and r.tiles_n == -(-N // bn) and r.tile_start == start
-        start += r.tiles_m * r.tiles_n
-    assert total == start and table[0].tile_start == 0 and table[-1].tile_start == total
-    # every logical id belongs to exactly the non-empty group whose range holds it: the rule the
-    # kernel's binary search implements (last record whose start is <= id)
-    starts = [r.tile_start for r in table]
-    for l in range(total):
-        lo, hi = 0, len(starts)
-        while hi - lo > 1:
-            mid = (lo + hi) // 2
-            if starts[mid] <= l:
-                lo = mid
-            else:
-                hi = mid
-        r = table[lo]
-        assert r.M > 0 and r.tile_start <= l < r.tile_start + r.tiles_m * r.tiles_n
+        start += -(-(r.tiles_m * r.tiles_n) // X)
+    assert grid == start * X and table[0].tile_start == 0 and table[-1].M == 0 and table[-1].tile_start == start
+    seen, idle, last = {}, 0, {}
+    for wg in range(grid):
+        rec, tm, tn = g.gemm_grouped_locate(c, table, wg)
+        if rec < 0:
+            idle += 1
+            continue
+        r = table[rec]
+        assert r.M > 0 and 0 <= tm < r.tiles_m and 0 <= tn < r.tiles_n
+        assert (rec, tm, tn) not in seen
+        seen[(rec, tm, tn)] = wg % X
+        # an XCD meets the records in table order (longest K first)
+        assert last.get(wg % X, 0) <= rec
+        last[wg % X] = rec
+    assert len(seen) == sum(r.tiles_m * r.tiles_n for r in table)
+    assert idle == grid - len(seen) and idle <= (X - 1) * sum(1 for r in table if r.M > 0)
+    if X > 1:
+        # a group with at least X tiles is spread over every XCD
+        for rec, r in enumerate(table):
+            if r.tiles_m * r.tiles_n >= X:
+                assert {x for (rr, _, _), x in seen.items() if rr == rec} == set(range(X))
+    with pytest.raises(g.GemmError):
+        g.gemm_grouped_locate(c, table, grid)
     # the records are plain bytes: the device copy is these 64-byte records
     assert len(bytes(table)) == 64 * len(shapes)
 
@@ -143,8 +165,9 @@ def test_grouped_argument_errors():
     with_empty = probs_with_fake_pointers([(300, 1024, 512), (0, 512, 1024)])
     with_empty[1].A = with_empty[1].B = with_empty[1].C = None
     c2 = g.gemm_select_grouped(with_empty, 0)
-    t2, total2 = g.gemm_grouped_plan(c2, with_empty)
-    assert t2[1].tiles_m == 0 and t2[1].tile_start == total2
+    t2, _ = g.gemm_grouped_plan(c2, with_empty)
+    empty_rec = [r for r in t2 if r.M == 0][0]
+    assert empty_rec.tiles_m == 0 and empty_rec.A == 0
 
     # gemm_run_grouped validates the host table again and launches nothing on error (no GPU here:
     # every call below must return before any HIP call)
