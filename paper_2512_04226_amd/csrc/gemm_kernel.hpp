@@ -298,9 +298,8 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     }
     // Load instruction l of a slab request (A units first, then B units): asynchronous,
     // completion is counted by vmcnt.
-    auto issue_one = [&](int l, int slab, int stage) {
+    auto issue_one = [&](int l, int slab, G355_LDS uint8_t *sbase) {
         const int kk = slab * BK;
-        G355_LDS uint8_t *sbase = (G355_LDS uint8_t *)smem + stage * T::STAGE;
         if (l < T::A_LOADS) {
             const int i = l, u = i * T::NW + wave;
             if (T::A_UNITS % T::NW == 0 || u < T::A_UNITS) {
@@ -354,30 +353,29 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
 
     // Fragment `u` of k-step `kstep` of LDS stage `stage` into register buffer `buf`:
     // u < TM is the A fragment of MFMA tile row u, otherwise the B fragment of tile column u-TM.
-    auto load_frag = [&](int stage, int kstep, int buf, int u) {
-        const uint8_t *sA = smem + stage * T::STAGE;
-        const uint8_t *sB = sA + T::A_BYTES;
+    auto load_frag = [&](const G355_LDS uint8_t *sA, int kstep, int buf, int u) {
+        const G355_LDS uint8_t *sB = sA + T::A_BYTES;
         const int k0 = kstep * T::KI;
         if (u < T::TM) {
             const int i = u;
             if constexpr (ES == 2) {
                 const int chunk = (k0 + a_kg * T::KL) / 8;
-                af[buf][i] = *(const bf16x8 *)(sA + T::a_off(a_row + i * MI, chunk));
+                af[buf][i] = *(const G355_LDS bf16x8 *)(sA + T::a_off(a_row + i * MI, chunk));
             } else {
                 const int chunk = (k0 + a_kg * T::KL) / 16;
-                i32x4 lo = *(const i32x4 *)(sA + T::a_off(a_row + i * MI, chunk));
-                i32x4 hi = *(const i32x4 *)(sA + T::a_off(a_row + i * MI, chunk + 1));
+                i32x4 lo = *(const G355_LDS i32x4 *)(sA + T::a_off(a_row + i * MI, chunk));
+                i32x4 hi = *(const G355_LDS i32x4 *)(sA + T::a_off(a_row + i * MI, chunk + 1));
                 af[buf][i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
         } else {
             const int j = u - T::TM;
             if constexpr (T::BL == 1 && ES == 2) {
                 const int chunk = (k0 + a_kg * T::KL) / 8;
-                bfr[buf][j] = *(const bf16x8 *)(sB + T::a_off(bk_row + j * MI, chunk));
+                bfr[buf][j] = *(const G355_LDS bf16x8 *)(sB + T::a_off(bk_row + j * MI, chunk));
             } else if constexpr (T::BL == 1) {
                 const int chunk = (k0 + a_kg * T::KL) / 16;
-                i32x4 lo = *(const i32x4 *)(sB + T::a_off(bk_row + j * MI, chunk));
-                i32x4 hi = *(const i32x4 *)(sB + T::a_off(bk_row + j * MI, chunk + 1));
+                i32x4 lo = *(const G355_LDS i32x4 *)(sB + T::a_off(bk_row + j * MI, chunk));
+                i32x4 hi = *(const G355_LDS i32x4 *)(sB + T::a_off(bk_row + j * MI, chunk + 1));
                 bfr[buf][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             } else if constexpr (ES == 2) {
                 short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -435,40 +433,61 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     static_assert((T::NS - 1) * FULL <= 63, "vmcnt is a 6-bit counter");
     auto publish = [&]() { asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(ALLOW) : "memory"); };
 
+    // The compiler cannot tell which LDS bytes a direct-to-LDS load will write, and before an LDS
+    // read that might touch them it waits for every such load in flight (vmcnt(0)), which would
+    // serialise each refill with the reads that follow it.  The part of an iteration between two
+    // barriers therefore lives in a function whose two stage pointers are `__restrict__`: it
+    // refills only the stage that was just freed and reads only the next one, the two never
+    // overlap, and the waits that order refills against reads are the explicit ones of publish().
+    G355_LDS uint8_t *const lds = (G355_LDS uint8_t *)smem;
+    auto mma_kstep = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int m = 0; m < T::TM * T::TN; ++m)
+            mma_one(buf, m / T::TM, m % T::TM);
+    };
+    // k-steps 0 .. KSTEPS-2 of the slab in `cur` (its first fragments are in registers), then the
+    // slab's barrier
+    auto until_barrier = [&](const G355_LDS uint8_t *cur) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kstep = 0; kstep < T::KSTEPS - 1; ++kstep) {
+#pragma unroll
+            for (int u = 0; u < NF; ++u)
+                load_frag(cur, kstep + 1, (kstep + 1) & 1, u);
+            mma_kstep(kstep & 1);
+        }
+        publish();
+    };
+    // from the barrier of slab kt to the barrier of slab kt + 1
+    auto after_barrier = [&](G355_LDS uint8_t *__restrict__ freed, const G355_LDS uint8_t *__restrict__ next, int kt)
+                             __attribute__((always_inline)) {
+#pragma unroll
+        for (int l = 0; l < NL; ++l)
+            issue_one(l, kt + T::NS, freed);
+#pragma unroll
+        for (int u = 0; u < NF; ++u)
+            load_frag(next, 0, 0, u);
+        mma_kstep((T::KSTEPS - 1) & 1);
+        if (kt + 1 < kt_count)
+            until_barrier(next);
+    };
+
     if (kt_count > 0) {
 #pragma unroll
         for (int s = 0; s < T::NS; ++s)
 #pragma unroll
             for (int l = 0; l < NL; ++l)
-                issue_one(l, s, s);
+                issue_one(l, s, lds + s * T::STAGE);
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((T::NS - 1) * FULL) : "memory");
 #pragma unroll
         for (int u = 0; u < NF; ++u)
-            load_frag(0, 0, 0, u);
-    }
-    int stage = 0;                         // stage of slab kt
-    for (int kt = 0; kt < kt_count; ++kt) {
-        const int next = (stage + 1 == T::NS) ? 0 : stage + 1;
-#pragma unroll
-        for (int kstep = 0; kstep < T::KSTEPS - 1; ++kstep) {
-#pragma unroll
-            for (int u = 0; u < NF; ++u)
-                load_frag(stage, kstep + 1, (kstep + 1) & 1, u);
-#pragma unroll
-            for (int m = 0; m < T::TM * T::TN; ++m)
-                mma_one(kstep & 1, m / T::TM, m % T::TM);
+            load_frag(lds, 0, 0, u);
+        until_barrier(lds);
+        int stage = 0;                         // stage of slab kt
+        for (int kt = 0; kt < kt_count; ++kt) {
+            const int next = (stage + 1 == T::NS) ? 0 : stage + 1;
+            after_barrier(lds + stage * T::STAGE, lds + next * T::STAGE, kt);
+            stage = next;
         }
-        publish();
-#pragma unroll
-        for (int l = 0; l < NL; ++l)
-            issue_one(l, kt + T::NS, stage);
-#pragma unroll
-        for (int u = 0; u < NF; ++u)
-            load_frag(next, 0, 0, u);
-#pragma unroll
-        for (int m = 0; m < T::TM * T::TN; ++m)
-            mma_one((T::KSTEPS - 1) & 1, m / T::TM, m % T::TM);
-        stage = next;
     }
     // nothing may still be in flight towards LDS when the workgroup ends
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
