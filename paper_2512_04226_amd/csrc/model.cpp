@@ -48,19 +48,19 @@ static gemm_hw make_default_hw()
     h.mall_bytes = 256.0 * 1024 * 1024;
     h.clk_ghz = 2.4;
     h.hbm_bytes_per_clk = 2700.0;    // 6.5 TB/s: the streaming-read probe's rate, of the 8 TB/s pins
-    h.mall_bytes_per_clk = 4000.0;   // what L2 misses are served at when the MALL holds the data (fitted; a streaming read sees 6.5 TB/s)
+    h.mall_bytes_per_clk = 2400.0;   // what L2 misses are served at when the MALL holds the data (fitted; a streaming read sees 6.5 TB/s)
     h.l2_bytes_per_clk = 2048.0;     // 16 channels x 128 B per XCD
     h.lds_bytes_per_clk = 118.0;     // ds_read_b128 fragments
     h.lds_tr_bytes_per_clk = 62.0;   // ds_read_b64_tr_* fragments
-    h.vmem_bytes_per_clk = 64.0;
-    h.mem_latency_clk = 2500.0;
-    h.cache_eff_frac = 0.5;
-    h.launch_clk = 1137.5;
-    h.wg_overhead_clk = 666.4;
-    h.epilogue_clk = 850.0;
-    h.reduce_launch_clk = 7200.0;
-    h.under_occ_frac = 0.72;
-    h.seg_eff_lo = 0.15;
+    h.vmem_bytes_per_clk = 25.3;       // direct-to-LDS fill rate a CU sustains next to its MFMA work (fitted)
+    h.mem_latency_clk = 1350.0;
+    h.cache_eff_frac = 0.175;
+    h.launch_clk = 2600.0;
+    h.wg_overhead_clk = 330.0;
+    h.epilogue_clk = 425.0;
+    h.reduce_launch_clk = 10600.0;   // 4.4 us: the second launch of a split-K or stream-K run
+    h.under_occ_frac = 0.85;
+    h.seg_eff_lo = 0.105;
     h.l_mi_clk[GEMM_BF16][0] = 35.6;      // v_mfma_f32_32x32x16_bf16  (2259 TFLOP/s device-wide)
     h.l_mi_clk[GEMM_BF16][1] = 27.8;      // v_mfma_f32_16x16x32_bf16  (1449 TFLOP/s)
     h.l_mi_clk[GEMM_FP8_E4M3][0] = 65.0;  // v_mfma_f32_32x32x64_f8f6f4 (4953 TFLOP/s)

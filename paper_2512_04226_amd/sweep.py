@@ -159,6 +159,39 @@ def sweep_grouped(name, shapes, dtype, b_layout=0):
             "top5": sorted(rows, key=lambda r: r["us"])[:5]}
 
 
+def summarize(paths):
+    """Text summary of sweep records (the JSONL files this tool wrote): one line per file with the
+    selection efficiency, then one line per shape."""
+    dt_name = {g.GEMM_BF16: "bf16", g.GEMM_FP8_E4M3: "fp8", g.GEMM_FP16: "fp16"}
+    heads, body = [], []
+    for path in paths:
+        recs = [json.loads(line) for line in open(path) if line.strip()]
+        if not recs:
+            continue
+        if "set" in recs[0]:      # grouped records
+            e = [r["efficiency"] for r in recs]
+            heads.append("%-52s n=%2d  median %.3f  mean %.3f  min %.3f  >=0.95: %d" % (
+                os.path.basename(path) + " (grouped)", len(e), np.median(e), np.mean(e), np.min(e), sum(x >= 0.95 for x in e)))
+            for r in recs:
+                tag = " groups%d" % r["groups"]
+                body.append("%-36s | %-44s %8.1f | %-44s %8.1f | %5.3f | %7.1f | separate launches %8.1f us" % (
+                    r["set"], r["pick"].replace(tag, ""), r["pick_us"], r["best"]["cfg"].replace(tag, ""), r["best"]["us"],
+                    r["efficiency"], r["pick_tflops"], r["separate_launches_us"]))
+            continue
+        e = [r["efficiency"] for r in recs]
+        n_cfg = [r["n_cfgs"] for r in recs]
+        heads.append("%-52s n=%2d  median %.3f  mean %.3f  min %.3f  >=0.95: %d  configs/shape %d..%d  Stream-K picked %d, sweep-best %d" % (
+            os.path.basename(path), len(e), np.median(e), np.mean(e), np.min(e), sum(x >= 0.95 for x in e), min(n_cfg),
+            max(n_cfg), sum("streamk" in r["pick"] for r in recs), sum("streamk" in r["best"]["cfg"] for r in recs)))
+        for r in recs:
+            body.append("%6d %6d %6d %-4s L%d | %-44s %8.1f | %-44s %8.1f | %5.3f | %7.1f" % (
+                r["M"], r["N"], r["K"], dt_name[r["dtype"]], r.get("b_layout", 0), r["pick"], r["pick_us"], r["best"]["cfg"],
+                r["best"]["us"], r["efficiency"], r["pick_tflops"]))
+    print("\n".join(heads))
+    print("\nPer shape (M N K dtype layout | pick | pick us | sweep best | best us | efficiency | pick TFLOP/s):")
+    print("\n".join(body))
+
+
 def shape_set(name):
     if name == "config5":
         return [(m, n, k, g.GEMM_BF16) for (m, n, k) in wl.config5_shapes()]
@@ -181,7 +214,11 @@ def main(argv=None):
     ap.add_argument("--quick", action="store_true")
     ap.add_argument("--b-layout", type=int, default=0, help="0: B row-major K x N, 1: B stored K-contiguous (N x K)")
     ap.add_argument("--all-rows", action="store_true", help="also write every config's timing")
+    ap.add_argument("--summarize", nargs="+", metavar="JSONL", help="print a text summary of sweep records and exit")
     args = ap.parse_args(argv)
+    if args.summarize:
+        summarize(args.summarize)
+        return
     if args.set == "grouped":
         os.makedirs(os.path.dirname(args.out) or ".", exist_ok=True)
         effs = []

@@ -61,7 +61,7 @@ def test_config3_skinny_bf16(g, oracle, N, K):
     for M in wl.SKINNY_M:
         A, B = wl.config3(M, N, K)
         cfg = g.gemm_select(M, N, K, BF16)
-        assert cfg.block_m <= max(64, M), cfg.describe()      # the selector shrinks BLOCK_M for few tokens
+        assert cfg.block_m <= max(128, M), cfg.describe()     # never a 256-row tile for a few tokens
         max_a = float(np.abs(wl.bf16_bits_to_f32(A)).max())
         max_b = float(np.abs(wl.bf16_bits_to_f32(B)).max())
         rows = np.arange(M) if M <= 16 else _rows_to_check(M, cfg.block_m, n_random=2)

@@ -228,7 +228,7 @@ def test_batched_selection_matches_the_oracle_and_scales_the_tile_count():
     device, so the selector stops splitting K and may take larger tiles."""
     from paper_2512_04226_amd import binding as g
     hw = _hw_dict(g)
-    M, N, K = 512, 512, 4096
+    M, N, K = 512, 512, 16384
     for batch in (1, 3, 64):
         best = None
         for idx in range(g.gemm_cfg_count(0)):
