@@ -1,14 +1,15 @@
 /*
  * gemm.h -- C ABI of the MI355X (gfx950) GEMM library.
  *
- * Computes C = alpha * A * B (the paper's Section II-A definition with beta = 0):
- *   A  M x K, row-major, leading dimension lda (elements), bf16 or fp8 e4m3 (OCP "e4m3fn")
+ * Computes C = alpha * A * B + beta * C (the paper's Section II-A definition; beta defaults to 0):
+ *   A  M x K, row-major, leading dimension lda (elements), bf16, IEEE fp16 or fp8 e4m3 (OCP "e4m3fn")
  *   B  K x N, row-major, leading dimension ldb (GEMM_B_ROW_MAJOR, the default), or stored as its
  *      transpose, N x K row-major, K-contiguous, ldb >= K (GEMM_B_K_CONTIGUOUS: the operand layout of
  *      the paper's own runs, Section V, and of an nn.Linear weight)
- *   C  M x N, row-major, leading dimension ldc, bf16, rounded to nearest even from an
- *      fp32 accumulator.
- * A, B, C and the split-K workspace are DEVICE pointers owned by the caller; the library
+ *   C  M x N, row-major, leading dimension ldc, bf16 (fp16 for fp16 inputs), rounded to nearest
+ *      even from an fp32 accumulator.
+ * One launch computes one product, a strided batch of equal shapes, or a group of different shapes.
+ * A, B, C, the split-K / Stream-K workspace and a grouped launch's table are DEVICE memory owned by the caller; the library
  * never allocates, frees or copies them.  Per-tensor fp8 scales enter as
  * cfg.alpha = scale_a * scale_b.
  *
