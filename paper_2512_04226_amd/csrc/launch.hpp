@@ -9,5 +9,5 @@ typedef hipError_t (*LaunchFn)(const KernelArgs &, hipStream_t);
 LaunchFn kLaunchBf16_0(int, int), kLaunchBf16_1(int, int), kLaunchBf16_2(int, int), kLaunchBf16_3(int, int),
     kLaunchFp8_0(int, int), kLaunchFp8_1(int, int), kLaunchFp16_0(int, int), kLaunchFp16_1(int, int),
     kLaunchFp16_2(int, int), kLaunchFp16_3(int, int), kLaunchBf16_4(int, int),
-    kLaunchFp16_4(int, int);   // fp16 shares the bf16 variant lists
+    kLaunchFp16_4(int, int), kLaunchBf16_5(int, int), kLaunchFp16_5(int, int);   // fp16 shares the bf16 variant lists
 }  // namespace g355

@@ -125,6 +125,7 @@ LaunchFn launcher_of(int dtype, int id, int bl)
     constexpr int n_b1 = 0 G355_VARIANTS_BF16_1(G355_COUNT);
     constexpr int n_b2 = 0 G355_VARIANTS_BF16_2(G355_COUNT);
     constexpr int n_b3 = 0 G355_VARIANTS_BF16_3(G355_COUNT);
+    constexpr int n_b4 = 0 G355_VARIANTS_BF16_4(G355_COUNT);
     constexpr int n_f0 = 0 G355_VARIANTS_FP8_0(G355_COUNT);
 #undef G355_COUNT
     if (dtype == GEMM_FP16) {
@@ -136,7 +137,9 @@ LaunchFn launcher_of(int dtype, int id, int bl)
             return kLaunchFp16_2(id - n_b0 - n_b1, bl);
         if (id < n_b0 + n_b1 + n_b2 + n_b3)
             return kLaunchFp16_3(id - n_b0 - n_b1 - n_b2, bl);
-        return kLaunchFp16_4(id - n_b0 - n_b1 - n_b2 - n_b3, bl);
+        if (id < n_b0 + n_b1 + n_b2 + n_b3 + n_b4)
+            return kLaunchFp16_4(id - n_b0 - n_b1 - n_b2 - n_b3, bl);
+        return kLaunchFp16_5(id - n_b0 - n_b1 - n_b2 - n_b3 - n_b4, bl);
     }
     if (dtype == GEMM_BF16) {
         if (id < n_b0)
@@ -147,7 +150,9 @@ LaunchFn launcher_of(int dtype, int id, int bl)
             return kLaunchBf16_2(id - n_b0 - n_b1, bl);
         if (id < n_b0 + n_b1 + n_b2 + n_b3)
             return kLaunchBf16_3(id - n_b0 - n_b1 - n_b2, bl);
-        return kLaunchBf16_4(id - n_b0 - n_b1 - n_b2 - n_b3, bl);
+        if (id < n_b0 + n_b1 + n_b2 + n_b3 + n_b4)
+            return kLaunchBf16_4(id - n_b0 - n_b1 - n_b2 - n_b3, bl);
+        return kLaunchBf16_5(id - n_b0 - n_b1 - n_b2 - n_b3 - n_b4, bl);
     }
     if (id < n_f0)
         return kLaunchFp8_0(id, bl);
