@@ -30,7 +30,7 @@
 extern "C" {
 #endif
 
-#define GEMM_ABI_VERSION 5u
+#define GEMM_ABI_VERSION 6u
 
 typedef enum gemm_dtype {
     GEMM_BF16 = 0,     /* A, B bf16; C bf16 */

@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("GEMM355_LIB") or os.path.join(_PKG, "libgemm355.so") 
 GEMM_BF16 = 0
 GEMM_FP8_E4M3 = 1
 GEMM_FP16 = 2
-GEMM_ABI_VERSION = 5
+GEMM_ABI_VERSION = 6
 GEMM_B_ROW_MAJOR = 0
 GEMM_B_K_CONTIGUOUS = 1
 

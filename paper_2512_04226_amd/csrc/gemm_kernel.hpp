@@ -492,50 +492,70 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     // nothing may still be in flight towards LDS when the workgroup ends
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-    // ---- epilogue: lane holds, per MFMA tile, output row m = lane % MI and
-    //      n = 8*(r/4) + 4*(lane/32) + r%4 (32x32) or n = 4*(lane/16) + r (16x16) ----
-    const int out_m = m0 + wm * T::WTM + (lane % MI);
-    const int out_nl = n0 + wn * T::WTN + 4 * (lane / MI);
+    // ---- epilogue: a lane holds, per MFMA tile, output row m = lane % MI and columns
+    //      n = 8*(r/4) + 4*(lane/32) + r%4 (32x32) or n = 4*(lane/16) + r (16x16).  Stored from
+    //      there, one instruction would write 16- or 32-byte pieces of many rows; instead every
+    //      wave passes its accumulators through a private piece of the (now free) LDS ring, one
+    //      MFMA row block (MI rows of its wave tile) at a time, and stores whole row segments of
+    //      its tile: 128 bytes and more per row.  Staged rows are padded by 16 bytes so that the
+    //      16-byte writes of a column of lanes spread over the banks. ----
+    typedef typename std::conditional<T::FT == 1, _Float16, __bf16>::type out_t;
+    typedef typename std::conditional<T::FT == 1, f16x8, bf16x8>::type out8_t;
+    constexpr int ST_ROW = T::WTN * 4 + 16;                 // bytes per staged row
+    constexpr int ST_CPR = T::WTN / 8;                      // 8-float chunks per row
+    static_assert(T::NW * MI * ST_ROW <= T::NS * T::STAGE, "the staging rows of all waves must fit the LDS ring");
     const float alpha = args.alpha, beta = args.beta;
+    // every wave's requests towards LDS have landed (above) and every wave is past its last fragment read
+    __syncthreads();
+    G355_LDS uint8_t *stg = lds + wave * (MI * ST_ROW);
+    const int st_w = (lane % MI) * ST_ROW + 16 * (lane / MI);      // this lane's row and 4-column group
+    const int row0 = m0 + wm * T::WTM, col0 = n0 + wn * T::WTN;    // origin of the wave tile
 #pragma unroll
     for (int i = 0; i < T::TM; ++i) {
-        const int m = out_m + i * MI;
-        if (m >= pM)
-            continue;
 #pragma unroll
-        for (int j = 0; j < T::TN; ++j) {
+        for (int j = 0; j < T::TN; ++j)
 #pragma unroll
             for (int q = 0; q < T::ACC / 4; ++q) {
-                const int n = out_nl + j * MI + q * 8;
-                if (n >= pN)
-                    continue;
                 f32x4 v;
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     v[r] = acc[j][i][q * 4 + r];
-                if (out_mode == 1) {
-                    float *dst = args.ws + ((bz * args.split_k + ks) * pM + m) * pN + n;
-                    *(f32x4 *)dst = v;
-                } else if (out_mode == 2) {
-                    float *dst = args.ws + ((size_t)(2 * blockIdx.x + seg) * BM + (m - m0)) * BN + (n - n0);
-                    *(f32x4 *)dst = v;
-                } else {
-                    typedef typename std::conditional<T::FT == 1, _Float16, __bf16>::type out_t;
-                    typedef typename std::conditional<T::FT == 1, f16x4, bf16x4>::type out4_t;
-                    out_t *dst = (out_t *)pC + bz * args.stride_c + (size_t)m * pldc + n;
-                    out4_t o;
-                    if (beta != 0.f) {
-                        const out4_t c = *(const out4_t *)dst;
+                *(G355_LDS f32x4 *)(stg + st_w + (j * MI + q * 8) * 4) = v;
+            }
+        // the wave reads back what it wrote itself (LDS operations of one wave complete in order):
+        // 8 consecutive columns per lane, so that a 16-bit result leaves as one 16-byte store
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            o[r] = (out_t)__builtin_fmaf(beta, (float)c[r], v[r] * alpha);
-                    } else {
+        for (int c0 = 0; c0 < MI * ST_CPR; c0 += 64) {
+            const int c = c0 + lane;
+            const int m = row0 + i * MI + c / ST_CPR, n = col0 + (c % ST_CPR) * 8;
+            if ((MI * ST_CPR % 64 != 0 && c >= MI * ST_CPR) || m >= pM || n >= pN)
+                continue;
+            const G355_LDS uint8_t *src = stg + (c / ST_CPR) * ST_ROW + (c % ST_CPR) * 32;
+            const f32x4 lo = *(const G355_LDS f32x4 *)src, hi = *(const G355_LDS f32x4 *)(src + 16);
+            if (out_mode != 0) {
+                float *dst = (out_mode == 1)
+                                 ? args.ws + ((bz * args.split_k + ks) * pM + m) * pN + n
+                                 : args.ws + ((size_t)(2 * blockIdx.x + seg) * BM + (m - m0)) * BN + (n - n0);
+                *(f32x4 *)dst = lo;
+                *(f32x4 *)(dst + 4) = hi;
+            } else {
+                out_t *dst = (out_t *)pC + bz * args.stride_c + (size_t)m * pldc + n;
+                out8_t o;
+                if (beta != 0.f) {
+                    const out8_t cin = *(const out8_t *)dst;
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            o[r] = (out_t)(v[r] * alpha);
+                    for (int r = 0; r < 4; ++r) {
+                        o[r] = (out_t)__builtin_fmaf(beta, (float)cin[r], lo[r] * alpha);
+                        o[r + 4] = (out_t)__builtin_fmaf(beta, (float)cin[r + 4], hi[r] * alpha);
                     }
-                    *(out4_t *)dst = o;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        o[r] = (out_t)(lo[r] * alpha);
+                        o[r + 4] = (out_t)(hi[r] * alpha);
+                    }
                 }
+                *(out8_t *)dst = o;
             }
         }
     }

@@ -24,9 +24,6 @@
     X(128, 256, 64, 2, 2, 32, 3, 2556, 2562) \
     X(128, 128, 64, 2, 2, 32, 2, 1192, 1190) \
     X(128, 128, 64, 2, 2, 32, 3, 1423, 1471) \
-    X(128, 128, 128, 2, 2, 32, 2, 2942, 3091) \
-    X(128, 128, 32, 2, 2, 32, 4, 675, 745) \
-    X(256, 64, 64, 4, 1, 32, 2, 1311, 1283) \
     X(64, 256, 64, 1, 4, 32, 2, 1442, 1357) \
     X(128, 64, 64, 2, 2, 32, 3, 762, 752) \
     X(64, 128, 64, 2, 2, 32, 3, 831, 750)
@@ -37,9 +34,7 @@
     X(32, 256, 64, 1, 4, 32, 2, 946, 933) \
     X(32, 128, 64, 1, 4, 32, 3, 555, 537) \
     X(32, 128, 128, 1, 4, 32, 2, 1038, 1033) \
-    X(32, 64, 128, 1, 2, 32, 3, 635, 669) \
-    X(64, 32, 128, 2, 1, 32, 3, 717, 687) \
-    X(32, 32, 128, 1, 1, 32, 3, 527, 474)
+    X(32, 64, 128, 1, 2, 32, 3, 635, 669)
 #define G355_VARIANTS_BF16_3(X)    \
     X(16, 256, 64, 1, 4, 16, 4, 947, 1096) \
     X(16, 256, 128, 1, 4, 16, 2, 2286, 2225) \
