@@ -36,7 +36,7 @@ def measure_rates():
 
 def measure_slab_clk(dtype, n, b_layout=0):
     hw = g.gemm_hw_get()
-    A, B, C = make_operands(n, n, n, dtype)
+    A, B, C = make_operands(n, n, n, dtype, normal=True)     # the headline workload's value distribution
     ws = Workspace()
     rows = []
     count = g.gemm_cfg_count(dtype)

@@ -12,85 +12,85 @@
 
 // bf16: BLOCK_K in elements; MFMA 32 -> v_mfma_f32_32x32x16_bf16, 16 -> v_mfma_f32_16x16x32_bf16
 #define G355_VARIANTS_BF16_0(X)    \
-    X(256, 256, 64, 2, 4, 32, 2, 4796, 4359) \
-    X(256, 256, 64, 2, 2, 32, 2, 4654, 4525) \
-    X(256, 256, 32, 2, 4, 32, 4, 2101, 2173) \
-    X(256, 256, 32, 2, 2, 32, 4, 2224, 2287) \
-    X(256, 256, 32, 2, 4, 32, 5, 2066, 2150) \
-    X(256, 128, 64, 2, 4, 32, 3, 2415, 2468) \
-    X(256, 128, 64, 2, 2, 32, 3, 2347, 2567) \
-    X(128, 256, 64, 2, 4, 32, 3, 2340, 2392)
+    X(256, 256, 64, 2, 4, 32, 2, 4637, 4181) \
+    X(256, 256, 64, 2, 2, 32, 2, 4508, 4383) \
+    X(256, 256, 32, 2, 4, 32, 4, 2064, 2109) \
+    X(256, 256, 32, 2, 2, 32, 4, 2118, 2196) \
+    X(256, 256, 32, 2, 4, 32, 5, 2035, 2119) \
+    X(256, 128, 64, 2, 4, 32, 3, 2383, 2475) \
+    X(256, 128, 64, 2, 2, 32, 3, 2338, 2515) \
+    X(128, 256, 64, 2, 4, 32, 3, 2313, 2344)
 #define G355_VARIANTS_BF16_1(X)    \
-    X(128, 256, 64, 2, 2, 32, 3, 2556, 2562) \
-    X(128, 128, 64, 2, 2, 32, 2, 1192, 1190) \
-    X(128, 128, 64, 2, 2, 32, 3, 1423, 1471) \
-    X(64, 256, 64, 1, 4, 32, 2, 1442, 1357) \
-    X(128, 64, 64, 2, 2, 32, 3, 762, 752) \
-    X(64, 128, 64, 2, 2, 32, 3, 831, 750)
+    X(128, 256, 64, 2, 2, 32, 3, 2535, 2627) \
+    X(128, 128, 64, 2, 2, 32, 2, 1187, 1159) \
+    X(128, 128, 64, 2, 2, 32, 3, 1408, 1435) \
+    X(64, 256, 64, 1, 4, 32, 2, 1442, 1338) \
+    X(128, 64, 64, 2, 2, 32, 3, 758, 747) \
+    X(64, 128, 64, 2, 2, 32, 3, 850, 765)
 #define G355_VARIANTS_BF16_2(X)    \
-    X(64, 64, 64, 2, 2, 32, 3, 524, 472) \
-    X(64, 64, 128, 2, 2, 32, 2, 916, 911) \
-    X(128, 32, 64, 4, 1, 32, 3, 627, 565) \
-    X(32, 256, 64, 1, 4, 32, 2, 946, 933) \
-    X(32, 128, 64, 1, 4, 32, 3, 555, 537) \
-    X(32, 128, 128, 1, 4, 32, 2, 1038, 1033) \
-    X(32, 64, 128, 1, 2, 32, 3, 635, 669)
+    X(64, 64, 64, 2, 2, 32, 3, 513, 462) \
+    X(64, 64, 128, 2, 2, 32, 2, 902, 900) \
+    X(128, 32, 64, 4, 1, 32, 3, 642, 578) \
+    X(32, 256, 64, 1, 4, 32, 2, 918, 933) \
+    X(32, 128, 64, 1, 4, 32, 3, 559, 532) \
+    X(32, 128, 128, 1, 4, 32, 2, 1003, 1013) \
+    X(32, 64, 128, 1, 2, 32, 3, 628, 659)
 #define G355_VARIANTS_BF16_3(X)    \
-    X(16, 256, 64, 1, 4, 16, 4, 947, 1096) \
-    X(16, 256, 128, 1, 4, 16, 2, 2286, 2225) \
-    X(16, 128, 128, 1, 4, 16, 4, 1086, 1167) \
-    X(16, 128, 256, 1, 4, 16, 2, 2526, 2462) \
-    X(16, 64, 128, 1, 4, 16, 4, 455, 474) \
-    X(16, 64, 256, 1, 4, 16, 3, 1341, 1395) \
-    X(16, 32, 256, 1, 2, 16, 3, 844, 760) \
-    X(16, 16, 256, 1, 1, 16, 3, 819, 737)
+    X(16, 256, 64, 1, 4, 16, 4, 950, 1091) \
+    X(16, 256, 128, 1, 4, 16, 2, 2272, 2222) \
+    X(16, 128, 128, 1, 4, 16, 4, 1072, 1096) \
+    X(16, 128, 256, 1, 4, 16, 2, 2527, 2428) \
+    X(16, 64, 128, 1, 4, 16, 4, 458, 475) \
+    X(16, 64, 256, 1, 4, 16, 3, 1340, 1435) \
+    X(16, 32, 256, 1, 2, 16, 3, 837, 754) \
+    X(16, 16, 256, 1, 1, 16, 3, 820, 738)
 // 16x16x32 MFMA on the larger tiles, eight waves: fewer accumulator register bytes per flop than
 // 32x32x16, which is what counts once the chip is power-limited
 #define G355_VARIANTS_BF16_4(X)    \
-    X(256, 256, 64, 2, 4, 16, 2, 4141, 4083) \
-    X(256, 256, 64, 4, 2, 16, 2, 4044, 4026) \
-    X(256, 128, 64, 2, 4, 16, 3, 2236, 2327) \
-    X(128, 256, 64, 2, 4, 16, 3, 2202, 2340) \
-    X(128, 128, 64, 2, 4, 16, 2, 1203, 1158) \
-    X(128, 64, 64, 2, 4, 16, 3, 775, 738) \
-    X(64, 128, 64, 2, 4, 16, 3, 746, 714) \
-    X(128, 64, 64, 2, 4, 16, 2, 800, 766) \
-    X(64, 128, 64, 2, 4, 16, 2, 918, 826) \
-    X(64, 64, 64, 2, 4, 16, 3, 481, 453) \
-    X(64, 64, 128, 2, 4, 16, 2, 927, 916) \
-    X(128, 128, 64, 4, 2, 16, 2, 1218, 1149) \
-    X(32, 64, 128, 1, 4, 16, 3, 621, 617)
+    X(256, 256, 64, 2, 4, 16, 2, 4136, 4041) \
+    X(256, 256, 64, 4, 2, 16, 2, 4098, 3969) \
+    X(256, 128, 64, 2, 4, 16, 3, 2260, 2311) \
+    X(128, 256, 64, 2, 4, 16, 3, 2203, 2270) \
+    X(128, 128, 64, 2, 4, 16, 2, 1206, 1133) \
+    X(128, 64, 64, 2, 4, 16, 3, 769, 732) \
+    X(64, 128, 64, 2, 4, 16, 3, 782, 705) \
+    X(128, 64, 64, 2, 4, 16, 2, 796, 791) \
+    X(64, 128, 64, 2, 4, 16, 2, 772, 736) \
+    X(64, 64, 64, 2, 4, 16, 3, 488, 451) \
+    X(64, 64, 128, 2, 4, 16, 2, 918, 921) \
+    X(128, 128, 64, 4, 2, 16, 2, 1215, 1130) \
+    X(32, 64, 128, 1, 4, 16, 3, 630, 619)
 
 // deeper LDS rings of tiles that win latency- and bandwidth-bound shapes (a request has NS-1 whole slabs
 // of time to land); of eight such candidates these three were sweep-best on 10-20 % of the irregular shapes
 #define G355_VARIANTS_BF16_5(X)    \
-    X(64, 128, 64, 2, 4, 16, 4, 868, 868) \
-    X(128, 128, 64, 2, 4, 16, 3, 1313, 1337) \
-    X(128, 128, 64, 2, 4, 16, 4, 1323, 1314)
+    X(64, 128, 64, 2, 4, 16, 4, 820, 860) \
+    X(128, 128, 64, 2, 4, 16, 3, 1306, 1294) \
+    X(128, 128, 64, 2, 4, 16, 4, 1307, 1292)
 
 // fp8 e4m3: MFMA 32 -> v_mfma_f32_32x32x64_f8f6f4, 16 -> v_mfma_f32_16x16x128_f8f6f4
 #define G355_VARIANTS_FP8_0(X)     \
-    X(256, 256, 128, 2, 4, 32, 2, 4373, 4254) \
-    X(256, 256, 128, 2, 2, 32, 2, 4515, 4196) \
-    X(256, 128, 128, 2, 4, 32, 3, 2304, 2350) \
-    X(128, 256, 128, 2, 4, 32, 3, 2231, 2280) \
-    X(128, 128, 128, 2, 2, 32, 2, 1125, 1143) \
-    X(128, 128, 128, 2, 2, 32, 3, 1363, 1436) \
-    X(128, 128, 256, 2, 2, 32, 2, 2865, 2866) \
-    X(128, 64, 128, 2, 2, 32, 3, 842, 757) \
-    X(64, 128, 128, 2, 2, 32, 3, 738, 749)
+    X(256, 256, 128, 2, 4, 32, 2, 4058, 4005) \
+    X(256, 256, 128, 2, 2, 32, 2, 4043, 4032) \
+    X(256, 128, 128, 2, 4, 32, 3, 2226, 2263) \
+    X(128, 256, 128, 2, 4, 32, 3, 2152, 2199) \
+    X(128, 128, 128, 2, 2, 32, 2, 1063, 1082) \
+    X(128, 128, 128, 2, 2, 32, 3, 1314, 1312) \
+    X(128, 128, 256, 2, 2, 32, 2, 2686, 2719) \
+    X(128, 64, 128, 2, 2, 32, 3, 816, 734) \
+    X(64, 128, 128, 2, 2, 32, 3, 715, 717)
 #define G355_VARIANTS_FP8_1(X)     \
-    X(64, 128, 256, 2, 2, 32, 3, 1954, 1943) \
-    X(64, 64, 128, 2, 2, 32, 3, 572, 514) \
-    X(64, 64, 256, 2, 2, 32, 2, 1132, 1019) \
-    X(64, 256, 128, 1, 4, 32, 2, 1216, 1263) \
-    X(32, 256, 128, 1, 4, 32, 2, 959, 959) \
-    X(32, 128, 256, 1, 4, 32, 2, 1058, 1087) \
-    X(32, 32, 256, 1, 1, 32, 3, 800, 720) \
-    X(16, 256, 256, 1, 4, 16, 2, 2634, 2536) \
-    X(16, 128, 256, 1, 4, 16, 4, 1192, 1223) \
-    X(16, 64, 256, 1, 4, 16, 4, 753, 678) \
-    X(16, 16, 256, 1, 1, 16, 4, 669, 602)
+    X(64, 128, 256, 2, 2, 32, 3, 1918, 1945) \
+    X(64, 64, 128, 2, 2, 32, 3, 556, 500) \
+    X(64, 64, 256, 2, 2, 32, 2, 1134, 1020) \
+    X(64, 256, 128, 1, 4, 32, 2, 1166, 1203) \
+    X(32, 256, 128, 1, 4, 32, 2, 943, 952) \
+    X(32, 128, 256, 1, 4, 32, 2, 1061, 1072) \
+    X(32, 32, 256, 1, 1, 32, 3, 789, 710) \
+    X(16, 256, 256, 1, 4, 16, 2, 2613, 2490) \
+    X(16, 128, 256, 1, 4, 16, 4, 1185, 1209) \
+    X(16, 64, 256, 1, 4, 16, 4, 751, 676) \
+    X(16, 16, 256, 1, 1, 16, 4, 668, 601)
 
 #define G355_VARIANTS_BF16(X) \
     G355_VARIANTS_BF16_0(X) G355_VARIANTS_BF16_1(X) G355_VARIANTS_BF16_2(X) G355_VARIANTS_BF16_3(X) G355_VARIANTS_BF16_4(X) \
