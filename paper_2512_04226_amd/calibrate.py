@@ -12,10 +12,11 @@ B K-contiguous).
 """
 import argparse
 
+import numpy as np
 import torch
 
 from . import binding as g
-from .sweep import Workspace, make_operands, time_cfg
+from .sweep import Workspace, make_operands
 
 
 def measure_rates():
@@ -34,19 +35,48 @@ def measure_rates():
     return out
 
 
-def measure_slab_clk(dtype, n, b_layout=0):
+def _time_plain(cfg, A, B, C, launches=10):
+    """Microseconds per launch: plain back-to-back launches between two events, after two warm-ups
+    (how an application, and bench.py, sees the kernel)."""
+    for _ in range(2):
+        g.gemm_run(cfg, A, B, C)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(launches):
+        g.gemm_run(cfg, A, B, C)
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / launches
+
+
+def measure_slab_clk(dtype, n, b_layout=0, passes=5):
+    """Median over `passes` sweeps of the variant list, each in a different order: the chip is
+    power-limited on these shapes, so what ran just before moves a timing by a few percent."""
     hw = g.gemm_hw_get()
     A, B, C = make_operands(n, n, n, dtype, normal=True)     # the headline workload's value distribution
     ws = Workspace()
-    rows = []
-    count = g.gemm_cfg_count(dtype)
+    cfgs = []
     seen = set()
-    for idx in range(count):
+    for idx in range(g.gemm_cfg_count(dtype)):
         cfg = g.gemm_cfg_at_ex(idx, n, n, n, dtype, b_layout)
-        if cfg is None or cfg.split_k != 1 or cfg.kernel_id in seen:
+        if cfg is None or cfg.split_k != 1 or cfg.stream_k or cfg.kernel_id in seen:
             continue
         seen.add(cfg.kernel_id)
-        us = time_cfg(cfg, A, B, C, ws, min_ms=3.0)
+        ws.ensure(cfg)
+        cfgs.append(cfg)
+    times = {c.kernel_id: [] for c in cfgs}
+    rng = np.random.default_rng(0)
+    for p in range(passes):
+        order = list(range(len(cfgs)))
+        if p % 2:
+            order.reverse()
+        if p >= 2:
+            rng.shuffle(order)
+        for i in order:
+            times[cfgs[i].kernel_id].append(_time_plain(cfgs[i], A, B, C))
+    rows = []
+    for cfg in cfgs:
+        us = float(np.median(times[cfg.kernel_id]))
         tiles = -(-n // cfg.block_m) * -(-n // cfg.block_n)
         slabs = -(-n // cfg.block_k)
         clk = us * hw.clk_ghz * 1e3 - hw.launch_clk
