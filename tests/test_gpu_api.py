@@ -55,3 +55,18 @@ def test_matmul_matches_the_oracle_across_dtypes_layouts_and_strides(oracle):
         api.matmul(dA.float(), dB.float())
     with pytest.raises(ValueError):
         api.matmul(dA, dB[:-8])
+
+
+@pytest.mark.parametrize("shape", [(1, 8, 8), (7, 8, 65536), (65537, 8, 8), (300001, 64, 64), (3, 16400, 24), (2049, 8, 4104)])
+def test_extreme_aspect_ratios_bit_exact(oracle, shape):
+    """Shapes at the edges of what the tiles were made for: one row, one 8-wide column block, a very
+    tall or very deep problem.  Integer data: exactly one correct result."""
+    from paper_2512_04226_amd import api
+    from gpu_util import to_dev
+    M, N, K = shape
+    A, B = wl.integer_bf16(M, N, K, seed=95)
+    ref16, _ = oracle.gemm(A, B, oracle.BF16)
+    C = api.matmul(to_dev(A).view(torch.bfloat16), to_dev(B).view(torch.bfloat16))
+    torch.cuda.synchronize()
+    got = C.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, ref16), (shape, api.select(M, N, K, 0).describe(), int((got != ref16).sum()))
