@@ -343,12 +343,13 @@ int gemm_select_batched(int64_t M, int64_t N, int64_t K, int64_t batch, int dtyp
     // fixed enumeration order and a strict '<': the first of equal predictions wins
     for (int id = 0; id < variant_count(dtype); ++id) {
         const Variant &v = variant_at(dtype, id);
+        FactorPairs pairs;
         for (int s = 0; s < kNumSplits; ++s) {
             if (!variant_legal(hw, v, dtype, M, N, K, split_k_of(s), stream_k_of(s), batch))
                 continue;
             gemm_prediction p;
             int gm, gn;
-            predict(hw, dtype, b_layout, M, N, K, v, split_k_of(s), stream_k_of(s), &p, &gm, &gn, batch);
+            predict(hw, dtype, b_layout, M, N, K, v, split_k_of(s), stream_k_of(s), &p, &gm, &gn, batch, nullptr, &pairs);
             if (best_id < 0 || p.l_total < best) {
                 best = p.l_total;
                 best_id = id;

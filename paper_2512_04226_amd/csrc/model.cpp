@@ -249,7 +249,7 @@ static double segment_efficiency(const gemm_hw &hw, double seg)
 // `bm_e` x `bn_e`: mean valid extent of a tile (rows and columns outside the matrix are never
 // fetched); `per_cu_mem`: tiles per CU whose bytes move (fractional in the last wave).
 static MemTerms memory_latency(const gemm_hw &hw, const Variant &v, int es, int b_layout, double per_cu, double active,
-                               double h1, double h2, double bm_e, double bn_e, double per_cu_mem)
+                               double h1, double h2, double bm_e, double bn_e, double per_cu_mem, double ea, double eb)
 {
     MemTerms t;
     // every load instruction of the nominal tile is issued; only the valid extent moves bytes
@@ -268,8 +268,7 @@ static MemTerms memory_latency(const gemm_hw &hw, const Variant &v, int es, int 
     t.l_l2 = (total / xcds_busy) / hw.l2_bytes_per_clk;
     t.l_mall = (1.0 - h1) * total / hw.mall_bytes_per_clk;
     // what misses both caches, inflated by the row-segment efficiency of each operand
-    const double ea = segment_efficiency(hw, (double)v.block_k * es);
-    const double eb = segment_efficiency(hw, (double)(b_layout ? v.block_k : v.block_n) * es);
+    // (ea, eb: row-segment efficiency of A and B, constant for the variant and layout)
     // Both hit rates come from Algorithm 5 on nested scopes, so h2 already contains the reuse h1
     // counts: the share of requested bytes that reaches HBM is what neither scope can serve,
     // min(1 - h1, 1 - h2), not the product (which could fall below the bytes the matrices hold).
@@ -297,7 +296,8 @@ static int label_of(const MemTerms &t, double l_comp, bool under, double fixed, 
 }
 
 void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, int64_t K, const Variant &v, int split_k,
-             int stream_k, gemm_prediction *p, int *group_m, int *group_n, int64_t batch, double *l_tile_full_out)
+             int stream_k, gemm_prediction *p, int *group_m, int *group_n, int64_t batch, double *l_tile_full_out,
+             FactorPairs *pairs)
 {
     std::memset(p, 0, sizeof(*p));
     const int es = elem_bytes(dtype);
@@ -330,8 +330,19 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
     const int l2_scope = hw.n_cu / hw.n_xcd * occ;
     double fm, fn, fm2, fn2;
     int fm_raw, fm2_raw;
-    best_factor_pair(l2_scope, v, tiles_m, tiles_n, &fm, &fn, &fm_raw);
-    best_factor_pair(hw.n_cu * occ, v, tiles_m, tiles_n, &fm2, &fn2, &fm2_raw);
+    // the pairs depend on the variant and the tile grid only: the K splits of one variant share them
+    if (pairs && pairs->valid) {
+        fm = pairs->fm[0], fn = pairs->fn[0], fm_raw = pairs->raw[0];
+        fm2 = pairs->fm[1], fn2 = pairs->fn[1], fm2_raw = pairs->raw[1];
+    } else {
+        best_factor_pair(l2_scope, v, tiles_m, tiles_n, &fm, &fn, &fm_raw);
+        best_factor_pair(hw.n_cu * occ, v, tiles_m, tiles_n, &fm2, &fn2, &fm2_raw);
+        if (pairs) {
+            pairs->fm[0] = fm, pairs->fn[0] = fn, pairs->raw[0] = fm_raw;
+            pairs->fm[1] = fm2, pairs->fn[1] = fn2, pairs->raw[1] = fm2_raw;
+            pairs->valid = true;
+        }
+    }
     // unique / requested counts of Algorithm 5 on the mean valid extent of a tile
     const double bm_e = (double)M / tiles_m, bn_e = (double)N / tiles_n;
     double h1 = hit_rate(fm, fn, bm_e, bn_e);
@@ -354,13 +365,15 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
     p->iters = slabs - 1.0;
     const double out_bytes = (split_k > 1) ? 4.0 : 2.0;
 
+    const double ea = segment_efficiency(hw, (double)v.block_k * es);
+    const double eb = segment_efficiency(hw, (double)(b_layout ? v.block_k : v.block_n) * es);
     auto tile_latency = [&](double per_cu, double act, double per_cu_mem, MemTerms *mt_out, double *l_comp_out,
                             double *pro, double *epi, double *iter) {
         // per_cu tiles share the CU; fewer than fit run a little faster each, but not in proportion
         double l_comp = (double)(b_layout ? v.slab_clk_kc : v.slab_clk) * per_cu;
         if (per_cu < occ)
             l_comp *= hw.under_occ_frac + (1.0 - hw.under_occ_frac) * per_cu / occ;
-        const MemTerms mt = memory_latency(hw, v, es, b_layout, per_cu, act, h1, h2, bm_e, bn_e, per_cu_mem);
+        const MemTerms mt = memory_latency(hw, v, es, b_layout, per_cu, act, h1, h2, bm_e, bn_e, per_cu_mem, ea, eb);
         const double l_pro = mt.l_mem + hw.mem_latency_clk + hw.wg_overhead_clk;
         // the store stage scales with the output tile only; results leave through HBM
         const double l_epi = act * per_cu * v.block_m * v.block_n * out_bytes / hw.hbm_bytes_per_clk + hw.epilogue_clk;
@@ -422,7 +435,7 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
         const double tile_elems = (double)v.block_m * v.block_n;
         // workers that share an L2 are at different K offsets of different tiles: no L2 reuse
         const MemTerms mt_sk =
-            memory_latency(hw, v, es, b_layout, (double)occ, (double)hw.n_cu, 0.0, h2, bm_e, bn_e, (double)occ);
+            memory_latency(hw, v, es, b_layout, (double)occ, (double)hw.n_cu, 0.0, h2, bm_e, bn_e, (double)occ, ea, eb);
         const double iter_sk = std::max(lc_full, mt_sk.l_mem);
         const double pro_sk = mt_sk.l_mem + hw.mem_latency_clk + hw.wg_overhead_clk;
         const double l_epi_sk = hw.n_cu * occ * tile_elems * 4.0 / hw.hbm_bytes_per_clk + hw.epilogue_clk;

@@ -20,9 +20,16 @@ int64_t k_per_split(const Variant &v, int64_t K, int split_k);
 bool variant_legal(const gemm_hw &hw, const Variant &v, int dtype, int64_t M, int64_t N, int64_t K, int split_k,
                    int stream_k, int64_t batch = 1);
 int stream_k_workers(const gemm_hw &hw, const Variant &v, int dtype);
+// Algorithm 6's chosen pairs for the L2 and the device scope of one (variant, M, N): a caller that
+// evaluates several K splits of one variant passes the same object to reuse them.
+struct FactorPairs {
+    double fm[2], fn[2];
+    int raw[2];
+    bool valid = false;
+};
 void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, int64_t K, const Variant &v, int split_k,
              int stream_k, gemm_prediction *p, int *group_m, int *group_n, int64_t batch = 1,
-             double *l_tile_full_out = nullptr);
+             double *l_tile_full_out = nullptr, FactorPairs *pairs = nullptr);
 // Grouped launch of n shapes (M == 0: empty group) with one variant: total latency in clocks, the
 // label of the group that weighs most, and each group's rasterisation band height.  False when
 // the variant cannot run some group or every group is empty.
