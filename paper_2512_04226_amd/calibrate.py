@@ -6,17 +6,42 @@ gemm_select or gemm_run):
     from one large compute-bound problem per datatype (8192^3).
 
 Prints the hardware lines and the variants.hpp rows with the two measured columns (B row-major,
-B K-contiguous).
+B K-contiguous); the two K-loop-form columns are carried over from the table as it stands.
 
     python -m paper_2512_04226_amd.calibrate [--n 8192]
+
+The K-loop form of each variant (LOOP / LOOP_KC columns) is chosen from a comparison of three
+builds of the library, each with one form forced on every variant:
+
+    for k in 0 1 2: python -m paper_2512_04226_amd.build --out /tmp/lf$k.so -DG355_FORCE_LOOP_FORM=$k
+    python -m paper_2512_04226_amd.calibrate --loop-forms /tmp/lf0.so /tmp/lf1.so /tmp/lf2.so
 """
 import argparse
+import ctypes
+import os
+import re
 
 import numpy as np
 import torch
 
 from . import binding as g
 from .sweep import Workspace, make_operands
+
+
+def table_loop_forms():
+    """(section, block_m, block_n, block_k, waves_m, waves_n, mfma, stages) -> (LOOP, LOOP_KC) as
+    written in csrc/variants.hpp."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "variants.hpp")
+    out, sect = {}, "BF16"
+    for line in open(path):
+        m = re.match(r"#define G355_VARIANTS_(BF16|FP8)_\d", line)
+        if m:
+            sect = m.group(1)
+        m = re.match(r"\s*X\(" + ", ".join([r"(\d+)"] * 11) + r"\)", line)
+        if m:
+            v = [int(x) for x in m.groups()]
+            out[(sect,) + tuple(v[:7])] = (v[9], v[10])
+    return out
 
 
 def measure_rates():
@@ -84,11 +109,77 @@ def measure_slab_clk(dtype, n, b_layout=0, passes=5):
     return rows
 
 
+def compare_loop_forms(lib_paths, n=8192, passes=7):
+    """Times every variant of every datatype and B layout in each of the given builds of the
+    library (the same cfg, plain launches, the builds and variants interleaved in shuffled
+    passes, median) and prints one line per variant: microseconds per build and the ratios to
+    the first.  The outputs of the builds are compared bit for bit first."""
+    libs = [ctypes.CDLL(p) for p in lib_paths]
+    for lib in libs:
+        lib.gemm_run.restype = ctypes.c_int
+
+    def run(lib, cfg, A, B, C):
+        rc = lib.gemm_run(ctypes.byref(cfg), g._ptr(A), g._ptr(B), g._ptr(C), ctypes.c_void_p(g._stream_handle(None)))
+        if rc != 0:
+            raise RuntimeError("gemm_run returned %d" % rc)
+
+    def time_one(lib, cfg, A, B, C, launches=6):
+        for _ in range(2):
+            run(lib, cfg, A, B, C)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(launches):
+            run(lib, cfg, A, B, C)
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / launches
+
+    rng = np.random.default_rng(1)
+    for dtype, name in ((g.GEMM_BF16, "bf16"), (g.GEMM_FP16, "fp16"), (g.GEMM_FP8_E4M3, "fp8")):
+        for bl in (0, 1):
+            A, B, C = make_operands(n, n, n, dtype, normal=True)
+            if bl:
+                B = B.t().contiguous()
+            cfgs, seen = [], set()
+            for idx in range(g.gemm_cfg_count(dtype)):
+                c = g.gemm_cfg_at_ex(idx, n, n, n, dtype, bl)
+                if c is None or c.split_k != 1 or c.stream_k or c.kernel_id in seen:
+                    continue
+                seen.add(c.kernel_id)
+                cfgs.append(c)
+            for c in cfgs:
+                outs = []
+                for lib in libs:
+                    C.zero_()
+                    run(lib, c, A, B, C)
+                    torch.cuda.synchronize()
+                    outs.append(C.clone())
+                if any(not torch.equal(outs[0], o) for o in outs[1:]):
+                    raise RuntimeError("builds disagree on " + c.describe())
+            times = {(c.kernel_id, i): [] for c in cfgs for i in range(len(libs))}
+            for _ in range(passes):
+                order = [(c, i) for c in cfgs for i in range(len(libs))]
+                rng.shuffle(order)
+                for c, i in order:
+                    times[(c.kernel_id, i)].append(time_one(libs[i], c, A, B, C))
+            for c in cfgs:
+                med = [float(np.median(times[(c.kernel_id, i)])) for i in range(len(libs))]
+                print("%s b_layout %d variant %-3d %-44s us %s  vs first %s" % (
+                    name, bl, c.kernel_id, c.describe(), " ".join("%8.1f" % x for x in med),
+                    " ".join("%.3f" % (x / med[0]) for x in med)), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--n", type=int, default=8192)
     ap.add_argument("--skip-rates", action="store_true")
+    ap.add_argument("--loop-forms", nargs="+", metavar="LIB",
+                    help="compare builds of the library (one per forced K-loop form) instead of calibrating")
     args = ap.parse_args()
+    if args.loop_forms:
+        compare_loop_forms(args.loop_forms, args.n)
+        return
+    forms = table_loop_forms()
     if not args.skip_rates:
         r = measure_rates()
         for key, val in r.items():
@@ -104,9 +195,10 @@ def main():
             # the K-contiguous gain of a small tile on this huge problem (L2-resident panels, hundreds of
             # waves) is larger than what the small problems that pick such tiles see: floor it
             tau_kc = max(tau_kc, 0.9 * tau)
-            print("    X(%d, %d, %d, %d, %d, %d, %d, %d, %d)   // %.1f us %.0f TFLOP/s | K-contiguous B %.1f us %.0f TFLOP/s" % (
-                cfg.block_m, cfg.block_n, cfg.block_k, cfg.waves_m, cfg.waves_n, cfg.mfma, cfg.stages, round(tau),
-                round(tau_kc), us, 2.0 * args.n ** 3 / us * 1e-6, us_kc, 2.0 * args.n ** 3 / us_kc * 1e-6), flush=True)
+            key = (cfg.block_m, cfg.block_n, cfg.block_k, cfg.waves_m, cfg.waves_n, cfg.mfma, cfg.stages)
+            print("    X(%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d)   // %.1f us %.0f TFLOP/s | K-contiguous B %.1f us %.0f TFLOP/s" % (
+                key + (round(tau), round(tau_kc)) + forms[(name,) + key] +
+                (us, 2.0 * args.n ** 3 / us * 1e-6, us_kc, 2.0 * args.n ** 3 / us_kc * 1e-6)), flush=True)
 
 
 if __name__ == "__main__":

@@ -72,10 +72,25 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // layout of the paper's own runs, Section V): B is then staged and read exactly like A.
 // FT_ (16-bit inputs only): 0 bf16 in / bf16 out, 1 IEEE fp16 in / fp16 out (the precision of the
 // paper's runs); the data path is the same, only the MFMA instruction and the output rounding differ.
-template <int ES_, int BM_, int BN_, int BK_, int WM_, int WN_, int MI_, int NS_, int BL_, int FT_ = 0>
+// LF_: form of the K loop, one of three source arrangements of the same work between which the
+// compiler's instruction schedule, and with it the time per slab, differs by up to 15 % either
+// way; which one a variant uses is measured (8192^3, the three forms interleaved) and recorded
+// in the variant table.  0: one loop over all slabs, the part up to the next barrier under a
+// condition that is false for the last slab.  1: the last slab peeled off, so the first fragment
+// reads of the next slab cannot sink into a conditional part below the MFMAs meant to hide them.
+// 2: as 1, and no memory instruction may be scheduled across the end of the refill (the refill
+// of the freed stage goes out first: it has the fewest iterations to land in a two-stage ring).
+// Building with -DG355_FORCE_LOOP_FORM=k gives every variant form k (how the forms are compared).
+template <int ES_, int BM_, int BN_, int BK_, int WM_, int WN_, int MI_, int NS_, int BL_, int FT_ = 0, int LF_ = 0>
 struct Tile {
     static constexpr int ES = ES_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MI = MI_, NS = NS_, BL = BL_;
     static constexpr int FT = FT_;
+#ifdef G355_FORCE_LOOP_FORM
+    static constexpr int LF = G355_FORCE_LOOP_FORM;
+#else
+    static constexpr int LF = LF_;
+#endif
+    static_assert(LF >= 0 && LF <= 2, "unknown K-loop form");
     static_assert(FT == 0 || ES == 2, "fp16 is a 16-bit input type");
     static constexpr int NW = WM * WN;
     static constexpr int NT = WM * WN * 64;
@@ -431,6 +446,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     constexpr int FULL = T::common_loads();
     constexpr int ALLOW = (T::NS - 2) * FULL;
     static_assert((T::NS - 1) * FULL <= 63, "vmcnt is a 6-bit counter");
+    constexpr int LF = T::LF;
     auto publish = [&]() { asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(ALLOW) : "memory"); };
 
     // The compiler cannot tell which LDS bytes a direct-to-LDS load will write, and before an LDS
@@ -463,11 +479,15 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
 #pragma unroll
         for (int l = 0; l < NL; ++l)
             issue_one(l, kt + T::NS, freed);
+        // form 2: no memory instruction may be scheduled across this point (ALU and MFMA
+        // instructions may), or the refill drifts down the iteration it has to land in
+        if constexpr (LF == 2)
+            __builtin_amdgcn_sched_barrier(0xF);
 #pragma unroll
         for (int u = 0; u < NF; ++u)
             load_frag(next, 0, 0, u);
         mma_kstep((T::KSTEPS - 1) & 1);
-        if (kt + 1 < kt_count)
+        if (LF != 0 || kt + 1 < kt_count)
             until_barrier(next);
     };
 
@@ -483,11 +503,14 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             load_frag(lds, 0, 0, u);
         until_barrier(lds);
         int stage = 0;                         // stage of slab kt
-        for (int kt = 0; kt < kt_count; ++kt) {
+        // forms 1 and 2 peel the last slab off (see Tile)
+        for (int kt = 0; kt + (LF != 0) < kt_count; ++kt) {
             const int next = (stage + 1 == T::NS) ? 0 : stage + 1;
             after_barrier(lds + stage * T::STAGE, lds + next * T::STAGE, kt);
             stage = next;
         }
+        if constexpr (LF != 0)
+            mma_kstep((T::KSTEPS - 1) & 1);
     }
     // nothing may still be in flight towards LDS when the workgroup ends
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

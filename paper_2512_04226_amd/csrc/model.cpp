@@ -17,7 +17,7 @@
 
 namespace g355 {
 
-#define G355_X(bm, bn, bk, wm, wn, mi, ns, tau, tau_kc) {bm, bn, bk, wm, wn, mi, ns, tau, tau_kc},
+#define G355_X(bm, bn, bk, wm, wn, mi, ns, tau, tau_kc, lf, lf_kc) {bm, bn, bk, wm, wn, mi, ns, tau, tau_kc},
 static const Variant kVariantsBf16[] = {G355_VARIANTS_BF16(G355_X)};
 static const Variant kVariantsFp8[] = {G355_VARIANTS_FP8(G355_X)};
 #undef G355_X
