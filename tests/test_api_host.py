@@ -1,4 +1,5 @@
-"""Argument checks of api.matmul that need no GPU, and the sweep tool's summary of its own records."""
+"""Argument checks of api.matmul that need no GPU, the sweep tool's summary of its own records, and the
+calibration tool's reading of the variant table."""
 import json
 
 import pytest
@@ -39,3 +40,21 @@ def test_sweep_summary_of_records(tmp_path, capsys):
     out = capsys.readouterr().out
     assert "a_0.jsonl" in out and "median 0.800" in out and "Stream-K picked 1, sweep-best 0" in out
     assert "grouped.jsonl (grouped)" in out and "two groups" in out and "separate launches" in out
+
+
+def test_variant_table_loop_form_columns_cover_every_compiled_variant():
+    """calibrate.py reprints the variant table and must carry the two K-loop-form columns over: its
+    parser has to find one row per compiled variant, in table order, with forms 0, 1 or 2."""
+    from paper_2512_04226_amd import binding as g, calibrate
+
+    forms = calibrate.table_loop_forms()
+    for sect, dtype in (("BF16", g.GEMM_BF16), ("FP8", g.GEMM_FP8_E4M3)):
+        rows = [k for k in forms if k[0] == sect]
+        assert len(rows) == g.gemm_variant_count(dtype)
+        seen = set()
+        for idx in range(g.gemm_cfg_count(dtype)):
+            c = g.gemm_cfg_at(idx, 8192, 8192, 8192, dtype)
+            if c is not None:
+                seen.add((sect, c.block_m, c.block_n, c.block_k, c.waves_m, c.waves_n, c.mfma, c.stages))
+        assert seen == set(rows)
+    assert all(lf in (0, 1, 2) and lf_kc in (0, 1, 2) for lf, lf_kc in forms.values())
