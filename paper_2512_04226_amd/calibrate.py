@@ -13,8 +13,10 @@ B K-contiguous); the two K-loop-form columns are carried over from the table as 
 The K-loop form of each variant (LOOP / LOOP_KC columns) is chosen from a comparison of three
 builds of the library, each with one form forced on every variant:
 
-    for k in 0 1 2: python -m paper_2512_04226_amd.build --out /tmp/lf$k.so -DG355_FORCE_LOOP_FORM=$k
-    python -m paper_2512_04226_amd.calibrate --loop-forms /tmp/lf0.so /tmp/lf1.so /tmp/lf2.so
+    for k in 0 1 2 3: python -m paper_2512_04226_amd.build --out /tmp/lf$k.so -DG355_FORCE_LOOP_FORM=$k
+    python -m paper_2512_04226_amd.calibrate --loop-forms /tmp/lf0.so /tmp/lf1.so /tmp/lf2.so /tmp/lf3.so
+
+which ends with the table rows carrying the chosen forms.
 """
 import argparse
 import ctypes
@@ -28,9 +30,7 @@ from . import binding as g
 from .sweep import Workspace, make_operands
 
 
-def table_loop_forms():
-    """(section, block_m, block_n, block_k, waves_m, waves_n, mfma, stages) -> (LOOP, LOOP_KC) as
-    written in csrc/variants.hpp."""
+def _table(first, last):
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "variants.hpp")
     out, sect = {}, "BF16"
     for line in open(path):
@@ -40,8 +40,19 @@ def table_loop_forms():
         m = re.match(r"\s*X\(" + ", ".join([r"(\d+)"] * 11) + r"\)", line)
         if m:
             v = [int(x) for x in m.groups()]
-            out[(sect,) + tuple(v[:7])] = (v[9], v[10])
+            out[(sect,) + tuple(v[:7])] = tuple(v[first:last])
     return out
+
+
+def table_loop_forms():
+    """(section, block_m, block_n, block_k, waves_m, waves_n, mfma, stages) -> (LOOP, LOOP_KC) as
+    written in csrc/variants.hpp, in table order."""
+    return _table(9, 11)
+
+
+def table_rows():
+    """Same keys -> (SLAB_CLK, SLAB_CLK_KC)."""
+    return _table(7, 9)
 
 
 def measure_rates():
@@ -135,6 +146,7 @@ def compare_loop_forms(lib_paths, n=8192, passes=7):
         return e0.elapsed_time(e1) * 1e3 / launches
 
     rng = np.random.default_rng(1)
+    ratios = {}
     for dtype, name in ((g.GEMM_BF16, "bf16"), (g.GEMM_FP16, "fp16"), (g.GEMM_FP8_E4M3, "fp8")):
         for bl in (0, 1):
             A, B, C = make_operands(n, n, n, dtype, normal=True)
@@ -167,6 +179,22 @@ def compare_loop_forms(lib_paths, n=8192, passes=7):
                 print("%s b_layout %d variant %-3d %-44s us %s  vs first %s" % (
                     name, bl, c.kernel_id, c.describe(), " ".join("%8.1f" % x for x in med),
                     " ".join("%.3f" % (x / med[0]) for x in med)), flush=True)
+                key = (c.block_m, c.block_n, c.block_k, c.waves_m, c.waves_n, c.mfma, c.stages)
+                ratios.setdefault(("FP8" if dtype == g.GEMM_FP8_E4M3 else "BF16", bl) + key, []).append(
+                    [x / med[0] for x in med])
+    # the table's choice: build i is form i; bf16 and fp16 share the 16-bit list, so their ratios are
+    # averaged; a form other than 0 must be at least 1.5 % faster than form 0 to be taken
+    def choice(sect, bl, key):
+        mean = np.mean(np.array(ratios[(sect, bl) + key]), axis=0)
+        best = int(np.argmin(mean))
+        return best if mean[best] < 0.985 else 0
+
+    print("// LOOP / LOOP_KC columns chosen from the timings above (other columns as in the table)")
+    table = table_rows()
+    for full, (tau, tau_kc) in table.items():
+        sect, key = full[0], full[1:]
+        print("%s    X(%s, %d, %d, %d, %d)" % (sect, ", ".join(str(x) for x in key), tau, tau_kc,
+                                             choice(sect, 0, key), choice(sect, 1, key)), flush=True)
 
 
 def main():

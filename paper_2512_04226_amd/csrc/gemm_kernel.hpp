@@ -72,14 +72,18 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // layout of the paper's own runs, Section V): B is then staged and read exactly like A.
 // FT_ (16-bit inputs only): 0 bf16 in / bf16 out, 1 IEEE fp16 in / fp16 out (the precision of the
 // paper's runs); the data path is the same, only the MFMA instruction and the output rounding differ.
-// LF_: form of the K loop, one of three source arrangements of the same work between which the
+// LF_: form of the K loop, one of four source arrangements of the same work between which the
 // compiler's instruction schedule, and with it the time per slab, differs by up to 15 % either
-// way; which one a variant uses is measured (8192^3, the three forms interleaved) and recorded
+// way; which one a variant uses is measured (8192^3, the forms interleaved) and recorded
 // in the variant table.  0: one loop over all slabs, the part up to the next barrier under a
 // condition that is false for the last slab.  1: the last slab peeled off, so the first fragment
 // reads of the next slab cannot sink into a conditional part below the MFMAs meant to hide them.
 // 2: as 1, and no memory instruction may be scheduled across the end of the refill (the refill
 // of the freed stage goes out first: it has the fewest iterations to land in a two-stage ring).
+// 3: as 1, with the order of every k-step's memory and matrix instructions prescribed: after the
+// barrier the refill two loads per MFMA, then in each k-step the fragment reads of the next one a
+// few per MFMA over the first half of its MFMAs, so that a read has half a k-step to land (the
+// compiler alone issues reads next to their uses, which costs most with one wave per SIMD).
 // Building with -DG355_FORCE_LOOP_FORM=k gives every variant form k (how the forms are compared).
 template <int ES_, int BM_, int BN_, int BK_, int WM_, int WN_, int MI_, int NS_, int BL_, int FT_ = 0, int LF_ = 0>
 struct Tile {
@@ -90,7 +94,7 @@ struct Tile {
 #else
     static constexpr int LF = LF_;
 #endif
-    static_assert(LF >= 0 && LF <= 2, "unknown K-loop form");
+    static_assert(LF >= 0 && LF <= 3, "unknown K-loop form");
     static_assert(FT == 0 || ES == 2, "fp16 is a 16-bit input type");
     static constexpr int NW = WM * WN;
     static constexpr int NT = WM * WN * 64;
@@ -187,6 +191,28 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned by
 
 // beyond every window (windows are validated to stay below 2 GiB); small advances keep it there
 constexpr unsigned OOB_OFFSET = 0x80000000u;
+
+// Scheduling pipelines of K-loop form 3: COUNT times "A LDS reads (or A global loads), then one
+// MFMA".  The calls follow the code they order: a group takes the nearest matching instructions
+// before it, so the counts of a pipeline add up to exactly the instructions of its k-step.
+template <int COUNT, int A>
+__device__ __forceinline__ void sched_reads_then_mfma()
+{
+    if constexpr (COUNT > 0) {
+        __builtin_amdgcn_sched_group_barrier(0x100, A, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        sched_reads_then_mfma<COUNT - 1, A>();
+    }
+}
+template <int COUNT, int A>
+__device__ __forceinline__ void sched_fills_then_mfma()
+{
+    if constexpr (COUNT > 0) {
+        __builtin_amdgcn_sched_group_barrier(0x020, A, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        sched_fills_then_mfma<COUNT - 1, A>();
+    }
+}
 
 template <class T>
 __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
@@ -447,6 +473,11 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     constexpr int ALLOW = (T::NS - 2) * FULL;
     static_assert((T::NS - 1) * FULL <= 63, "vmcnt is a 6-bit counter");
     constexpr int LF = T::LF;
+    // form 3: LDS read instructions per k-step and how they are spread over its MN MFMAs
+    constexpr int MN = T::TM * T::TN;
+    constexpr int NFR = T::TM * (ES == 2 ? 1 : 2) + T::TN * (T::BL == 1 ? (ES == 2 ? 1 : 2) : (ES == 2 ? 2 : 4));
+    constexpr int RD_A = (NFR + (MN > 1 ? MN / 2 : 1) - 1) / (MN > 1 ? MN / 2 : 1);
+    constexpr int RD_PAIRS = NFR / RD_A, RD_REM = NFR - RD_PAIRS * RD_A;
     auto publish = [&]() { asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(ALLOW) : "memory"); };
 
     // The compiler cannot tell which LDS bytes a direct-to-LDS load will write, and before an LDS
@@ -470,6 +501,15 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             for (int u = 0; u < NF; ++u)
                 load_frag(cur, kstep + 1, (kstep + 1) & 1, u);
             mma_kstep(kstep & 1);
+            if constexpr (LF == 3) {
+                sched_reads_then_mfma<RD_PAIRS, RD_A>();
+                if constexpr (RD_REM > 0) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, RD_REM, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                }
+                if constexpr (MN - RD_PAIRS - (RD_REM > 0) > 0)
+                    __builtin_amdgcn_sched_group_barrier(0x008, MN - RD_PAIRS - (RD_REM > 0), 0);
+            }
         }
         publish();
     };
@@ -487,6 +527,27 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         for (int u = 0; u < NF; ++u)
             load_frag(next, 0, 0, u);
         mma_kstep((T::KSTEPS - 1) & 1);
+        if constexpr (LF == 3) {
+            // the refill two loads per MFMA, then the fragment reads as in the other k-steps
+            constexpr int FP = (NL + 1) / 2 < MN / 2 ? (NL + 1) / 2 : MN / 2;     // MFMAs that carry fills
+            constexpr int RP = MN - FP;                                            // MFMAs left for the reads
+            constexpr int A3 = (NFR + (RP > 1 ? RP - 1 : 1) - 1) / (RP > 1 ? RP - 1 : 1);
+            constexpr int P3 = NFR / A3, R3 = NFR - P3 * A3;
+            if constexpr (FP > 0) {
+                sched_fills_then_mfma<FP - 1, 2>();
+                __builtin_amdgcn_sched_group_barrier(0x020, NL - 2 * (FP - 1), 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            } else {
+                __builtin_amdgcn_sched_group_barrier(0x020, NL, 0);
+            }
+            sched_reads_then_mfma<P3, A3>();
+            if constexpr (R3 > 0) {
+                __builtin_amdgcn_sched_group_barrier(0x100, R3, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            }
+            if constexpr (RP - P3 - (R3 > 0) > 0)
+                __builtin_amdgcn_sched_group_barrier(0x008, RP - P3 - (R3 > 0), 0);
+        }
         if (LF != 0 || kt + 1 < kt_count)
             until_barrier(next);
     };
