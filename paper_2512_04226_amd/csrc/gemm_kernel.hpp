@@ -195,6 +195,7 @@ constexpr unsigned OOB_OFFSET = 0x80000000u;
 // Scheduling pipelines of K-loop form 3: COUNT times "A LDS reads (or A global loads), then one
 // MFMA".  The calls follow the code they order: a group takes the nearest matching instructions
 // before it, so the counts of a pipeline add up to exactly the instructions of its k-step.
+// Group masks: 0x008 matrix instructions, 0x020 vector-memory loads, 0x100 LDS reads.
 template <int COUNT, int A>
 __device__ __forceinline__ void sched_reads_then_mfma()
 {
