@@ -108,6 +108,14 @@ def secondary(also, g, wl, np, torch, dev, sizes, timed_us, ensure_ws):
                                             "frac_of_hbm_peak": sk_bytes / us * 1e-3 / PEAK_HBM_GBPS,
                                             "picked": cfgs.describe()}
     also["hbm_stream_gbps"] = g.gemm_probe_stream(dBs, scratch)
+    # the same weight against 256 rows: still on the HBM side of the ridge (61 us of bytes, 48 us of flops at the peaks)
+    Mw = 256
+    dAw = torch.randn((Mw, Ks), device="cuda", generator=torch.Generator(device="cuda").manual_seed(2)).to(torch.bfloat16)
+    cfgw = g.gemm_select(Mw, Ns, Ks, g.GEMM_BF16)
+    us = timed_us(cfgw, dAw.view(torch.int16), dBs, torch.empty((Mw, Ns), dtype=torch.int16, device="cuda"))
+    w_bytes = (Mw * Ks + Ks * Ns + Mw * Ns) * 2.0
+    also["skinny_bf16_M256_N28672_K8192"] = {"us": us, "gbps": w_bytes / us * 1e-3, "frac_of_hbm_peak": w_bytes / us * 1e-3 / PEAK_HBM_GBPS,
+                                             "tflops": 2.0 * Mw * Ns * Ks / us * 1e-6, "picked": cfgw.describe()}
     del dBs
 
     # grouped launch: 16 groups of routing-like row counts (16384 rows in all) against one 4096 x 4096
