@@ -209,6 +209,8 @@ def shape_set(name):
         return [(n, n, n, g.GEMM_FP8_E4M3) for n in (1024, 4096, 8192)]
     if name == "fp16":      # the paper's precision; run with --b-layout 1 for its operand layout too
         return [(n, n, n, g.GEMM_FP16) for n in (1024, 2048, 4096, 8192)] + [(4864, 4096, 4096, g.GEMM_FP16)]
+    if name == "uniform128":    # the shape distribution and precision of the paper's Section V-A; --b-layout 1 for its layout
+        return [(m, n, k, g.GEMM_FP16) for (m, n, k) in wl.uniform128_shapes()]
     raise SystemExit("unknown shape set " + name)
 
 

@@ -147,6 +147,15 @@ def config5_shapes(count=64, seed=4, lo=64, hi=16384):
     return [tuple(int(v) for v in row) for row in dims]
 
 
+def uniform128_shapes(count=192, seed=5, hi=8192):
+    """Shapes drawn like those of the paper's selection-efficiency experiment (Section V-A): each of
+    M, N, K a uniformly random multiple of 128 up to 8192.  The paper uses 150,000 of them; this is a
+    seeded sample."""
+    g = np.random.default_rng(seed)
+    dims = 128 * g.integers(1, hi // 128 + 1, size=(count, 3))
+    return [tuple(int(v) for v in row) for row in dims]
+
+
 def config5(index, shapes=None):
     shapes = shapes or config5_shapes()
     M, N, K = shapes[index]

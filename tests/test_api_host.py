@@ -58,3 +58,13 @@ def test_variant_table_loop_form_columns_cover_every_compiled_variant():
                 seen.add((sect, c.block_m, c.block_n, c.block_k, c.waves_m, c.waves_n, c.mfma, c.stages))
         assert seen == set(rows)
     assert all(lf in (0, 1, 2, 3) and lf_kc in (0, 1, 2, 3) for lf, lf_kc in forms.values())
+
+
+def test_uniform128_shapes_follow_the_papers_recipe():
+    """Section V-A: dimensions are multiples of 128 up to 8192; the sample is seeded."""
+    from paper_2512_04226_amd import workloads as wl
+
+    s = wl.uniform128_shapes()
+    assert len(s) == 192 and s == wl.uniform128_shapes()
+    assert all(d % 128 == 0 and 128 <= d <= 8192 for shape in s for d in shape)
+    assert len({d for shape in s for d in shape}) > 48          # spread over the 64 possible values
