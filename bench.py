@@ -50,6 +50,29 @@ def cpu_baseline(A, B, rows):
             "sample": "%d evenly spaced rows of the 8192^3 product (%.1f s)" % (rows, dt)}
 
 
+def settled_us(torch, fn, reps=10):
+    """Microseconds per call of an enqueueing function in the chip's settled state: at least 30 ms of untimed
+    calls first (after idling the chip boosts, then throttles for 15-20 ms before it settles under its power
+    limit), then at least `reps` calls and 20 ms timed."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fn()                               # the first call of a kernel also loads its code
+    e0.record()
+    for _ in range(2):
+        fn()
+    e1.record()
+    e1.synchronize()
+    est_ms = max(e0.elapsed_time(e1) / 2, 1e-3)
+    for _ in range(int(30.0 / est_ms) + 1):
+        fn()
+    reps = max(reps, int(20.0 / est_ms) + 1)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
 def secondary(also, g, wl, np, torch, dev, sizes, timed_us, ensure_ws):
     """Figures outside the timed region: per-shape rates, the other layouts, precisions and the
     bandwidth-bound path, and the measured ceilings the rooflines are also quoted against."""
@@ -62,16 +85,8 @@ def secondary(also, g, wl, np, torch, dev, sizes, timed_us, ensure_ws):
     n_small = sizes[0]
     cfg_s = g.gemm_select(n_small, n_small, n_small, g.GEMM_BF16)
     sets = [dev[n_small]] + [tuple(t.clone() for t in dev[n_small]) for _ in range(3)]
-    for dA, dB, dC in sets:
-        g.gemm_run(cfg_s, dA, dB, dC)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for rep in range(5):
-        for dA, dB, dC in sets:
-            g.gemm_run(cfg_s, dA, dB, dC)
-    e1.record()
-    e1.synchronize()
-    also["bf16_%d_rotating_buffers_tflops" % n_small] = 2.0 * n_small ** 3 * 20 / (e0.elapsed_time(e1) * 1e-3) * 1e-12
+    us_rot = settled_us(torch, lambda: [g.gemm_run(cfg_s, dA, dB, dC) for dA, dB, dC in sets])
+    also["bf16_%d_rotating_buffers_tflops" % n_small] = 2.0 * n_small ** 3 * len(sets) / us_rot * 1e-6
     del sets
     n_big = sizes[-1]
     dBt = dev[n_big][1].t().contiguous()
@@ -138,16 +153,8 @@ def secondary(also, g, wl, np, torch, dev, sizes, timed_us, ensure_ws):
     singles = [(g.gemm_select(m, Ng, Kg, g.GEMM_BF16), t) for m, t in zip(rows, tensors) if m]
     ensure_ws(max(g.gemm_workspace_bytes(c1) for c1, _ in singles))   # a single pick may split K
 
-    def time_loop(fn, reps=10):
-        for _ in range(2):
-            fn()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record()
-        e1.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / reps
+    def time_loop(fn):
+        return settled_us(torch, fn)
 
     flops_g = 2.0 * sum(rows) * Ng * Kg
     us_g = time_loop(lambda: g.gemm_run_grouped(cfg_g, table, dtab))
@@ -161,15 +168,8 @@ def secondary(also, g, wl, np, torch, dev, sizes, timed_us, ensure_ws):
     # N(0,1) data under its power limit; not a baseline and not part of the product path)
     try:
         a16, b16 = dev[n_big][0].view(torch.bfloat16), dev[n_big][1].view(torch.bfloat16)
-        for _ in range(3):
-            torch.matmul(a16, b16)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(10):
-            torch.matmul(a16, b16)
-        e1.record()
-        e1.synchronize()
-        also["calibration_torch_matmul_bf16_%d_tflops" % n_big] = 2.0 * n_big ** 3 / (e0.elapsed_time(e1) * 1e-4) * 1e-12
+        us_v = settled_us(torch, lambda: torch.matmul(a16, b16))
+        also["calibration_torch_matmul_bf16_%d_tflops" % n_big] = 2.0 * n_big ** 3 / us_v * 1e-6
     except Exception as exc:   # the calibration figure is optional; the product figures above are not
         also["calibration_torch_matmul_bf16_%d_tflops" % n_big] = None
         print("bench.py: vendor calibration skipped (%s)" % exc, file=sys.stderr)
@@ -178,8 +178,12 @@ def secondary(also, g, wl, np, torch, dev, sizes, timed_us, ensure_ws):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    # A step takes about 1 ms.  After idling the chip first boosts, then throttles hard and needs 15-20 ms of
+    # continuous work to settle at its power-limited clock (8192^3 launches: 845, 958, 1121, 1088, 1000, ...
+    # back to 846 us): the warm-up has to outlast that, and the timed region is long enough to show the
+    # sustained rate (it is the same over 200 and over 1000 steps).
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--brief", action="store_true", help="skip the secondary figures (for profiler runs)")
     ap.add_argument("--cpu-rows", type=int, default=4096)
@@ -271,17 +275,9 @@ def main():
             ws = torch.empty(need // 4, dtype=torch.float32, device="cuda")
             g.gemm_set_workspace(ws)
 
-    def timed_us(cfg, dA, dB, dC, reps=10):
+    def timed_us(cfg, dA, dB, dC):
         ensure_ws(g.gemm_workspace_bytes(cfg))
-        for _ in range(2):
-            g.gemm_run(cfg, dA, dB, dC)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            g.gemm_run(cfg, dA, dB, dC)
-        e1.record()
-        e1.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / reps
+        return settled_us(torch, lambda: g.gemm_run(cfg, dA, dB, dC))
 
     also = {}
     if not args.brief:
