@@ -30,7 +30,7 @@
 extern "C" {
 #endif
 
-#define GEMM_ABI_VERSION 6u
+#define GEMM_ABI_VERSION 7u
 
 typedef enum gemm_dtype {
     GEMM_BF16 = 0,     /* A, B bf16; C bf16 */
@@ -97,6 +97,8 @@ typedef struct gemm_hw {
     double reduce_launch_clk;  /* fixed cost of the split-K reduction pass */
     double under_occ_frac;     /* slab cost of a tile that has a CU to itself, as a fraction of its cost when the CU is full */
     double seg_eff_lo;         /* share of the HBM rate reached with 32-byte row segments (1 from 256 bytes up) */
+    double overlap_frac;       /* with two or more workgroups resident per CU: share of a tile's prologue and store stage
+                                  that hides under the other workgroups' K loops in every wave but the last (0 .. 1) */
     double l_mi_clk[2][2];     /* issue interval L_MI of one MFMA: [dtype][0: 32x32, 1: 16x16] */
 } gemm_hw;
 

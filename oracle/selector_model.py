@@ -265,8 +265,11 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0, batch=1):
         l_reduce = hw["reduce_launch_clk"] + nbytes / rate
     out["l_reduce"] = l_reduce
     # Algorithm 9.  READING: full waves and the under-occupied last wave are priced separately,
-    # plus one launch.
-    out["l_total"] = hw["launch_clk"] + (waves - 1) * full["l_tile"] + tail["l_tile"] + l_reduce
+    # plus one launch; with two or more workgroups resident per CU a share overlap_frac of a tile's
+    # prologue and store stage hides under the other workgroups' K loops in every wave that is
+    # followed by another.
+    hidden = hw["overlap_frac"] * (full["l_prologue"] + full["l_epilogue"]) if (occ >= 2 and waves > 1) else 0.0
+    out["l_total"] = hw["launch_clk"] + (waves - 1) * (full["l_tile"] - hidden) + tail["l_tile"] + l_reduce
 
     if stream_k:
         # READING (fractional waves in Algorithms 4 and 9): after `whole` full waves the remaining

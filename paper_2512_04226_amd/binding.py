@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("GEMM355_LIB") or os.path.join(_PKG, "libgemm355.so") 
 GEMM_BF16 = 0
 GEMM_FP8_E4M3 = 1
 GEMM_FP16 = 2
-GEMM_ABI_VERSION = 6
+GEMM_ABI_VERSION = 7
 GEMM_B_ROW_MAJOR = 0
 GEMM_B_K_CONTIGUOUS = 1
 
@@ -46,7 +46,8 @@ class gemm_hw(ctypes.Structure):
                 ("cache_eff_frac", ctypes.c_double), ("launch_clk", ctypes.c_double),
                 ("wg_overhead_clk", ctypes.c_double), ("epilogue_clk", ctypes.c_double),
                 ("reduce_launch_clk", ctypes.c_double), ("under_occ_frac", ctypes.c_double),
-                ("seg_eff_lo", ctypes.c_double), ("l_mi_clk", (ctypes.c_double * 2) * 2)]
+                ("seg_eff_lo", ctypes.c_double), ("overlap_frac", ctypes.c_double),
+                ("l_mi_clk", (ctypes.c_double * 2) * 2)]
 
 
 class gemm_cfg(ctypes.Structure):

@@ -454,7 +454,8 @@ int gemm_hw_set(const gemm_hw *in)
     if (in->n_cu < 1 || in->n_xcd < 1 || in->n_cu % in->n_xcd || in->simd_per_cu < 1 || in->clk_ghz <= 0 ||
         in->hbm_bytes_per_clk <= 0 || in->mall_bytes_per_clk <= 0 || in->l2_bytes_per_clk <= 0 ||
         in->lds_bytes_per_clk <= 0 || in->lds_tr_bytes_per_clk <= 0 || in->vmem_bytes_per_clk <= 0 ||
-        in->lds_bytes <= 0 || in->under_occ_frac <= 0 || in->under_occ_frac > 1 || in->seg_eff_lo <= 0 || in->seg_eff_lo > 1)
+        in->lds_bytes <= 0 || in->under_occ_frac <= 0 || in->under_occ_frac > 1 || in->seg_eff_lo <= 0 || in->seg_eff_lo > 1 ||
+        in->overlap_frac < 0 || in->overlap_frac > 1)
         return GEMM_ERR_SHAPE;
     hw_replace(*in);
     return GEMM_OK;

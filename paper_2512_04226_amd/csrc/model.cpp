@@ -61,6 +61,7 @@ static gemm_hw make_default_hw()
     h.reduce_launch_clk = 10600.0;   // 4.4 us: the second launch of a split-K or stream-K run
     h.under_occ_frac = 0.85;
     h.seg_eff_lo = 0.105;
+    h.overlap_frac = 0.5;            // fitted
     h.l_mi_clk[GEMM_BF16][0] = 35.6;      // v_mfma_f32_32x32x16_bf16  (2259 TFLOP/s device-wide)
     h.l_mi_clk[GEMM_BF16][1] = 27.8;      // v_mfma_f32_16x16x32_bf16  (1449 TFLOP/s)
     h.l_mi_clk[GEMM_FP8_E4M3][0] = 65.0;  // v_mfma_f32_32x32x64_f8f6f4 (4953 TFLOP/s)
@@ -420,8 +421,11 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
     }
     p->l_reduce = l_reduce;
 
-    // Algorithm 9, with full waves and the under-occupied last wave priced separately.
-    p->l_total = hw.launch_clk + (waves - 1.0) * l_tile_full + l_tile_tail + l_reduce;
+    // Algorithm 9, with full waves and the under-occupied last wave priced separately.  With two or
+    // more workgroups resident on a CU, part of a tile's prologue and store stage hides under the K
+    // loops of the others whenever another wave of tiles follows.
+    const double hidden = (occ >= 2 && has_full) ? hw.overlap_frac * (pro + epi) : 0.0;
+    p->l_total = hw.launch_clk + (waves - 1.0) * (l_tile_full - hidden) + l_tile_tail + l_reduce;
 
     if (stream_k) {
         // Fractional last wave: the tiles % slots tiles left over after the whole waves are cut

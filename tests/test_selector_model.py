@@ -173,7 +173,7 @@ def test_model_reduces_to_the_papers_form_when_extras_are_off():
               clk_ghz=2.4, hbm_bytes_per_clk=2500.0, mall_bytes_per_clk=6000.0, l2_bytes_per_clk=2048.0,
               lds_bytes_per_clk=128.0, lds_tr_bytes_per_clk=128.0, vmem_bytes_per_clk=64.0, mem_latency_clk=0.0,
               cache_eff_frac=0.5, launch_clk=0.0, wg_overhead_clk=0.0, epilogue_clk=0.0, reduce_launch_clk=0.0,
-              under_occ_frac=1.0, seg_eff_lo=1.0, l_mi_clk=[[32.0, 16.0], [64.0, 32.0]])
+              under_occ_frac=1.0, seg_eff_lo=1.0, overlap_frac=0.0, l_mi_clk=[[32.0, 16.0], [64.0, 32.0]])
     v = dict(block_m=256, block_n=256, block_k=64, waves_m=2, waves_n=2, mfma=32, stages=2, slab_clk=2048)
     o = sm.predict(hw, 0, 8192, 8192, 8192, v, 1)
     assert o["waves"] == 4 and o["active_cu"] == 256 and o["l_mt_ideal"] == 256 * 32.0 / 4
