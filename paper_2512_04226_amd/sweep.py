@@ -211,6 +211,8 @@ def shape_set(name):
         return [(n, n, n, g.GEMM_FP16) for n in (1024, 2048, 4096, 8192)] + [(4864, 4096, 4096, g.GEMM_FP16)]
     if name == "uniform128":    # the shape distribution and precision of the paper's Section V-A; --b-layout 1 for its layout
         return [(m, n, k, g.GEMM_FP16) for (m, n, k) in wl.uniform128_shapes()]
+    if name == "uniform128fp8":  # the same distribution (first 96 shapes) in fp8 e4m3
+        return [(m, n, k, g.GEMM_FP8_E4M3) for (m, n, k) in wl.uniform128_shapes()[:96]]
     raise SystemExit("unknown shape set " + name)
 
 
