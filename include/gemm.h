@@ -157,7 +157,7 @@ typedef struct gemm_prediction {
     double l_total;       /* Algorithm 9 with the tail reading, clocks */
     double total_us;
     int32_t bottleneck;
-    int32_t reserved;
+    int32_t occupancy;    /* workgroups of the variant the model takes to be resident on one CU (slots per CU in Algorithm 4) */
 } gemm_prediction;
 
 uint32_t gemm_abi_version(void);
@@ -301,6 +301,15 @@ int gemm_cfg_at_ex(int idx, int64_t M, int64_t N, int64_t K, int dtype, int b_la
 /* Model terms for a cfg (Algorithms 3-9), host only. */
 int gemm_predict(const gemm_cfg *cfg, gemm_prediction *out);
 
+/*
+ * Diagnostic (needs the GPU, not part of selection): the number of workgroups of compiled variant
+ * `variant` in [0, gemm_variant_count(dtype)) that the HIP runtime reports as resident on one CU
+ * (registers, LDS and wave slots of the actual code object) -- what gemm_prediction.occupancy
+ * estimates on the host.  Errors: GEMM_ERR_NULL, GEMM_ERR_DTYPE, GEMM_ERR_INDEX,
+ * GEMM_ERR_CFG_ILLEGAL (b_layout), GEMM_ERR_HIP.
+ */
+int gemm_variant_occupancy(int dtype, int variant, int b_layout, int *blocks_per_cu);
+
 /* Hardware descriptor: get a copy / replace it (process-wide; not thread-safe against
  * concurrent gemm_select).  gemm_hw_reset restores the MI355X defaults. */
 int gemm_hw_get(gemm_hw *out);
@@ -324,16 +333,49 @@ int gemm_hw_preset(int id, gemm_hw *out);
 
 /*
  * Calibration probes (Section I: the model's hardware rates come from micro-benchmarks).
- * Each runs two launches on hip_stream, times the second with HIP events, synchronises and
- * writes the measured rate.  scratch4: caller-owned device memory, at least 4 bytes.
- *   gemm_probe_mfma   register-resident MFMA loop for (dtype, mfma in {32, 16}) -> TFLOP/s on the
- *                     whole device; L_MI in clocks = flop per instruction * n_cu * simd_per_cu *
+ * Each launches its kernel on hip_stream at least twice, times the later launches with HIP events,
+ * synchronises and writes the measured rate.  scratch4: caller-owned device memory, at least 4 bytes.
+ *   gemm_probe_mfma   register-resident MFMA loop on constant operands for (dtype, mfma in {32, 16}),
+ *                     10 ms untimed then 10 ms timed (gemm_probe_mfma_ex with operands = 0) -> TFLOP/s
+ *                     on the whole device; L_MI in clocks = flop per instruction * n_cu * simd_per_cu *
  *                     clk_ghz / (TFLOP/s * 1e3).
  *   gemm_probe_stream streaming 128-bit reads of buf[0, bytes) (device memory, 16-byte aligned,
  *                     >= 1 MiB; use more than the 256 MiB MALL to measure HBM) -> GB/s.
  */
 int gemm_probe_mfma(int dtype, int mfma, void *scratch4, void *hip_stream, double *tflops_out);
 int gemm_probe_stream(const void *buf, size_t bytes, void *scratch4, void *hip_stream, double *gbps_out);
+/*
+ * Further probes, one per remaining measurable entry of the hardware descriptor (Section I; Section IV's
+ * H: the rates R_1, R_2, R_MEM and the latency L_lat of Algorithm 7, L_MI of Algorithm 3).  Same
+ * conventions: synchronous, self-timed, scratch4 = caller-owned device memory of at least 4 bytes.
+ *   gemm_probe_mfma_ex   the matrix-core ceiling on a workload's own operand statistics.  A wave keeps
+ *                        2 register sets of 2-4 column and 4 row fragments and accumulates their
+ *                        products in turn, as the GEMM kernel's k-steps do.  operands = 0: every
+ *                        element 1.0; operands = 1: per-lane different N(0,1) values (bf16), or N(0,1)
+ *                        scaled to a maximum of 448 (e4m3), so the datapath toggles as on the benchmark
+ *                        inputs.  Launches run untimed for about warm_ms, then timed for about
+ *                        timed_ms (each in (0, 1000]; warm_ms may be 0): the chip needs 15-20 ms of
+ *                        work after an idle gap to settle under its power limit.  -> TFLOP/s.
+ *   gemm_probe_read      `passes` (1 .. 4096) reads of buf[0, bytes) by one launch, every workgroup
+ *                        re-reading its own grid-strided share.  Which level serves the repeats follows
+ *                        from the size: up to about 2 MiB per L2 (16 MiB on 8 XCDs) the L2s, up to the
+ *                        MALL's capacity the MALL, beyond it HBM.  -> GB/s over all passes.
+ *   gemm_probe_lds       LDS fragment-read rate with `waves_per_cu` in {4, 8, 16} waves per CU reading
+ *                        conflict-free: kind 0 ds_read_b128, 1 ds_read_b64, 2 ds_read_b64_tr_b16,
+ *                        3 ds_read_b64_tr_b8.  -> GB/s over the whole device (divide by CUs and clock
+ *                        for bytes per clock and CU).
+ *   gemm_probe_latency   4096 dependent loads by one lane through buf[0, bytes) (device memory,
+ *                        128-byte aligned, >= 1 MiB; OVERWRITTEN with the chain), every hop on another
+ *                        128-byte line; the level that holds the chain follows from the size as for
+ *                        gemm_probe_read.  -> nanoseconds per load.
+ * Errors: GEMM_ERR_NULL, GEMM_ERR_DTYPE, GEMM_ERR_CFG_ILLEGAL (mfma, operands, kind, waves, times),
+ * GEMM_ERR_ALIGN (buffer too small or misaligned), GEMM_ERR_SHAPE (passes), GEMM_ERR_HIP.
+ */
+int gemm_probe_mfma_ex(int dtype, int mfma, int operands, double warm_ms, double timed_ms, void *scratch4,
+                       void *hip_stream, double *tflops_out);
+int gemm_probe_read(const void *buf, size_t bytes, int passes, void *scratch4, void *hip_stream, double *gbps_out);
+int gemm_probe_lds(int kind, int waves_per_cu, void *scratch4, void *hip_stream, double *gbps_out);
+int gemm_probe_latency(void *buf, size_t bytes, void *scratch4, void *hip_stream, double *ns_out);
 
 #ifdef __cplusplus
 }

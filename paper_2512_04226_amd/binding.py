@@ -83,7 +83,7 @@ class gemm_prediction(ctypes.Structure):
         "n_mi", "l_mt_ideal", "l_compute", "tiles", "waves", "active_cu", "f_m", "f_n", "h_l2", "h_mall", "l_issue", "l_lds",
         "l_l2", "l_mall", "l_hbm", "l_mem", "l_mem_tail", "l_prologue", "l_epilogue", "l_iter", "iters", "l_tile",
         "l_tile_tail", "l_reduce", "l_total", "total_us")] + [("bottleneck", ctypes.c_int32),
-                                                              ("reserved", ctypes.c_int32)]
+                                                              ("occupancy", ctypes.c_int32)]
 
 
 if not os.path.exists(LIB_PATH):
@@ -128,6 +128,61 @@ _lib.gemm_probe_mfma.restype = _int
 _lib.gemm_probe_mfma.argtypes = [_int, _int, _vp, _vp, ctypes.POINTER(ctypes.c_double)]
 _lib.gemm_probe_stream.restype = _int
 _lib.gemm_probe_stream.argtypes = [_vp, ctypes.c_size_t, _vp, _vp, ctypes.POINTER(ctypes.c_double)]
+
+
+_lib.gemm_variant_occupancy.restype = _int
+_lib.gemm_variant_occupancy.argtypes = [_int, _int, _int, ctypes.POINTER(_int)]
+
+
+def gemm_variant_occupancy(dtype, variant, b_layout=GEMM_B_ROW_MAJOR):
+    """Workgroups of a compiled variant the HIP runtime keeps resident on one CU (needs the GPU)."""
+    out = _int()
+    _check(_lib.gemm_variant_occupancy(dtype, variant, b_layout, ctypes.byref(out)), "gemm_variant_occupancy")
+    return out.value
+
+
+_lib.gemm_probe_mfma_ex.restype = _int
+_lib.gemm_probe_mfma_ex.argtypes = [_int, _int, _int, ctypes.c_double, ctypes.c_double, _vp, _vp,
+                                    ctypes.POINTER(ctypes.c_double)]
+_lib.gemm_probe_read.restype = _int
+_lib.gemm_probe_read.argtypes = [_vp, ctypes.c_size_t, _int, _vp, _vp, ctypes.POINTER(ctypes.c_double)]
+_lib.gemm_probe_lds.restype = _int
+_lib.gemm_probe_lds.argtypes = [_int, _int, _vp, _vp, ctypes.POINTER(ctypes.c_double)]
+_lib.gemm_probe_latency.restype = _int
+_lib.gemm_probe_latency.argtypes = [_vp, ctypes.c_size_t, _vp, _vp, ctypes.POINTER(ctypes.c_double)]
+
+
+def gemm_probe_mfma_ex(dtype, mfma, operands, scratch, warm_ms=30.0, timed_ms=20.0, stream=None):
+    """TFLOP/s of the MFMA loop on constant (operands=0) or workload-like (operands=1) register contents,
+    in the settled state."""
+    out = ctypes.c_double()
+    _check(_lib.gemm_probe_mfma_ex(dtype, mfma, operands, warm_ms, timed_ms, _ptr(scratch),
+                                   ctypes.c_void_p(_stream_handle(stream)), ctypes.byref(out)), "gemm_probe_mfma_ex")
+    return out.value
+
+
+def gemm_probe_read(buf, passes, scratch, stream=None):
+    """GB/s of `passes` reads of the whole tensor by one launch."""
+    out = ctypes.c_double()
+    _check(_lib.gemm_probe_read(_ptr(buf), buf.numel() * buf.element_size(), passes, _ptr(scratch),
+                                ctypes.c_void_p(_stream_handle(stream)), ctypes.byref(out)), "gemm_probe_read")
+    return out.value
+
+
+def gemm_probe_lds(kind, waves_per_cu, scratch, stream=None):
+    """Device-wide GB/s of LDS fragment reads (kind 0 b128, 1 b64, 2 tr_b16, 3 tr_b8)."""
+    out = ctypes.c_double()
+    _check(_lib.gemm_probe_lds(kind, waves_per_cu, _ptr(scratch), ctypes.c_void_p(_stream_handle(stream)),
+                               ctypes.byref(out)), "gemm_probe_lds")
+    return out.value
+
+
+def gemm_probe_latency(buf, scratch, stream=None):
+    """Nanoseconds per dependent load through the tensor (which is overwritten)."""
+    out = ctypes.c_double()
+    _check(_lib.gemm_probe_latency(_ptr(buf), buf.numel() * buf.element_size(), _ptr(scratch),
+                                   ctypes.c_void_p(_stream_handle(stream)), ctypes.byref(out)), "gemm_probe_latency")
+    return out.value
 
 
 def gemm_probe_mfma(dtype, mfma, scratch, stream=None):

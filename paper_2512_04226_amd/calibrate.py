@@ -1,7 +1,8 @@
 """Device calibration of the model's constants (a one-off, offline step; never run by
 gemm_select or gemm_run):
 
-  * L_MI of every matrix instruction and the HBM streaming rate, from the library's probes;
+  * L_MI of every matrix instruction, the MFMA ceiling on workload-like operands, the L2, MALL and HBM
+    read rates, the LDS fragment-read rates and the load latency, from the library's probes;
   * SLAB_CLK of every kernel variant: steady-state clocks per K slab of one tile on a full CU,
     from one large compute-bound problem per datatype (8192^3).
 
@@ -56,6 +57,9 @@ def table_rows():
 
 
 def measure_rates():
+    """Every entry of the hardware descriptor that the device itself can report, from the library's probes:
+    L_MI per matrix instruction, the MFMA ceiling on constant and on workload-like operands, the L2, MALL
+    and HBM read rates, the LDS fragment-read rates and the load latency at each level."""
     scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
     hw = g.gemm_hw_get()
     out = {}
@@ -66,8 +70,31 @@ def measure_rates():
             flop = 2.0 * mi * mi * k
             l_mi = flop * hw.n_cu * hw.simd_per_cu * hw.clk_ghz / (tf * 1e3)
             out[(name, mi)] = (tf, l_mi)
+            out[(name, mi, "settled")] = (g.gemm_probe_mfma_ex(dt, mi, 0, scratch), g.gemm_probe_mfma_ex(dt, mi, 1, scratch))
+    per_clk = 1.0 / hw.clk_ghz                                                # GB/s -> bytes per clock
     buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)     # 1 GiB > MALL
     out["hbm_gbps"] = g.gemm_probe_stream(buf, scratch)
+    # repeated reads: 16 MiB stays in the eight L2s (2 MiB each), 128 MiB in the MALL, 1 GiB in neither
+    out["l2_gbps"] = g.gemm_probe_read(buf[:16 << 20], 64, scratch)
+    out["mall_gbps"] = g.gemm_probe_read(buf[:128 << 20], 8, scratch)
+    out["hbm_repeat_gbps"] = g.gemm_probe_read(buf, 2, scratch)
+    for kind, name in enumerate(("lds_b128", "lds_b64", "lds_tr_b16", "lds_tr_b8")):
+        by_waves = {w: g.gemm_probe_lds(kind, w, scratch) for w in (4, 8, 16)}
+        for w, x in by_waves.items():
+            out["%s_%dwaves_gbps" % (name, w)] = x
+        out[name + "_gbps"] = max(by_waves.values())
+    out["lat_l2_ns"] = g.gemm_probe_latency(buf[:2 << 20], scratch)
+    out["lat_mall_ns"] = g.gemm_probe_latency(buf[:128 << 20], scratch)
+    out["lat_hbm_ns"] = g.gemm_probe_latency(buf, scratch)
+    out["gemm_hw"] = {
+        "hbm_bytes_per_clk": out["hbm_gbps"] * per_clk,
+        "mall_bytes_per_clk": out["mall_gbps"] * per_clk,
+        "l2_bytes_per_clk": out["l2_gbps"] * per_clk / hw.n_xcd,
+        "lds_bytes_per_clk": out["lds_b128_gbps"] * per_clk / hw.n_cu,
+        "lds_tr_bytes_per_clk": out["lds_tr_b16_gbps"] * per_clk / hw.n_cu,
+        "mem_latency_clk": out["lat_hbm_ns"] * hw.clk_ghz,
+        "l_mi_clk": [[out[("bf16", 32)][1], out[("bf16", 16)][1]], [out[("fp8", 32)][1], out[("fp8", 16)][1]]],
+    }
     return out
 
 
@@ -201,6 +228,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--n", type=int, default=8192)
     ap.add_argument("--skip-rates", action="store_true")
+    ap.add_argument("--rates-only", action="store_true", help="run the probes, print the descriptor fields, stop")
     ap.add_argument("--loop-forms", nargs="+", metavar="LIB",
                     help="compare builds of the library (one per forced K-loop form) instead of calibrating")
     args = ap.parse_args()
@@ -211,10 +239,20 @@ def main():
     if not args.skip_rates:
         r = measure_rates()
         for key, val in r.items():
-            if key == "hbm_gbps":
-                print("HBM streaming read: %.0f GB/s" % val)
+            if key == "gemm_hw":
+                print("gemm_hw fields from the probes (bytes per %.1f GHz clock):" % g.gemm_hw_get().clk_ghz)
+                for f, x in val.items():
+                    print("    %-22s %s" % (f, ("%.1f" % x) if not isinstance(x, list) else
+                                            "[[%.1f, %.1f], [%.1f, %.1f]]" % (x[0][0], x[0][1], x[1][0], x[1][1])))
+            elif isinstance(key, str):
+                print("%-18s %.1f" % (key, val))
+            elif len(key) == 3:
+                print("MFMA %s %dx%d settled: %.0f TFLOP/s on constant operands, %.0f on workload-like operands" % (
+                    key[0], key[1], key[1], val[0], val[1]))
             else:
                 print("MFMA %s %dx%d: %.0f TFLOP/s device-wide -> L_MI = %.1f clk" % (key[0], key[1], key[1], val[0], val[1]))
+        if args.rates_only:
+            return
     for dtype, name in ((g.GEMM_BF16, "BF16"), (g.GEMM_FP8_E4M3, "FP8")):
         print("// %s variants, SLAB_CLK measured on %d^3" % (name, args.n))
         rows = measure_slab_clk(dtype, args.n, 0)

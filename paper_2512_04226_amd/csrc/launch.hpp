@@ -5,9 +5,24 @@
 
 namespace g355 {
 typedef hipError_t (*LaunchFn)(const KernelArgs &, hipStream_t);
+typedef hipError_t (*OccupancyFn)(int *blocks_per_cu);
+struct VariantFns {
+    LaunchFn launch;
+    OccupancyFn occupancy;   // the runtime's resident-workgroups-per-CU figure for the instantiation
+};
 // (variant index inside the translation unit's list, storage of B: 0 row-major K x N, 1 K-contiguous N x K)
-LaunchFn kLaunchBf16_0(int, int), kLaunchBf16_1(int, int), kLaunchBf16_2(int, int), kLaunchBf16_3(int, int),
-    kLaunchFp8_0(int, int), kLaunchFp8_1(int, int), kLaunchFp16_0(int, int), kLaunchFp16_1(int, int),
-    kLaunchFp16_2(int, int), kLaunchFp16_3(int, int), kLaunchBf16_4(int, int),
-    kLaunchFp16_4(int, int), kLaunchBf16_5(int, int), kLaunchFp16_5(int, int);   // fp16 shares the bf16 variant lists
+const VariantFns &kLaunchBf16_0(int, int),
+    &kLaunchBf16_1(int, int),
+    &kLaunchBf16_2(int, int),
+    &kLaunchBf16_3(int, int),
+    &kLaunchFp8_0(int, int),
+    &kLaunchFp8_1(int, int),
+    &kLaunchFp16_0(int, int),
+    &kLaunchFp16_1(int, int),
+    &kLaunchFp16_2(int, int),
+    &kLaunchFp16_3(int, int),
+    &kLaunchBf16_4(int, int),
+    &kLaunchFp16_4(int, int),
+    &kLaunchBf16_5(int, int),
+    &kLaunchFp16_5(int, int);   // fp16 shares the bf16 variant lists
 }  // namespace g355

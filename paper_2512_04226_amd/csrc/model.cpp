@@ -326,6 +326,7 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
     p->tiles = tiles;
     p->waves = waves;
     p->active_cu = active;
+    p->occupancy = occ;
 
     // Algorithms 5/6: L2 scope = CUs of one XCD (times resident workgroups), MALL scope = device.
     const int l2_scope = hw.n_cu / hw.n_xcd * occ;

@@ -118,7 +118,7 @@ struct Workspace {
 };
 Workspace g_ws[kMaxDevices];
 
-LaunchFn launcher_of(int dtype, int id, int bl)
+const VariantFns &launcher_of(int dtype, int id, int bl)
 {
 #define G355_COUNT(...) +1
     constexpr int n_b0 = 0 G355_VARIANTS_BF16_0(G355_COUNT);
@@ -282,7 +282,7 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
 
     hipStream_t stream = (hipStream_t)hip_stream;
     const int f16 = (dtype == GEMM_FP16) ? 1 : 0;
-    if (launcher_of(dtype, cfg->kernel_id, cfg->b_layout)(a, stream) != hipSuccess) {
+    if (launcher_of(dtype, cfg->kernel_id, cfg->b_layout).launch(a, stream) != hipSuccess) {
         (void)hipGetLastError();
         return GEMM_ERR_HIP;
     }
@@ -316,6 +316,24 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
                            a.N, a.ldc, a.split_k, a.alpha, a.beta, f16, a.stride_c);
         if (hipGetLastError() != hipSuccess)
             return GEMM_ERR_HIP;
+    }
+    return GEMM_OK;
+}
+
+extern "C" int gemm_variant_occupancy(int dtype, int variant, int b_layout, int *blocks_per_cu)
+{
+    if (!blocks_per_cu)
+        return GEMM_ERR_NULL;
+    if (dtype != GEMM_BF16 && dtype != GEMM_FP8_E4M3 && dtype != GEMM_FP16)
+        return GEMM_ERR_DTYPE;
+    if (variant < 0 || variant >= variant_count(dtype))
+        return GEMM_ERR_INDEX;
+    if (b_layout != GEMM_B_ROW_MAJOR && b_layout != GEMM_B_K_CONTIGUOUS)
+        return GEMM_ERR_CFG_ILLEGAL;
+    (void)hipGetLastError();
+    if (launcher_of(dtype, variant, b_layout).occupancy(blocks_per_cu) != hipSuccess) {
+        (void)hipGetLastError();
+        return GEMM_ERR_HIP;
     }
     return GEMM_OK;
 }
@@ -362,7 +380,7 @@ extern "C" int gemm_run_grouped(const gemm_cfg *cfg, int n_groups, const gemm_gr
     a.batch = 1;
     a.groups = (const GroupRec *)dev_table;
     a.n_groups = n_groups;
-    if (launcher_of(cfg->dtype, cfg->kernel_id, cfg->b_layout)(a, (hipStream_t)hip_stream) != hipSuccess) {
+    if (launcher_of(cfg->dtype, cfg->kernel_id, cfg->b_layout).launch(a, (hipStream_t)hip_stream) != hipSuccess) {
         (void)hipGetLastError();
         return GEMM_ERR_HIP;
     }
