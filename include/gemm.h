@@ -253,6 +253,22 @@ int gemm_run_grouped(const gemm_cfg *cfg, int n_groups, const gemm_group_rec *ho
  */
 int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void *C, void *hip_stream);
 
+/*
+ * gemm_run for callers that cannot allocate or register device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same launch, but split-K slabs and Stream-K
+ * partial tiles go to a buffer of GEMM_NOALLOC_WORKSPACE_BYTES that is part of the library's code object
+ * (one copy per GPU, held from module load until the process ends) instead of the registered workspace.
+ * Calls no hipMalloc / hipFree and no allocating routine; the registered workspace is neither used nor
+ * changed.  A cfg whose gemm_workspace_bytes exceeds GEMM_NOALLOC_WORKSPACE_BYTES returns
+ * GEMM_ERR_WORKSPACE and launches nothing (cfgs with split_k = 1 and stream_k = 0 need no workspace and
+ * always fit).  Every call on a GPU shares that GPU's buffer: the kernels overwrite what they later
+ * read, so nothing has to be cleared between calls, but two calls in flight at once on one GPU (different
+ * streams, or a captured graph replayed concurrently) race on it -- order them.  Other arguments and
+ * errors as for gemm_run.
+ */
+#define GEMM_NOALLOC_WORKSPACE_BYTES (64u << 20)
+int gemm_run_noalloc(const gemm_cfg *cfg, const void *A, const void *B, void *C, void *hip_stream);
+
 /* fp32 partial sums: batch * split_k * M * N * 4 bytes when split_k > 1; 2 * sk_workers * block_m *
  * block_n * 4 bytes (two partial tiles per stream-K workgroup) when stream_k = 1; else 0. */
 size_t gemm_workspace_bytes(const gemm_cfg *cfg);

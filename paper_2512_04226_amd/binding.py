@@ -104,6 +104,9 @@ _lib.gemm_cfg_at_ex.restype = _int
 _lib.gemm_cfg_at_ex.argtypes = [_int, _i64, _i64, _i64, _int, _int, ctypes.POINTER(gemm_cfg)]
 _lib.gemm_run.restype = _int
 _lib.gemm_run.argtypes = [ctypes.POINTER(gemm_cfg), _vp, _vp, _vp, _vp]
+_lib.gemm_run_noalloc.restype = _int
+_lib.gemm_run_noalloc.argtypes = [ctypes.POINTER(gemm_cfg), _vp, _vp, _vp, _vp]
+GEMM_NOALLOC_WORKSPACE_BYTES = 64 << 20
 _lib.gemm_workspace_bytes.restype = ctypes.c_size_t
 _lib.gemm_workspace_bytes.argtypes = [ctypes.POINTER(gemm_cfg)]
 _lib.gemm_set_workspace.restype = _int
@@ -369,6 +372,12 @@ def gemm_run(cfg, A, B, C, stream=None):
     None for torch's current stream."""
     _check(_lib.gemm_run(ctypes.byref(cfg), _ptr(A), _ptr(B), _ptr(C), ctypes.c_void_p(_stream_handle(stream))),
            "gemm_run")
+
+
+def gemm_run_noalloc(cfg, A, B, C, stream=None):
+    """gemm_run with the library's own built-in workspace (at most GEMM_NOALLOC_WORKSPACE_BYTES); allocates nothing."""
+    _check(_lib.gemm_run_noalloc(ctypes.byref(cfg), _ptr(A), _ptr(B), _ptr(C), ctypes.c_void_p(_stream_handle(stream))),
+           "gemm_run_noalloc")
 
 
 class gemm_problem(ctypes.Structure):

@@ -3,6 +3,7 @@
 
 #include <cstddef>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/gemm.h"
 #include "gemm_kernel.hpp"
@@ -110,13 +111,44 @@ __global__ __launch_bounds__(256) void streamk_sum_kernel(const float *__restric
 
 }  // namespace g355
 
+// Workspace of gemm_run_noalloc: device memory that belongs to the code object, one copy per GPU, from
+// module load to process end.  In host code this name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[GEMM_NOALLOC_WORKSPACE_BYTES];
+
 namespace {
 constexpr int kMaxDevices = 16;
 struct Workspace {
     void *ptr;
     size_t bytes;
 };
+// Registered by gemm_set_workspace, read by gemm_run: plain process-wide state, one entry per device.
+// Callers that register and run from several threads order those calls themselves.
 Workspace g_ws[kMaxDevices];
+
+// Device address of `scratch` on each GPU (every GPU holds its own copy at its own address),
+// looked up on the first gemm_run_noalloc call with that device current.
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];
+
+int scratch_of_current_device(void **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return GEMM_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return GEMM_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return GEMM_OK;
+}
 
 const VariantFns &launcher_of(int dtype, int id, int bl)
 {
@@ -178,7 +210,10 @@ extern "C" int gemm_set_workspace(void *dev_ptr, size_t bytes)
     return GEMM_OK;
 }
 
-extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void *C, void *hip_stream)
+// The body of gemm_run and gemm_run_noalloc.  own_ws: nullptr = the workspace registered for the
+// current device, else the buffer of own_ws_bytes bytes to use instead.
+static int run_impl(const gemm_cfg *cfg, const void *A, const void *B, void *C, void *hip_stream, void *own_ws,
+                    size_t own_ws_bytes)
 {
     if (!cfg || !A || !B || !C)
         return GEMM_ERR_NULL;
@@ -241,7 +276,11 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
         return GEMM_ERR_SHAPE;
 
     float *ws = nullptr;
-    if (cfg->split_k > 1 || cfg->stream_k) {
+    if ((cfg->split_k > 1 || cfg->stream_k) && own_ws) {
+        if (own_ws_bytes < gemm_workspace_bytes(cfg))
+            return GEMM_ERR_WORKSPACE;
+        ws = (float *)own_ws;
+    } else if (cfg->split_k > 1 || cfg->stream_k) {
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
             (void)hipGetLastError();
@@ -318,6 +357,25 @@ extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void 
             return GEMM_ERR_HIP;
     }
     return GEMM_OK;
+}
+
+extern "C" int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void *C, void *hip_stream)
+{
+    return run_impl(cfg, A, B, C, hip_stream, nullptr, 0);
+}
+
+extern "C" int gemm_run_noalloc(const gemm_cfg *cfg, const void *A, const void *B, void *C, void *hip_stream)
+{
+    if (!cfg)
+        return GEMM_ERR_NULL;
+    // sizes beyond the built-in buffer are refused before anything else is looked at
+    if (gemm_workspace_bytes(cfg) > (size_t)GEMM_NOALLOC_WORKSPACE_BYTES)
+        return GEMM_ERR_WORKSPACE;
+    void *ws = nullptr;
+    const int rc = scratch_of_current_device(&ws);
+    if (rc)
+        return rc;
+    return run_impl(cfg, A, B, C, hip_stream, ws, (size_t)GEMM_NOALLOC_WORKSPACE_BYTES);
 }
 
 extern "C" int gemm_variant_occupancy(int dtype, int variant, int b_layout, int *blocks_per_cu)
