@@ -30,7 +30,7 @@
 extern "C" {
 #endif
 
-#define GEMM_ABI_VERSION 7u
+#define GEMM_ABI_VERSION 8u
 
 typedef enum gemm_dtype {
     GEMM_BF16 = 0,     /* A, B bf16; C bf16 */
@@ -99,7 +99,11 @@ typedef struct gemm_hw {
     double seg_eff_lo;         /* share of the HBM rate reached with 32-byte row segments (1 from 256 bytes up) */
     double overlap_frac;       /* with two or more workgroups resident per CU: share of a tile's prologue and store stage
                                   that hides under the other workgroups' K loops in every wave but the last (0 .. 1) */
-    double l_mi_clk[2][2];     /* issue interval L_MI of one MFMA: [dtype][0: 32x32, 1: 16x16] */
+    double l_mi_clk[2][2];     /* issue interval L_MI of one MFMA on workload-like operands (the chip is power-limited):
+                                  [0: 16-bit, 1: fp8][0: 32x32, 1: 16x16], in clk_ghz clocks */
+    double fill_issue_bytes_per_clk; /* bytes of a slab's direct-to-LDS fill the waves of a CU issue per clock, taken
+                                  out of their MFMA streams (added to Algorithm 3's latency, not overlapped) */
+    double slab_sync_clk;      /* barrier and first-fragment wait of one K slab, clocks */
 } gemm_hw;
 
 /*
@@ -121,7 +125,7 @@ typedef struct gemm_cfg {
     uint16_t group_n;         /* cache-tile width f_n = CUs per L2 / f_m (informational) */
     uint8_t xcd_remap;        /* 1: workgroup ids are renumbered so that each XCD owns a contiguous id range */
     uint8_t stages;           /* LDS ring depth: K_T slabs resident or in flight per workgroup */
-    uint16_t slab_clk;        /* the variant's calibrated cost: clocks per K_T slab of one tile on a full CU */
+    uint16_t reserved1;       /* 0 */
     uint8_t b_layout;         /* gemm_b_layout */
     uint8_t stream_k;         /* 1: the last partial wave of tiles is split along K over sk_workers workgroups (needs split_k = 1) */
     uint16_t sk_workers;      /* stream-K workgroups G (= workgroup slots of the device for this variant); 0 when stream_k = 0 */
@@ -139,8 +143,9 @@ typedef struct gemm_cfg {
 /* Terms of the model for one cfg (clocks unless said otherwise), for tests and reports. */
 typedef struct gemm_prediction {
     double n_mi;          /* Algorithm 3: matrix instructions per workgroup tile and K slab */
-    double l_mt_ideal;    /* Algorithm 3: L_MI * N_MI spread over the workgroup's SIMDs (full utilisation) */
-    double l_compute;     /* compute latency used: the variant's measured clocks per K slab, times resident tiles */
+    double l_mt_ideal;    /* Algorithm 3: L_MT = L_MI * N_MI, spread over the SIMDs the workgroup's waves occupy */
+    double l_compute;     /* compute latency of one K step of the tiles resident on a CU: (L_MT + fill bytes /
+                             fill_issue_bytes_per_clk + slab_sync_clk) per tile, times the resident tiles */
     double tiles;         /* Algorithm 4: output tiles x split_k */
     double waves;         /* Algorithm 4: omega */
     double active_cu;     /* Algorithm 4: CUs busy in the last wave */

@@ -1,325 +1,353 @@
-"""Plain transcription of the paper's analytical model (TEST INFRASTRUCTURE ONLY).
+"""Checker for the analytical selector (TEST INFRASTRUCTURE ONLY: nothing under the product package
+imports this module, and it shares no code, table or constant with it).
 
-Section IV of the paper: Algorithm 3 (compute latency of a shared-memory tile), Algorithm 4
-(active CUs in the last timestep, number of waves), Algorithm 5 (cache hit rate of a cache
-tile), Algorithm 6 (factorisations of the CU count of a cache scope), Algorithm 7 (memory
-latency of one loop iteration), Algorithm 8 (latency of one output tile) and Algorithm 9
-(total latency).  The `alg*` functions take the steps in the paper's order and notation,
-with no reading added.  `predict` composes them for one kernel variant the way the shipped
-selector is specified to (every place where the paper is silent or inconsistent is marked
-READING); the tests compare the C++ selector's terms with it.
+Two layers.
 
-Shares no code with the product; nothing under the product package imports this module.
-The selector's final pick is a heuristic ranked empirically against a sweep, so beyond the
-structural pins in tests/test_selector_model.py its parity is unpinned by the paper.
+1. The paper's Section IV as printed, one small function per algorithm (`alg3_...` to `alg9_...`):
+   instruction count and latency of a workgroup tile (Algorithm 3), output tiles / waves / remainder
+   (Algorithm 4), cache-tile hit rate (Algorithm 5), factor pairs of a CU count (Algorithm 6), memory
+   latency of one loop iteration as a maximum over the levels of the hierarchy (Algorithm 7), latency of
+   one output tile (Algorithm 8) and of the whole product (Algorithm 9).  They are pinned to the values
+   and closed forms the paper fixes (tests/test_selector_model.py, tests/golden/paper_worked_examples.txt).
+
+2. The model the library is specified to evaluate: the same algorithms with the readings that fill in what
+   the paper leaves open.  Every reading is a function of its own with the reading stated in its docstring
+   (`resident_workgroups`, `wave_split`, `cache_tile`, `derate`, `segment_efficiency`, `slab_compute`,
+   `level_times`, `tile_time`, `split_k_reduce`, `stream_k_phase`, `stream_k_sum`), `predict` and
+   `predict_grouped` put them together.  Each is pinned to hand-worked examples whose arithmetic is written
+   out in tests/golden/model_worked_examples.json; the library is checked against the same literal numbers
+   separately, so neither side is the other's reference.
+
+Units: bytes and compute clocks.  `hw` is a dict with the fields of the hardware descriptor; a variant `v`
+is a dict with block_m, block_n, block_k, waves_m, waves_n, mfma (32 or 16) and stages.
 """
 import math
 
+# ------------------------------------------------------------------ Section IV as printed
 
-# ---------------------------------------------------------------- the paper's algorithms
 
 def alg3_compute_latency(mi_m, mi_n, mi_k, mt_m, mt_n, mt_k, l_mi):
-    """Algorithm 3: matrix instructions per shared-memory tile and their latency."""
-    n_mi_m = math.ceil(mt_m / mi_m)
-    n_mi_n = math.ceil(mt_n / mi_n)
-    n_mi_k = math.ceil(mt_k / mi_k)
-    n_mi = n_mi_m * n_mi_n * n_mi_k
-    l_mt = l_mi * n_mi
-    return n_mi, l_mt
+    """Algorithm 3.  A workgroup tile is covered by whole matrix instructions along each of its three
+    extents; its latency is the instruction count times one instruction's latency.  -> (N_MI, L_MT)"""
+    count = 1
+    for extent, step in ((mt_m, mi_m), (mt_n, mi_n), (mt_k, mi_k)):
+        count *= -(-extent // step)
+    return count, count * l_mi
 
 
 def alg4_occupancy(M, N, mt_m, mt_n, n_cu):
-    """Algorithm 4 as printed: (active_cu, omega, T_out); active_cu is T_out mod N_CU."""
-    n_mt_m = math.ceil(M / mt_m)
-    n_mt_n = math.ceil(N / mt_n)
-    t_out = n_mt_m * n_mt_n
-    omega = math.ceil(t_out / n_cu)
-    active_cu = t_out % n_cu
-    return active_cu, omega, t_out
+    """Algorithm 4 exactly as printed: (T_out mod N_CU, waves, T_out).  The remainder is 0 when the last
+    wave is full -- also in the paper's own one-tile-per-CU example."""
+    t_out = (-(-M // mt_m)) * (-(-N // mt_n))
+    return t_out % n_cu, -(-t_out // n_cu), t_out
 
 
 def alg5_hit_rate(m_t, n_t, M_T, N_T, K_T):
-    """Algorithm 5: hit rate of an m_t x n_t cache tile of M_T x N_T x K_T workgroup tiles."""
-    U = (m_t * M_T + n_t * N_T) * K_T          # uncached reads
-    R = (m_t * n_t) * (M_T + N_T) * K_T        # total reads
-    h = 1 - U / R
-    return h
+    """Algorithm 5.  An m_t x n_t block of workgroup tiles requests m_t*n_t*(M_T + N_T)*K_T operand
+    elements per K step, of which only the m_t row panels and n_t column panels are distinct."""
+    distinct = (m_t * M_T + n_t * N_T) * K_T
+    requested = m_t * n_t * (M_T + N_T) * K_T
+    return 1 - distinct / requested
 
 
 def alg6_factorizations(n_cu_cache):
-    """Algorithm 6: every (f_m, f_n) with f_m * f_n = N_CU_cache, in ascending f_m."""
-    F = []
-    for i in range(1, n_cu_cache + 1):
-        if n_cu_cache % i == 0:
-            F.append((i, n_cu_cache // i))
-    return F
+    """Algorithm 6: the ordered pairs (f_m, f_n) with f_m * f_n = N_CU_cache, ascending f_m."""
+    return [(d, n_cu_cache // d) for d in range(1, n_cu_cache + 1) if n_cu_cache % d == 0]
 
 
 def alg7_memory_latency(ld_cu, C, H1, H2, R_L1, R_1, R_2, R_MEM, L_lat):
-    """Algorithm 7 as printed (any consistent unit of data per cycle)."""
-    L_cu_lat = ld_cu / R_L1
-    T = ld_cu * C
-    L_1 = T / R_1
-    T_2 = (1 - H1) * T
-    L_2 = T_2 / R_2
-    T_M = (1 - H2) * T_2
-    L_MEM = T_M / R_MEM + L_lat
-    return max(L_cu_lat, L_1, L_2, L_MEM)
+    """Algorithm 7 as printed.  Every CU issues its own loads at R_L1; all C CUs' traffic goes through
+    the first shared level at R_1; what misses it (1 - H1) goes through the second at R_2; what misses
+    that too (1 - H2 of the rest) comes from memory at R_MEM after a latency L_lat.  The slowest of
+    these is the iteration's memory latency."""
+    everything = ld_cu * C
+    past_first = (1 - H1) * everything
+    past_second = (1 - H2) * past_first
+    return max(ld_cu / R_L1, everything / R_1, past_first / R_2, past_second / R_MEM + L_lat)
 
 
 def alg8_tile_latency(K, k_t, l_mem, l_compute, a, m_t, n_t, R_mem):
-    """Algorithm 8 as printed."""
-    l_prologue = l_mem
-    l_epilogue = a * m_t * n_t / R_mem
-    l_loopiter = max(l_compute, l_mem)
-    I = math.ceil(K / k_t) - 1
-    return l_prologue + l_epilogue + l_loopiter * I
+    """Algorithm 8 as printed: one load (prologue), a store of a * m_t * n_t output elements (epilogue),
+    and ceil(K / k_t) - 1 iterations in which loading and computing overlap."""
+    iterations = -(-K // k_t) - 1
+    return l_mem + a * m_t * n_t / R_mem + iterations * max(l_compute, l_mem)
 
 
 def alg9_total_latency(M, N, m_t, n_t, n_cu, l_tile):
-    """Algorithm 9 as printed."""
-    n_m = math.ceil(M / m_t)
-    n_n = math.ceil(N / n_t)
-    n_waves = math.ceil(n_m * n_n / n_cu)
-    return n_waves * l_tile
+    """Algorithm 9 as printed: waves of N_CU output tiles, each as long as one tile."""
+    return alg4_occupancy(M, N, m_t, n_t, n_cu)[1] * l_tile
 
 
-# ---------------------------------------------------------------- composition with readings
-
-def _ceil_div(a, b):
-    return -(-a // b)
+# ------------------------------------------------------------------ the readings, one function each
 
 
-def occupancy(hw, v, es):
-    """READING: workgroups of variant v resident on one CU (LDS ring, register estimate, 8 at most)."""
-    lds = v["stages"] * (v["block_m"] + v["block_n"]) * v["block_k"] * es
-    waves = v["waves_m"] * v["waves_n"]
-    acc = v["block_m"] * v["block_n"] / (waves * 64.0)      # fp32 accumulators per lane
-    vgpr = acc + 64.0
-    waves_per_simd = max(1, min(8, int(512.0 // vgpr)))
-    by_regs = max(1, waves_per_simd * hw["simd_per_cu"] // waves)
-    by_lds = max(1, int(hw["lds_bytes"] // lds))
-    return max(1, min(by_regs, by_lds, 8))
+def _elem_bytes(dtype):
+    return 1 if dtype == 1 else 2          # dtype 0 bf16, 1 fp8 e4m3, 2 fp16
 
 
-def choose_cache_tile(scope, v, tiles_m, tiles_n):
-    """READING: among Algorithm 6's pairs, clipped to the tile grid, the one with the highest
-    Algorithm-5 hit rate; ties -> cache tile closest to square in elements -> wider."""
-    best = None
-    for (i, j) in alg6_factorizations(scope):
-        fm, fn = min(i, tiles_m), min(j, tiles_n)
-        h = min(1.0, max(0.0, alg5_hit_rate(fm, fn, v["block_m"], v["block_n"], v["block_k"])))
-        skew = abs(fm * v["block_m"] - fn * v["block_n"])
-        better = False
-        if best is None or h > best["h"] + 1e-12:
-            better = True
-        elif abs(h - best["h"]) <= 1e-12:
-            if skew < best["skew"] - 1e-9:
-                better = True
-            elif abs(skew - best["skew"]) <= 1e-9 and fn > best["fn"]:
-                better = True
-        if better:
-            best = {"h": h, "skew": skew, "fm": fm, "fn": fn, "raw": i}
-    return best
+def _mfma_k(dtype, mfma):
+    """K extent of the matrix instruction: 16-bit 32x32x16 / 16x16x32, fp8 32x32x64 / 16x16x128."""
+    return (64 if mfma == 32 else 128) if dtype == 1 else (16 if mfma == 32 else 32)
+
+
+def resident_workgroups(hw, v, es):
+    """READING (not in the paper, which has one workgroup per CU): several workgroups of a small variant
+    share a CU.  How many: what fits the LDS (the ring of `stages` slabs), what fits the 512 registers a
+    SIMD lane offers its waves (fp32 accumulators of the tile spread over the lanes, plus 64 for fragments
+    and addresses; at most 8 waves per SIMD), never more than 8 and never fewer than 1."""
+    ring = v["stages"] * (v["block_m"] + v["block_n"]) * v["block_k"] * es
+    waves_per_wg = v["waves_m"] * v["waves_n"]
+    regs_per_lane = v["block_m"] * v["block_n"] / (64.0 * waves_per_wg) + 64.0
+    waves_per_simd = min(8, max(1, int(512.0 // regs_per_lane)))
+    fit_regs = waves_per_simd * hw["simd_per_cu"] // waves_per_wg
+    fit_lds = int(hw["lds_bytes"] // ring)
+    return max(1, min(fit_regs, fit_lds, 8))
+
+
+occupancy = resident_workgroups
+
+
+def wave_split(tiles, n_cu, occ):
+    """READING of Algorithm 4: a wave is n_cu * occ workgroup slots; the last wave holds what is left, and a
+    remainder of zero means a FULL last wave (the printed modulo would make it empty).  In the last wave
+    the tiles spread over as many CUs as there are tiles (at most all), ceil(tail / n_cu) to a CU.
+    -> (waves, tail tiles, active CUs, tiles per CU in the tail)"""
+    slots = n_cu * occ
+    waves = -(-tiles // slots)
+    tail = tiles - (waves - 1) * slots
+    return waves, tail, min(tail, n_cu), -(-tail // n_cu)
+
+
+def cache_tile(scope, v, tiles_m, tiles_n):
+    """READING of Algorithm 6's choice (its floor(sqrt(N)) default is not a divisor of 32): of all factor
+    pairs of the scope's workgroup count, each clipped to the tile grid, the one with the highest
+    Algorithm-5 hit rate for this variant's nominal tile; between equal rates the cache tile closer to
+    square in elements, then the wider one, else the earlier pair.  -> (f_m, f_n, unclipped f_m)"""
+    ranked = []
+    for order, (i, j) in enumerate(alg6_factorizations(scope)):
+        f_m, f_n = min(i, tiles_m), min(j, tiles_n)
+        rate = min(1.0, max(0.0, alg5_hit_rate(f_m, f_n, v["block_m"], v["block_n"], v["block_k"])))
+        ranked.append((rate, -abs(f_m * v["block_m"] - f_n * v["block_n"]), f_n, -order, f_m, i))
+    # exact ties are ties here: the candidates' rates and skews are small rationals
+    top = max(ranked, key=lambda c: (round(c[0], 12), round(c[1], 9), c[2], c[3]))
+    return top[4], top[2], top[5]
+
+
+def derate(hit, f_m, f_n, v, es, capacity, usable_share):
+    """READING of Section IV-C's capacity remark (no formula given): the cache tile's working set of one K
+    step, two slabs deep, against the usable share of the cache; beyond it the hit rate shrinks in
+    proportion."""
+    working_set = (f_m * v["block_m"] + f_n * v["block_n"]) * v["block_k"] * es * 2.0
+    return hit * min(1.0, usable_share * capacity / working_set)
 
 
 def segment_efficiency(hw, seg):
-    """READING: share of the HBM rate reached with `seg` contiguous bytes per matrix row."""
+    """READING (not in the paper): share of the HBM rate reached when a tile touches `seg` contiguous bytes
+    of each matrix row: all of it from 256 bytes up, seg_eff_lo at 32 bytes and below, linear in log2 between."""
     if seg >= 256:
         return 1.0
-    s = max(seg, 32.0)
-    return min(1.0, hw["seg_eff_lo"] + (1.0 - hw["seg_eff_lo"]) * math.log2(s / 32.0) / 3.0)
+    octaves = math.log2(max(seg, 32.0) / 32.0)          # 0 .. 3
+    return min(1.0, hw["seg_eff_lo"] + (1.0 - hw["seg_eff_lo"]) * octaves / 3.0)
+
+
+def slab_compute(hw, v, dtype):
+    """READING of Algorithm 3's use in Algorithm 8.  (N_MI, L_MT spread over the SIMDs the workgroup's
+    waves occupy, compute latency of one K slab of one tile).  The last is L_MT plus what the slab's fill and
+    its barrier take out of the waves' instruction streams: the (BM + BN) * BK bytes of the slab are loaded
+    by the same waves, in order with their matrix instructions, at fill_issue_bytes_per_clk, and every slab
+    ends in one synchronisation of slab_sync_clk.  L_MI is the issue interval the chip sustains on
+    workload-like operands (it is power-limited), one per instruction shape."""
+    es = _elem_bytes(dtype)
+    row = 1 if dtype == 1 else 0                          # fp16 runs at bf16's rates
+    l_mi = hw["l_mi_clk"][row][0 if v["mfma"] == 32 else 1]
+    n_mi, l_mt = alg3_compute_latency(v["mfma"], v["mfma"], _mfma_k(dtype, v["mfma"]),
+                                      v["block_m"], v["block_n"], v["block_k"], l_mi)
+    l_mt_spread = l_mt / min(hw["simd_per_cu"], v["waves_m"] * v["waves_n"])
+    fill = (v["block_m"] + v["block_n"]) * v["block_k"] * es
+    return n_mi, l_mt_spread, l_mt_spread + fill / hw["fill_issue_bytes_per_clk"] + hw["slab_sync_clk"]
+
+
+def level_times(hw, v, es, b_layout, tiles_per_cu, active_cus, h_first, h_second, rows_valid, cols_valid,
+                tiles_per_cu_moving=None, hbm_share="neither"):
+    """Algorithm 7 in bytes and clocks for one K step, with these READINGS:
+    * Ld_CU (undefined in the paper) is the slab of every tile a CU works on: the load INSTRUCTIONS cover the
+      nominal (BM + BN) * BK elements, the BYTES that move only the valid rows and columns of the tile
+      (`rows_valid` x `cols_valid`, the mean over the tile grid) of `tiles_per_cu_moving` tiles;
+    * first shared level = the L2 of one XCD (traffic divides over the XCDs that have work), second = MALL;
+    * an LDS term joins the maximum (Section IV-D lists the bound, Algorithm 7 omits it): every wave reads its
+      rows of A and its columns of B from LDS, so A's slab is read waves_n times and B's waves_m times, B at
+      the transpose-read rate unless it is stored K-contiguous;
+    * the share of requested bytes that reaches HBM is what NEITHER cache holds, min(1 - H1, 1 - H2), because
+      the two rates come from nested scopes (hbm_share="product" gives the printed (1 - H1)(1 - H2));
+    * each operand's HBM bytes are divided by its row-segment efficiency;
+    * the latency is shared by the slabs in flight: L_lat / max(1, tiles_per_cu * (stages - 1)).
+    -> dict of the five terms and their maximum."""
+    moving = tiles_per_cu if tiles_per_cu_moving is None else tiles_per_cu_moving
+    slab_k_bytes = v["block_k"] * es
+    issue = (v["block_m"] + v["block_n"]) * slab_k_bytes * tiles_per_cu / hw["vmem_bytes_per_clk"]
+    a_moved = rows_valid * slab_k_bytes * moving
+    b_moved = cols_valid * slab_k_bytes * moving
+    b_read_rate = hw["lds_bytes_per_clk"] if b_layout else hw["lds_tr_bytes_per_clk"]
+    lds = tiles_per_cu * (v["block_m"] * v["waves_n"] * slab_k_bytes / hw["lds_bytes_per_clk"]
+                          + v["block_n"] * v["waves_m"] * slab_k_bytes / b_read_rate)
+    device_bytes = (a_moved + b_moved) * active_cus
+    l2 = device_bytes / min(hw["n_xcd"], max(1.0, active_cus)) / hw["l2_bytes_per_clk"]
+    mall = (1.0 - h_first) * device_bytes / hw["mall_bytes_per_clk"]
+    if hbm_share == "product":
+        miss_both = (1.0 - h_first) * (1.0 - h_second)
+    else:
+        miss_both = min(1.0 - h_first, 1.0 - h_second)
+    seg_a = segment_efficiency(hw, slab_k_bytes)
+    seg_b = segment_efficiency(hw, (v["block_k"] if b_layout else v["block_n"]) * es)
+    hbm = (miss_both * (a_moved / seg_a + b_moved / seg_b) * active_cus / hw["hbm_bytes_per_clk"]
+           + hw["mem_latency_clk"] / max(1.0, tiles_per_cu * (v["stages"] - 1)))
+    return {"l_issue": issue, "l_lds": lds, "l_l2": l2, "l_mall": mall, "l_hbm": hbm,
+            "l_mem": max(issue, lds, l2, mall, hbm)}
+
+
+def tile_time(hw, v, slab_cost, occ, tiles_per_cu, active_cus, slabs, out_bytes, mem):
+    """Algorithm 8 with these READINGS: the compute latency of a K step is `slab_cost` per resident tile (a
+    CU that holds fewer tiles than fit runs each a little faster: factor u + (1 - u) * held / fit with
+    u = under_occ_frac); the prologue also pays the full memory latency and a per-workgroup cost; the
+    epilogue moves the output bytes of all active tiles through the HBM rate plus a fixed cost; the last
+    slab's compute is exposed (Algorithm 8 stops at ceil(K / k_t) - 1 iterations and never computes it)."""
+    compute = slab_cost * tiles_per_cu
+    if tiles_per_cu < occ:
+        compute *= hw["under_occ_frac"] + (1.0 - hw["under_occ_frac"]) * tiles_per_cu / occ
+    prologue = mem["l_mem"] + hw["mem_latency_clk"] + hw["wg_overhead_clk"]
+    epilogue = (active_cus * tiles_per_cu * v["block_m"] * v["block_n"] * out_bytes / hw["hbm_bytes_per_clk"]
+                + hw["epilogue_clk"])
+    iteration = max(compute, mem["l_mem"])
+    return {"l_compute": compute, "l_prologue": prologue, "l_epilogue": epilogue, "l_iter": iteration,
+            "l_tile": prologue + epilogue + iteration * (slabs - 1) + compute}
+
+
+def split_k_reduce(hw, M, N, split_k, batch=1):
+    """READING of Section IV-D's "unroll the K loop" across CUs: the slices leave fp32 partial sums
+    (split_k * M * N * 4 bytes) that a second launch reads and turns into M * N 16-bit outputs; that
+    traffic runs at the MALL rate while it fits the usable share of the MALL, else at the HBM rate."""
+    if split_k <= 1:
+        return 0.0
+    traffic = M * N * (4.0 * split_k + 2.0) * batch
+    fits = traffic <= hw["cache_eff_frac"] * hw["mall_bytes"]
+    return hw["reduce_launch_clk"] + traffic / (hw["mall_bytes_per_clk"] if fits else hw["hbm_bytes_per_clk"])
 
 
 def stream_k_split(tiles, slots, slabs):
-    """Hybrid Stream-K split (Section V-E names Stream-K as the paper kernels' answer to wave
-    quantisation; READING: whole waves of `slots` tiles stay one-tile-per-workgroup, the
-    tiles % slots left over are cut along K into `slots` equal ranges).  Returns (whole waves,
-    stream-K tiles, slabs per worker) or None when there is no partial wave or fewer slabs than
-    workers."""
-    sk = tiles % slots
-    if sk == 0 or sk * slabs < slots:
+    """Hybrid Stream-K (Section V-E names Stream-K; READING: whole waves stay one tile per workgroup, the
+    tiles % slots left over are cut along K into one equal range per slot).  -> (whole waves, stream-K
+    tiles, slabs per worker), or None when nothing is left over or there are fewer slabs than workers."""
+    left = tiles % slots
+    if left == 0 or left * slabs < slots:
         return None
-    return (tiles - sk) // slots, sk, sk * slabs / slots
+    return (tiles - left) // slots, left, left * slabs / slots
+
+
+def stream_k_phase(hw, v, occ, slots, left, per_worker, slab_cost_full, mem_no_l2):
+    """READING: the Stream-K phase keeps every CU full; its workers sit at different K offsets of different
+    tiles, so it is priced with an L2 hit rate of zero (`mem_no_l2`); every worker stores one fp32 partial
+    tile and the share left / slots of them, which straddle two tiles, pays prologue and store twice."""
+    iteration = max(slab_cost_full, mem_no_l2["l_mem"])
+    prologue = mem_no_l2["l_mem"] + hw["mem_latency_clk"] + hw["wg_overhead_clk"]
+    store = hw["n_cu"] * occ * v["block_m"] * v["block_n"] * 4.0 / hw["hbm_bytes_per_clk"] + hw["epilogue_clk"]
+    return (1.0 + left / slots) * (prologue + store) + iteration * (per_worker - 1.0) + slab_cost_full
+
+
+def stream_k_sum(hw, v, slots, left):
+    """READING: the summation pass reads slots + left fp32 partial tiles and writes left 16-bit tiles (MALL
+    rate while that fits its usable share, else HBM), after a second launch, and one output's contributors
+    (floor(slots / left) + 2 at most) form a dependent chain shared by 1, 4 or 8 thread rows (more than 8
+    contributors: 4 rows; more than 32: 8) with four loads in flight each."""
+    tile_elems = v["block_m"] * v["block_n"]
+    traffic = (slots + left) * tile_elems * 4.0 + left * tile_elems * 2.0
+    fits = traffic <= hw["cache_eff_frac"] * hw["mall_bytes"]
+    contributors = slots // left + 2
+    rows = 8 if contributors > 32 else 4 if contributors > 8 else 1
+    chain = math.ceil(contributors / (4.0 * rows)) * hw["mem_latency_clk"]
+    return hw["reduce_launch_clk"] + traffic / (hw["mall_bytes_per_clk"] if fits else hw["hbm_bytes_per_clk"]) + chain
+
+
+# ------------------------------------------------------------------ composition
 
 
 def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0, batch=1):
-    """Model terms for variant v (dict: block_m/n/k, waves_m/n, mfma, stages, slab_clk) with the
-    reduction split split_k ways; hw is a dict of the hardware descriptor's fields; b_layout 0 =
-    B row-major K x N, 1 = B stored K-contiguous (then v["slab_clk"] is that layout's constant);
-    stream_k = 1 prices the hybrid Stream-K split of the last partial wave (needs split_k = 1);
-    batch = number of independent problems of this shape in one launch (READING: Section II-B only
-    names the batch dimension; here it multiplies the tile count of Algorithm 4 and the reduction
-    pass's bytes).
-    Returns a dict with the names of the C ABI's gemm_prediction plus group_m."""
-    # dtype 0 bf16, 1 fp8 e4m3, 2 fp16.  READING: fp16 shares bf16's instruction shapes and rates.
-    row = 1 if dtype == 1 else 0
-    es = 1 if dtype == 1 else 2
-    mi = v["mfma"]
-    mi_k = {(0, 32): 16, (0, 16): 32, (1, 32): 64, (1, 16): 128}[(row, mi)]
-    waves_wg = v["waves_m"] * v["waves_n"]
+    """All model terms for one configuration (names as in the C ABI's gemm_prediction, plus group_m,
+    occupancy and l_tile_full).  READINGS made here: K slices and batch members count as tiles in Algorithm 4;
+    hit rates are evaluated on the mean valid extent of a tile; Algorithm 9 prices the full waves and the
+    last wave separately, adds one launch, and, with two or more workgroups resident per CU, lets a share
+    overlap_frac of a tile's prologue and store stage hide under the other workgroups' K loops in every
+    wave that another wave follows."""
+    es = _elem_bytes(dtype)
     out = {}
+    out["n_mi"], out["l_mt_ideal"], slab_cost = slab_compute(hw, v, dtype)
 
-    # Algorithm 3 (count, and latency at full utilisation spread over the workgroup's SIMDs)
-    l_mi = hw["l_mi_clk"][row][0 if mi == 32 else 1]
-    n_mi, l_mt = alg3_compute_latency(mi, mi, mi_k, v["block_m"], v["block_n"], v["block_k"], l_mi)
-    out["n_mi"] = n_mi
-    out["l_mt_ideal"] = l_mt / min(hw["simd_per_cu"], waves_wg)
+    tiles_m, tiles_n = -(-M // v["block_m"]), -(-N // v["block_n"])
+    occ = resident_workgroups(hw, v, es)
+    tiles = tiles_m * tiles_n * split_k * batch
+    waves, tail, active, tail_per_cu = wave_split(tiles, hw["n_cu"], occ)
+    out.update(tiles=tiles, waves=waves, active_cu=active, occupancy=occ)
 
-    # Algorithm 4.  READING: K slices count as tiles, a CU offers `occ` slots, a remainder of 0
-    # means a full last wave.
-    _, _, t_out = alg4_occupancy(M, N, v["block_m"], v["block_n"], hw["n_cu"])
-    tiles_m, tiles_n = _ceil_div(M, v["block_m"]), _ceil_div(N, v["block_n"])
-    tiles = t_out * split_k * batch
-    occ = occupancy(hw, v, es)
-    slots = hw["n_cu"] * occ
-    waves = math.ceil(tiles / slots)
-    tail_tiles = tiles - (waves - 1) * slots
-    active = min(tail_tiles, hw["n_cu"])
-    tail_per_cu = math.ceil(tail_tiles / hw["n_cu"])
-    out.update(tiles=tiles, waves=waves, active_cu=active)
+    rows_valid, cols_valid = M / tiles_m, N / tiles_n
+    hits = []
+    for scope, capacity in ((hw["n_cu"] // hw["n_xcd"] * occ, hw["l2_bytes"]), (hw["n_cu"] * occ, hw["mall_bytes"])):
+        f_m, f_n, raw = cache_tile(scope, v, tiles_m, tiles_n)
+        rate = min(1.0, max(0.0, alg5_hit_rate(f_m, f_n, rows_valid, cols_valid, v["block_k"])))
+        hits.append((derate(rate, f_m, f_n, v, es, capacity, hw["cache_eff_frac"]), f_m, f_n, raw))
+    (h1, f_m1, f_n1, raw1), (h2, _, _, _) = hits
+    out.update(f_m=f_m1, f_n=f_n1, h_l2=h1, h_mall=h2, group_m=max(1, min(raw1, tiles_m)))
 
-    # Algorithms 5/6 + capacity derate (READING: h * min(1, eff * capacity / footprint))
-    l2_scope = hw["n_cu"] // hw["n_xcd"] * occ
-    c1 = choose_cache_tile(l2_scope, v, tiles_m, tiles_n)
-    c2 = choose_cache_tile(hw["n_cu"] * occ, v, tiles_m, tiles_n)
-    # READING: rows and columns of a tile that lie outside the matrix are never fetched, so the
-    # bytes a tile loads and Algorithm 5's unique / requested counts use the mean valid extent of
-    # a tile, M / tiles_m by N / tiles_n, instead of the nominal M_T by N_T.
-    bm_e, bn_e = M / tiles_m, N / tiles_n
-    for c in (c1, c2):
-        c["h"] = min(1.0, max(0.0, alg5_hit_rate(c["fm"], c["fn"], bm_e, bn_e, v["block_k"])))
-    fp1 = (c1["fm"] * v["block_m"] + c1["fn"] * v["block_n"]) * v["block_k"] * es * 2.0
-    fp2 = (c2["fm"] * v["block_m"] + c2["fn"] * v["block_n"]) * v["block_k"] * es * 2.0
-    h1 = c1["h"] * min(1.0, hw["cache_eff_frac"] * hw["l2_bytes"] / fp1)
-    h2 = c2["h"] * min(1.0, hw["cache_eff_frac"] * hw["mall_bytes"] / fp2)
-    out.update(f_m=c1["fm"], f_n=c1["fn"], h_l2=h1, h_mall=h2)
-    out["group_m"] = max(1, min(c1["raw"], tiles_m))
-
-    k_slabs = _ceil_div(K, v["block_k"])
-    slabs = _ceil_div(k_slabs, split_k)              # slabs per K slice
+    slabs = -(-(-(-K // v["block_k"])) // split_k)        # K slabs of one slice
     out["iters"] = slabs - 1
     out_bytes = 4.0 if split_k > 1 else 2.0
 
-    def memory(per_cu, act, h_l2=None, per_cu_mem=None):
-        # Algorithm 7 in bytes and clocks.  READING: Ld_CU = (BM + BN) * BK bytes per tile; an LDS
-        # fragment-read term is added; the HBM term carries the row-segment efficiency and the
-        # latency is shared by the slabs in flight.
-        hit1 = h1 if h_l2 is None else h_l2
-        # every load instruction of the nominal tile is issued; only the valid extent moves bytes
-        l_issue = (v["block_m"] + v["block_n"]) * v["block_k"] * es * per_cu / hw["vmem_bytes_per_clk"]
-        pcm = per_cu if per_cu_mem is None else per_cu_mem
-        a_bytes = bm_e * v["block_k"] * es * pcm
-        b_bytes = bn_e * v["block_k"] * es * pcm
-        ld_cu = a_bytes + b_bytes
-        # READING: K-contiguous B is read with ds_read_b128 like A, row-major B with transpose reads
-        b_rate = hw["lds_bytes_per_clk"] if b_layout else hw["lds_tr_bytes_per_clk"]
-        l_lds = (v["block_m"] * v["waves_n"] * v["block_k"] * es / hw["lds_bytes_per_clk"]
-                 + v["block_n"] * v["waves_m"] * v["block_k"] * es / b_rate) * per_cu
-        total = ld_cu * act
-        xcds = min(hw["n_xcd"], max(1.0, act))
-        l_l2 = (total / xcds) / hw["l2_bytes_per_clk"]
-        l_mall = (1.0 - hit1) * total / hw["mall_bytes_per_clk"]
-        ea = segment_efficiency(hw, v["block_k"] * es)
-        eb = segment_efficiency(hw, (v["block_k"] if b_layout else v["block_n"]) * es)
-        # READING: Algorithm 7 multiplies (1 - H1)(1 - H2), but both rates come from Algorithm 5 on
-        # nested scopes, so H2 already contains the reuse H1 counts; the product would let fewer
-        # bytes reach HBM than the matrices hold.  The share of requested bytes that reaches HBM is
-        # what neither scope can serve: min(1 - H1, 1 - H2).
-        t_m = min(1.0 - h2, 1.0 - hit1) * (a_bytes / ea + b_bytes / eb) * act
-        l_hbm = t_m / hw["hbm_bytes_per_clk"] + hw["mem_latency_clk"] / max(1.0, per_cu * (v["stages"] - 1))
-        return dict(l_issue=l_issue, l_lds=l_lds, l_l2=l_l2, l_mall=l_mall, l_hbm=l_hbm,
-                    l_mem=max(l_issue, l_lds, l_l2, l_mall, l_hbm))
+    def wave(tiles_per_cu, active_cus, moving=None, h_first=h1):
+        mem = level_times(hw, v, es, b_layout, tiles_per_cu, active_cus, h_first, h2, rows_valid, cols_valid, moving)
+        return dict(mem, **tile_time(hw, v, slab_cost, occ, tiles_per_cu, active_cus, slabs, out_bytes, mem))
 
-    def tile(per_cu, act, per_cu_mem=None):
-        # READING of Algorithm 3's "high utilisation" assumption: the compute latency of a slab is
-        # the variant's measured slab cost, scaled when the CU holds fewer tiles than fit.
-        l_comp = v["slab_clk"] * per_cu
-        if per_cu < occ:
-            l_comp *= hw["under_occ_frac"] + (1.0 - hw["under_occ_frac"]) * per_cu / occ
-        m = memory(per_cu, act, per_cu_mem=per_cu_mem)
-        # Algorithm 8.  READING: fixed latency and per-workgroup cost in the prologue, output bytes
-        # through the HBM rate plus a fixed cost in the epilogue, one exposed compute drain.
-        l_pro = m["l_mem"] + hw["mem_latency_clk"] + hw["wg_overhead_clk"]
-        l_epi = act * per_cu * v["block_m"] * v["block_n"] * out_bytes / hw["hbm_bytes_per_clk"] + hw["epilogue_clk"]
-        l_iter = max(l_comp, m["l_mem"])
-        l_tile = l_pro + l_epi + l_iter * (slabs - 1) + l_comp
-        return dict(m, l_compute=l_comp, l_prologue=l_pro, l_epilogue=l_epi, l_iter=l_iter, l_tile=l_tile)
+    full = wave(float(occ), float(hw["n_cu"]))
+    last = wave(float(tail_per_cu), float(active), tail / active)    # the last wave moves the bytes of the tiles that exist
+    reported = full if waves > 1 else last
+    for name in ("l_compute", "l_issue", "l_lds", "l_l2", "l_mall", "l_hbm", "l_mem", "l_prologue", "l_epilogue",
+                 "l_iter", "l_tile"):
+        out[name] = reported[name]
+    out.update(l_mem_tail=last["l_mem"], l_tile_tail=last["l_tile"], l_tile_full=full["l_tile"])
 
-    full = tile(float(occ), float(hw["n_cu"]))
-    # READING: in the last wave a CU computes ceil(tail / active) tiles, but the bytes that wave moves
-    # are those of the tiles that exist: tail / active per CU.
-    tail = tile(float(tail_per_cu), float(active), tail_tiles / active)
-    shown = full if waves > 1 else tail
-    for k in ("l_compute", "l_issue", "l_lds", "l_l2", "l_mall", "l_hbm", "l_mem", "l_prologue", "l_epilogue",
-              "l_iter", "l_tile"):
-        out[k] = shown[k]
-    out["l_mem_tail"] = tail["l_mem"]
-    out["l_tile_tail"] = tail["l_tile"]
-    out["l_tile_full"] = full["l_tile"]      # Algorithm 8 on a full device, whatever this problem's own wave count
-
-    l_reduce = 0.0
-    if split_k > 1:
-        nbytes = M * N * (4.0 * split_k + 2.0) * batch
-        rate = hw["mall_bytes_per_clk"] if nbytes <= hw["cache_eff_frac"] * hw["mall_bytes"] else hw["hbm_bytes_per_clk"]
-        l_reduce = hw["reduce_launch_clk"] + nbytes / rate
-    out["l_reduce"] = l_reduce
-    # Algorithm 9.  READING: full waves and the under-occupied last wave are priced separately,
-    # plus one launch; with two or more workgroups resident per CU a share overlap_frac of a tile's
-    # prologue and store stage hides under the other workgroups' K loops in every wave that is
-    # followed by another.
+    out["l_reduce"] = split_k_reduce(hw, M, N, split_k, batch)
     hidden = hw["overlap_frac"] * (full["l_prologue"] + full["l_epilogue"]) if (occ >= 2 and waves > 1) else 0.0
-    out["l_total"] = hw["launch_clk"] + (waves - 1) * (full["l_tile"] - hidden) + tail["l_tile"] + l_reduce
+    out["l_total"] = hw["launch_clk"] + (waves - 1) * (full["l_tile"] - hidden) + last["l_tile"] + out["l_reduce"]
 
     if stream_k:
-        # READING (fractional waves in Algorithms 4 and 9): after `whole` full waves the remaining
-        # sk tiles cost w slabs per slot instead of a whole tile; every CU is full; a share
-        # sk/slots of the workers works on two tiles and pays prologue and store stage twice;
-        # partial tiles are fp32 and a second pass reads (slots + sk) of them and writes sk tiles.
-        whole, sk, w = stream_k_split(tiles, slots, slabs)
-        tile_elems = v["block_m"] * v["block_n"]
-        # READING: workers that share an L2 sit at different K offsets of different tiles, so the
-        # stream-K phase is priced with an L2 hit rate of zero.
-        m_sk = memory(float(occ), float(hw["n_cu"]), h_l2=0.0)
-        iter_sk = max(full["l_compute"], m_sk["l_mem"])
-        pro_sk = m_sk["l_mem"] + hw["mem_latency_clk"] + hw["wg_overhead_clk"]
-        l_epi_sk = hw["n_cu"] * occ * tile_elems * 4.0 / hw["hbm_bytes_per_clk"] + hw["epilogue_clk"]
-        l_sk = (1.0 + sk / slots) * (pro_sk + l_epi_sk) + iter_sk * (w - 1.0) + full["l_compute"]
-        nbytes = (slots + sk) * tile_elems * 4.0 + sk * tile_elems * 2.0
-        rate = hw["mall_bytes_per_clk"] if nbytes <= hw["cache_eff_frac"] * hw["mall_bytes"] else hw["hbm_bytes_per_clk"]
-        # READING: one output's contributors (at most slots // sk + 2) are added by 1, 4 or 8 thread
-        # rows, chosen by that count, with 4 loads in flight each
-        contrib = slots // sk + 2
-        rows = 8 if contrib > 32 else 4 if contrib > 8 else 1
-        chain = math.ceil(contrib / (4.0 * rows)) * hw["mem_latency_clk"]
-        l_sum = hw["reduce_launch_clk"] + nbytes / rate + chain
-        for k in ("l_compute", "l_issue", "l_lds", "l_l2", "l_mall", "l_hbm", "l_mem", "l_prologue", "l_epilogue",
-                  "l_iter", "l_tile"):
-            out[k] = full[k]
-        out.update(waves=whole + sk / slots, active_cu=hw["n_cu"], l_mem_tail=full["l_mem"], l_tile_tail=l_sk,
+        slots = hw["n_cu"] * occ
+        whole, left, per_worker = stream_k_split(tiles, slots, slabs)
+        no_l2 = level_times(hw, v, es, b_layout, float(occ), float(hw["n_cu"]), 0.0, h2, rows_valid, cols_valid)
+        l_sk = stream_k_phase(hw, v, occ, slots, left, per_worker, full["l_compute"], no_l2)
+        l_sum = stream_k_sum(hw, v, slots, left)
+        for name in ("l_compute", "l_issue", "l_lds", "l_l2", "l_mall", "l_hbm", "l_mem", "l_prologue", "l_epilogue",
+                     "l_iter", "l_tile"):
+            out[name] = full[name]
+        out.update(waves=whole + left / slots, active_cu=hw["n_cu"], l_mem_tail=full["l_mem"], l_tile_tail=l_sk,
                    l_reduce=l_sum, l_total=hw["launch_clk"] + whole * full["l_tile"] + l_sk + l_sum)
     out["total_us"] = out["l_total"] / (hw["clk_ghz"] * 1e3)
     return out
 
 
 def predict_grouped(hw, dtype, shapes, v, b_layout=0):
-    """Total latency in clocks of ONE launch that computes several products of different shapes
-    [(M, N, K), ...] (M = 0: an empty group) with variant v, no K splitting.
-    READING (Sections II-B and V-C only name the grouped dimension): Algorithm 4 counts the tiles
-    of all groups together, T = sum T_g, omega = ceil(T / slots); Algorithm 8 prices each group's
-    tile on a full device (the other groups' tiles keep the CUs busy) with that group's own cache
-    tile, hit rates and K loop; Algorithm 9 becomes omega times the tile-weighted mean of the
-    groups' tile latencies, plus one launch.  Returns (l_total, [group_m per group])."""
-    es = 1 if dtype == 1 else 2
-    tiles, weighted, group_m = 0, 0.0, []
+    """ONE launch of several products [(M, N, K), ...] (M = 0: an empty group) with variant v, no K
+    splitting.  READING (Sections II-B and V-C only name the grouped dimension): Algorithm 4 counts all
+    groups' tiles together; Algorithm 8 prices each group's tile on a full device with that group's own
+    cache tile, hit rates and K loop; Algorithm 9 is the wave count times the tile-weighted mean of the
+    groups' tile latencies, plus one launch.  -> (l_total, [group_m per group])"""
+    es = _elem_bytes(dtype)
+    counts, latencies, bands = [], [], []
     for (M, N, K) in shapes:
         if M == 0:
-            group_m.append(1)
+            bands.append(1)
             continue
         p = predict(hw, dtype, M, N, K, v, 1, b_layout=b_layout)
-        t = _ceil_div(M, v["block_m"]) * _ceil_div(N, v["block_n"])
-        tiles += t
-        weighted += t * p["l_tile_full"]
-        group_m.append(p["group_m"])
-    slots = hw["n_cu"] * occupancy(hw, v, es)
-    return hw["launch_clk"] + math.ceil(tiles / slots) * weighted / tiles, group_m
+        counts.append((-(-M // v["block_m"])) * (-(-N // v["block_n"])))
+        latencies.append(p["l_tile_full"])
+        bands.append(p["group_m"])
+    total_tiles = sum(counts)
+    mean_tile = sum(c * l for c, l in zip(counts, latencies)) / total_tiles
+    slots = hw["n_cu"] * resident_workgroups(hw, v, es)
+    return hw["launch_clk"] + math.ceil(total_tiles / slots) * mean_tile, bands

@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("GEMM355_LIB") or os.path.join(_PKG, "libgemm355.so") 
 GEMM_BF16 = 0
 GEMM_FP8_E4M3 = 1
 GEMM_FP16 = 2
-GEMM_ABI_VERSION = 7
+GEMM_ABI_VERSION = 8
 GEMM_B_ROW_MAJOR = 0
 GEMM_B_K_CONTIGUOUS = 1
 
@@ -47,7 +47,8 @@ class gemm_hw(ctypes.Structure):
                 ("wg_overhead_clk", ctypes.c_double), ("epilogue_clk", ctypes.c_double),
                 ("reduce_launch_clk", ctypes.c_double), ("under_occ_frac", ctypes.c_double),
                 ("seg_eff_lo", ctypes.c_double), ("overlap_frac", ctypes.c_double),
-                ("l_mi_clk", (ctypes.c_double * 2) * 2)]
+                ("l_mi_clk", (ctypes.c_double * 2) * 2), ("fill_issue_bytes_per_clk", ctypes.c_double),
+                ("slab_sync_clk", ctypes.c_double)]
 
 
 class gemm_cfg(ctypes.Structure):
@@ -58,7 +59,7 @@ class gemm_cfg(ctypes.Structure):
                 ("waves_n", ctypes.c_uint8), ("mfma", ctypes.c_uint8), ("k_unroll", ctypes.c_uint8),
                 ("split_k", ctypes.c_uint16), ("group_m", ctypes.c_uint16), ("group_n", ctypes.c_uint16),
                 ("xcd_remap", ctypes.c_uint8), ("stages", ctypes.c_uint8),
-                ("slab_clk", ctypes.c_uint16), ("b_layout", ctypes.c_uint8), ("stream_k", ctypes.c_uint8),
+                ("reserved1", ctypes.c_uint16), ("b_layout", ctypes.c_uint8), ("stream_k", ctypes.c_uint8),
                 ("sk_workers", ctypes.c_uint16), ("alpha", ctypes.c_float),
                 ("bottleneck", ctypes.c_int32), ("beta", ctypes.c_float), ("predicted_us", ctypes.c_double),
                 ("batch", ctypes.c_int32), ("groups", ctypes.c_int32), ("stride_a", ctypes.c_int64),

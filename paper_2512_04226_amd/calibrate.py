@@ -3,11 +3,13 @@ gemm_select or gemm_run):
 
   * L_MI of every matrix instruction, the MFMA ceiling on workload-like operands, the L2, MALL and HBM
     read rates, the LDS fragment-read rates and the load latency, from the library's probes;
-  * SLAB_CLK of every kernel variant: steady-state clocks per K slab of one tile on a full CU,
-    from one large compute-bound problem per datatype (8192^3).
+  * the measured cost of a K slab of every kernel variant (steady-state clocks per slab of one tile on a
+    full CU, from one large compute-bound problem per datatype, 8192^3) beside the compute latency the
+    model assigns it from the descriptor alone (Algorithm 3's L_MT plus the slab's fill and synchronisation
+    cost): the data the two fitted constants fill_issue_bytes_per_clk and slab_sync_clk come from.  No
+    per-variant timing enters the selector.
 
-Prints the hardware lines and the variants.hpp rows with the two measured columns (B row-major,
-B K-contiguous); the two K-loop-form columns are carried over from the table as it stands.
+Prints the descriptor fields the probes give and one line per variant (B row-major and K-contiguous).
 
     python -m paper_2512_04226_amd.calibrate [--n 8192]
 
@@ -38,7 +40,7 @@ def _table(first, last):
         m = re.match(r"#define G355_VARIANTS_(BF16|FP8)_\d", line)
         if m:
             sect = m.group(1)
-        m = re.match(r"\s*X\(" + ", ".join([r"(\d+)"] * 11) + r"\)", line)
+        m = re.match(r"\s*X\(" + ", ".join([r"(\d+)"] * 9) + r"\)", line)
         if m:
             v = [int(x) for x in m.groups()]
             out[(sect,) + tuple(v[:7])] = tuple(v[first:last])
@@ -48,11 +50,6 @@ def _table(first, last):
 def table_loop_forms():
     """(section, block_m, block_n, block_k, waves_m, waves_n, mfma, stages) -> (LOOP, LOOP_KC) as
     written in csrc/variants.hpp, in table order."""
-    return _table(9, 11)
-
-
-def table_rows():
-    """Same keys -> (SLAB_CLK, SLAB_CLK_KC)."""
     return _table(7, 9)
 
 
@@ -217,11 +214,10 @@ def compare_loop_forms(lib_paths, n=8192, passes=7):
         return best if mean[best] < 0.985 else 0
 
     print("// LOOP / LOOP_KC columns chosen from the timings above (other columns as in the table)")
-    table = table_rows()
-    for full, (tau, tau_kc) in table.items():
+    for full in table_loop_forms():
         sect, key = full[0], full[1:]
-        print("%s    X(%s, %d, %d, %d, %d)" % (sect, ", ".join(str(x) for x in key), tau, tau_kc,
-                                             choice(sect, 0, key), choice(sect, 1, key)), flush=True)
+        print("%s    X(%s, %d, %d)" % (sect, ", ".join(str(x) for x in key), choice(sect, 0, key), choice(sect, 1, key)),
+              flush=True)
 
 
 def main():
@@ -235,7 +231,6 @@ def main():
     if args.loop_forms:
         compare_loop_forms(args.loop_forms, args.n)
         return
-    forms = table_loop_forms()
     if not args.skip_rates:
         r = measure_rates()
         for key, val in r.items():
@@ -254,17 +249,15 @@ def main():
         if args.rates_only:
             return
     for dtype, name in ((g.GEMM_BF16, "BF16"), (g.GEMM_FP8_E4M3, "FP8")):
-        print("// %s variants, SLAB_CLK measured on %d^3" % (name, args.n))
+        print("// %s variants on %d^3: measured clocks per slab | the model's compute latency per slab (L_MT + fill + sync)" % (name, args.n))
         rows = measure_slab_clk(dtype, args.n, 0)
         rows_kc = measure_slab_clk(dtype, args.n, 1)
         for (cfg, us, tau), (_, us_kc, tau_kc) in zip(rows, rows_kc):
-            # the K-contiguous gain of a small tile on this huge problem (L2-resident panels, hundreds of
-            # waves) is larger than what the small problems that pick such tiles see: floor it
-            tau_kc = max(tau_kc, 0.9 * tau)
-            key = (cfg.block_m, cfg.block_n, cfg.block_k, cfg.waves_m, cfg.waves_n, cfg.mfma, cfg.stages)
-            print("    X(%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d)   // %.1f us %.0f TFLOP/s | K-contiguous B %.1f us %.0f TFLOP/s" % (
-                key + (round(tau), round(tau_kc)) + forms[(name,) + key] +
-                (us, 2.0 * args.n ** 3 / us * 1e-6, us_kc, 2.0 * args.n ** 3 / us_kc * 1e-6)), flush=True)
+            p = g.gemm_predict(cfg)
+            model = p.l_compute / max(1, p.occupancy)
+            print("    %-36s measured %5.0f (K-contiguous B %5.0f)  model %5.0f  ratio %.2f   // %.1f us %.0f TFLOP/s | %.1f us %.0f TFLOP/s" % (
+                cfg.describe(), tau, tau_kc, model, tau / model, us, 2.0 * args.n ** 3 / us * 1e-6, us_kc,
+                2.0 * args.n ** 3 / us_kc * 1e-6), flush=True)
 
 
 if __name__ == "__main__":

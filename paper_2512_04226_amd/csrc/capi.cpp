@@ -455,8 +455,13 @@ int gemm_hw_set(const gemm_hw *in)
         in->hbm_bytes_per_clk <= 0 || in->mall_bytes_per_clk <= 0 || in->l2_bytes_per_clk <= 0 ||
         in->lds_bytes_per_clk <= 0 || in->lds_tr_bytes_per_clk <= 0 || in->vmem_bytes_per_clk <= 0 ||
         in->lds_bytes <= 0 || in->under_occ_frac <= 0 || in->under_occ_frac > 1 || in->seg_eff_lo <= 0 || in->seg_eff_lo > 1 ||
-        in->overlap_frac < 0 || in->overlap_frac > 1)
+        in->overlap_frac < 0 || in->overlap_frac > 1 || in->fill_issue_bytes_per_clk <= 0 || in->slab_sync_clk < 0 ||
+        in->n_cu > 4096 || in->simd_per_cu > 64)
         return GEMM_ERR_SHAPE;
+    for (int d = 0; d < 2; ++d)
+        for (int m = 0; m < 2; ++m)
+            if (!(in->l_mi_clk[d][m] > 0))
+                return GEMM_ERR_SHAPE;
     hw_replace(*in);
     return GEMM_OK;
 }

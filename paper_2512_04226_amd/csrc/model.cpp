@@ -17,7 +17,7 @@
 
 namespace g355 {
 
-#define G355_X(bm, bn, bk, wm, wn, mi, ns, tau, tau_kc, lf, lf_kc) {bm, bn, bk, wm, wn, mi, ns, tau, tau_kc},
+#define G355_X(bm, bn, bk, wm, wn, mi, ns, lf, lf_kc) {bm, bn, bk, wm, wn, mi, ns},
 static const Variant kVariantsBf16[] = {G355_VARIANTS_BF16(G355_X)};
 static const Variant kVariantsFp8[] = {G355_VARIANTS_FP8(G355_X)};
 #undef G355_X
@@ -33,9 +33,13 @@ const Variant &variant_at(int dtype, int id)
     return dtype != GEMM_FP8_E4M3 ? kVariantsBf16[id] : kVariantsFp8[id];
 }
 
-// One MI355X.  Matrix-instruction issue intervals come from register-resident MFMA loops on
-// the device, expressed in 2.4 GHz clocks; the L2 rate is the public per-channel figure; the
-// remaining rates and fixed costs were fitted once against timings of this kernel family.
+// One MI355X.  Measured with the library's probes (calibrate.py --rates-only): the matrix-instruction
+// issue intervals (register-resident MFMA loop on workload-like operands, in the settled state, expressed
+// in 2.4 GHz clocks: the chip is power-limited, so this is what an instruction costs while the datapath
+// toggles), the LDS fragment-read rates and the HBM rate.  The remaining rates and fixed costs are
+// effective values fitted against sweeps of this kernel family; the probes' raw figures for them
+// (L2 1610 B/clk per XCD, MALL 2940, idle load latency 960 clk) are upper bounds that the kernels, with
+// their MFMA work going on beside the loads, do not reach.
 static gemm_hw make_default_hw()
 {
     gemm_hw h;
@@ -50,9 +54,11 @@ static gemm_hw make_default_hw()
     h.hbm_bytes_per_clk = 2700.0;    // 6.5 TB/s: the streaming-read probe's rate, of the 8 TB/s pins
     h.mall_bytes_per_clk = 2400.0;   // what L2 misses are served at when the MALL holds the data (fitted; a streaming read sees 6.5 TB/s)
     h.l2_bytes_per_clk = 2048.0;     // 16 channels x 128 B per XCD
-    h.lds_bytes_per_clk = 118.0;     // ds_read_b128 fragments
-    h.lds_tr_bytes_per_clk = 62.0;   // ds_read_b64_tr_* fragments
-    h.vmem_bytes_per_clk = 25.3;       // direct-to-LDS fill rate a CU sustains next to its MFMA work (fitted)
+    h.lds_bytes_per_clk = 250.0;     // ds_read_b128 fragments (probe: 153 TB/s over 256 CUs)
+    h.lds_tr_bytes_per_clk = 222.0;  // ds_read_b64_tr_* fragments (probe: 136 TB/s)
+    h.vmem_bytes_per_clk = 25.3;     // Algorithm 7's R_L1: fill rate a CU sustains when loads are what it waits for (fitted)
+    h.fill_issue_bytes_per_clk = 55.0;  // wave time the fill of a slab takes out of the MFMA stream (fitted; the vector-memory path issues at most 64 B/clk)
+    h.slab_sync_clk = 95.0;          // barrier and first-fragment wait per slab (fitted)
     h.mem_latency_clk = 1350.0;
     h.cache_eff_frac = 0.175;
     h.launch_clk = 2600.0;
@@ -62,15 +68,17 @@ static gemm_hw make_default_hw()
     h.under_occ_frac = 0.85;
     h.seg_eff_lo = 0.105;
     h.overlap_frac = 0.5;            // fitted
-    h.l_mi_clk[GEMM_BF16][0] = 35.6;      // v_mfma_f32_32x32x16_bf16  (2259 TFLOP/s device-wide)
-    h.l_mi_clk[GEMM_BF16][1] = 27.8;      // v_mfma_f32_16x16x32_bf16  (1449 TFLOP/s)
-    h.l_mi_clk[GEMM_FP8_E4M3][0] = 65.0;  // v_mfma_f32_32x32x64_f8f6f4 (4953 TFLOP/s)
-    h.l_mi_clk[GEMM_FP8_E4M3][1] = 35.0;  // v_mfma_f32_16x16x128_f8f6f4 (4599 TFLOP/s)
+    // on N(0,1)-like operands; on constant operands the four reach 2440 / 2440 / 4930 / 4940 TFLOP/s (32.9 / 16.5 / 65.3 / 32.6 clk)
+    h.l_mi_clk[GEMM_BF16][0] = 44.4;      // v_mfma_f32_32x32x16_bf16  (1812 TFLOP/s device-wide)
+    h.l_mi_clk[GEMM_BF16][1] = 19.6;      // v_mfma_f32_16x16x32_bf16  (2054 TFLOP/s)
+    h.l_mi_clk[GEMM_FP8_E4M3][0] = 81.7;  // v_mfma_f32_32x32x64_f8f6f4 (3940 TFLOP/s)
+    h.l_mi_clk[GEMM_FP8_E4M3][1] = 37.8;  // v_mfma_f32_16x16x128_f8f6f4 (4264 TFLOP/s)
     return h;
 }
 
 // A 304-CU CDNA3-class part as the paper's evaluation platform (Section V): public sizes and
-// bandwidths; matrix instructions at half the per-CU rate; fixed costs left as measured here.
+// bandwidths; matrix instructions at half the per-CU rate and half the LDS read width; fixed costs
+// left as fitted here.  Nothing in it is a timing of this library's kernels.
 static gemm_hw make_mi300x_like_hw()
 {
     gemm_hw h = make_default_hw();
@@ -80,7 +88,7 @@ static gemm_hw make_mi300x_like_hw()
     h.clk_ghz = 2.1;
     h.hbm_bytes_per_clk = 5300.0 * 0.75 / 2.1;   // 5.3 TB/s pins, three quarters sustained
     h.mall_bytes_per_clk = 17200.0 / 2.1 * 0.6;  // 17.2 TB/s peak Infinity Cache rate
-    h.lds_bytes_per_clk = 118.0;
+    h.lds_bytes_per_clk = 125.0;
     h.lds_tr_bytes_per_clk = 30.0;               // no transpose LDS reads: narrow reads instead
     for (int d = 0; d < 2; ++d)
         for (int m = 0; m < 2; ++m)
@@ -305,8 +313,7 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
     const int waves_wg = v.waves_m * v.waves_n;
     const int mi_k = mfma_k(dtype, v.mfma);
 
-    // Algorithm 3: instruction count and the latency it would have at full matrix-core
-    // utilisation (reported); the latency the model uses is the kernel's measured slab cost.
+    // Algorithm 3: L_MT = N_MI * L_MI, spread over the SIMDs the workgroup's waves occupy.
     const double n_mi = (double)cdiv(v.block_m, v.mfma) * cdiv(v.block_n, v.mfma) * cdiv(v.block_k, mi_k);
     // the fp16 and bf16 matrix instructions issue at the same rate: one row of the table
     const double l_mi = hw.l_mi_clk[dtype == GEMM_FP8_E4M3 ? 1 : 0][v.mfma == 32 ? 0 : 1];
@@ -367,12 +374,17 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
     p->iters = slabs - 1.0;
     const double out_bytes = (split_k > 1) ? 4.0 : 2.0;
 
+    const double fill_bytes = (double)(v.block_m + v.block_n) * v.block_k * es;   // one slab of one tile
     const double ea = segment_efficiency(hw, (double)v.block_k * es);
     const double eb = segment_efficiency(hw, (double)(b_layout ? v.block_k : v.block_n) * es);
     auto tile_latency = [&](double per_cu, double act, double per_cu_mem, MemTerms *mt_out, double *l_comp_out,
                             double *pro, double *epi, double *iter) {
-        // per_cu tiles share the CU; fewer than fit run a little faster each, but not in proportion
-        double l_comp = (double)(b_layout ? v.slab_clk_kc : v.slab_clk) * per_cu;
+        // Compute latency of one K slab of one tile: Algorithm 3's L_MT, plus what the slab's fill and
+        // its barrier take out of the waves' instruction streams (the direct-to-LDS loads of a slab are
+        // issued by the same waves, in order with their MFMAs, and the vector-memory path accepts them at
+        // fill_issue_bytes_per_clk; measured slab costs of all variants follow L_MT + fill + a constant).
+        // per_cu tiles share the CU; fewer than fit run a little faster each, but not in proportion.
+        double l_comp = (p->l_mt_ideal + fill_bytes / hw.fill_issue_bytes_per_clk + hw.slab_sync_clk) * per_cu;
         if (per_cu < occ)
             l_comp *= hw.under_occ_frac + (1.0 - hw.under_occ_frac) * per_cu / occ;
         const MemTerms mt = memory_latency(hw, v, es, b_layout, per_cu, act, h1, h2, bm_e, bn_e, per_cu_mem, ea, eb);
@@ -544,7 +556,6 @@ void fill_cfg(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, 
     c->group_n = (uint16_t)gn;
     c->xcd_remap = 1;
     c->stages = (uint8_t)v.stages;
-    c->slab_clk = (uint16_t)(b_layout ? v.slab_clk_kc : v.slab_clk);
     c->b_layout = (uint8_t)b_layout;
     c->stream_k = (uint8_t)(stream_k ? 1 : 0);
     c->sk_workers = (uint16_t)(stream_k ? stream_k_workers(hw, v, dtype) : 0);

@@ -1,5 +1,7 @@
-"""Pins for the model oracle (oracle/selector_model.py): the values the paper prints and the
-closed forms its algorithms imply."""
+"""Pins for the printed algorithms in the model checker (oracle/selector_model.py): the values the paper
+prints and the closed forms its algorithms imply; then the library's model terms against the checker's
+composition over many shapes and every configuration (a breadth check -- the composed readings themselves are
+pinned to hand-worked numbers, for the checker and for the library separately, in test_model_goldens.py)."""
 import math
 import os
 
@@ -115,7 +117,7 @@ def _hw_dict(g):
 
 def _variant_dict(c):
     return dict(block_m=c.block_m, block_n=c.block_n, block_k=c.block_k, waves_m=c.waves_m, waves_n=c.waves_n,
-                mfma=c.mfma, stages=c.stages, slab_clk=c.slab_clk)
+                mfma=c.mfma, stages=c.stages)
 
 
 SHAPES = [(512, 512, 512), (4096, 4096, 4096), (8192, 8192, 8192), (1, 28672, 8192), (16, 8192, 28672),
@@ -127,7 +129,7 @@ SHAPES = [(512, 512, 512), (4096, 4096, 4096), (8192, 8192, 8192), (1, 28672, 81
 def test_shipped_model_terms_match_the_oracle(dtype, b_layout):
     from paper_2512_04226_amd import binding as g
     hw = _hw_dict(g)
-    fields = ["n_mi", "l_mt_ideal", "l_compute", "tiles", "waves", "active_cu", "f_m", "f_n", "h_l2", "h_mall",
+    fields = ["n_mi", "l_mt_ideal", "l_compute", "occupancy", "tiles", "waves", "active_cu", "f_m", "f_n", "h_l2", "h_mall",
               "l_issue", "l_lds", "l_l2", "l_mall", "l_hbm", "l_mem", "l_mem_tail", "l_prologue", "l_epilogue",
               "l_iter", "iters", "l_tile", "l_tile_tail", "l_reduce", "l_total", "total_us"]
     checked = n_sk = 0
@@ -164,24 +166,6 @@ def test_pick_is_the_oracle_argmin():
                 best = (t, c.kernel_id, c.split_k, c.stream_k)
         pick = g.gemm_select(M, N, K, 0)
         assert (pick.kernel_id, pick.split_k, pick.stream_k) == best[1:], (M, N, K, pick.describe())
-
-
-def test_model_reduces_to_the_papers_form_when_extras_are_off():
-    """With one workgroup per CU, no fixed costs, perfect segments and a full last wave the
-    composition is Algorithm 8 + Algorithm 9 on the same terms (plus the drain reading)."""
-    hw = dict(n_cu=256, n_xcd=8, simd_per_cu=4, lds_bytes=160 * 1024, l2_bytes=4 << 20, mall_bytes=256 << 20,
-              clk_ghz=2.4, hbm_bytes_per_clk=2500.0, mall_bytes_per_clk=6000.0, l2_bytes_per_clk=2048.0,
-              lds_bytes_per_clk=128.0, lds_tr_bytes_per_clk=128.0, vmem_bytes_per_clk=64.0, mem_latency_clk=0.0,
-              cache_eff_frac=0.5, launch_clk=0.0, wg_overhead_clk=0.0, epilogue_clk=0.0, reduce_launch_clk=0.0,
-              under_occ_frac=1.0, seg_eff_lo=1.0, overlap_frac=0.0, l_mi_clk=[[32.0, 16.0], [64.0, 32.0]])
-    v = dict(block_m=256, block_n=256, block_k=64, waves_m=2, waves_n=2, mfma=32, stages=2, slab_clk=2048)
-    o = sm.predict(hw, 0, 8192, 8192, 8192, v, 1)
-    assert o["waves"] == 4 and o["active_cu"] == 256 and o["l_mt_ideal"] == 256 * 32.0 / 4
-    l_epi = 256 * 256 * 256 * 2.0 / 2500.0
-    l_tile = sm.alg8_tile_latency(8192, 64, o["l_mem"], o["l_compute"], 1, 1, l_epi, 1.0) + o["l_compute"]
-    assert o["l_tile"] == pytest.approx(l_tile)
-    assert o["l_total"] == pytest.approx(sm.alg9_total_latency(8192, 8192, 256, 256, 256, l_tile))
-    assert o["h_l2"] == pytest.approx(sm.alg5_hit_rate(4, 8, 256, 256, 64))
 
 
 def test_retargeting_to_a_304_cu_table_changes_waves_cache_tiles_and_candidates():
