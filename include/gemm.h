@@ -50,7 +50,7 @@ typedef enum gemm_status {
     GEMM_ERR_SHAPE = -2,       /* M, N or K < 1, or beyond the 32-bit tile arithmetic */
     GEMM_ERR_DTYPE = -3,       /* dtype is not a gemm_dtype */
     GEMM_ERR_CFG_ILLEGAL = -4, /* cfg fields do not describe a compiled kernel legal for the shape */
-    GEMM_ERR_ALIGN = -5,       /* pointer not 16-byte aligned, or ld/N/K not a multiple of 16 bytes */
+    GEMM_ERR_ALIGN = -5,       /* a pointer, leading dimension or batch stride is not a multiple of 16 bytes */
     GEMM_ERR_WORKSPACE = -6,   /* split_k > 1 and the registered workspace is missing or too small */
     GEMM_ERR_ABI = -7,         /* cfg.abi_version differs from GEMM_ABI_VERSION */
     GEMM_ERR_HIP = -8,         /* the HIP runtime refused the launch */
@@ -171,8 +171,14 @@ const char *gemm_strerror(int status);
 /*
  * Analytical selection (Algorithms 3-9 over every compiled variant, arg-min of predicted
  * latency, deterministic tie-break).  Pure host code: works with no GPU present.
- * out: caller-owned.  Requires M, N, K >= 1; N and K must be multiples of 8 (bf16) or
- * 16 (fp8) elements (else GEMM_ERR_ALIGN).
+ * out: caller-owned.  Total on M, N, K >= 1 (up to 2^30 each).  The cfg's leading dimensions are set to the
+ * smallest legal ones: K, N (K for K-contiguous B) and N, each rounded up to a whole number of 16-byte
+ * chunks (8 16-bit or 16 fp8 elements; ldc: 8 elements); the caller may overwrite them with larger
+ * multiples of that.  N and K themselves need not be such multiples: gemm_run then runs the variant's
+ * instantiation that trims the ragged ends in registers (slower than the direct-to-LDS one; the model
+ * does not price the difference).  Whatever lies between a row's end and its leading dimension is never
+ * used (NaN patterns there do not reach the result) and C's padding is never written; the library does
+ * read, without using it, the rest of the 16-byte chunk that holds a row's last element.
  */
 int gemm_select(int64_t M, int64_t N, int64_t K, int dtype, gemm_cfg *out);
 /* The same for a given storage of B (gemm_select is b_layout = GEMM_B_ROW_MAJOR). */
@@ -196,8 +202,8 @@ int gemm_cfg_at_batched(int idx, int64_t M, int64_t N, int64_t K, int64_t batch,
  * and that costs the analytical selector one more pass of the model over the groups.
  *
  *   gemm_problem      host-side description of one group.  M may be 0 (an empty group: nothing is
- *                     read or written, its pointers may be NULL); N, K >= 1 and aligned as for
- *                     gemm_select.  A, B, C: device pointers, 16-byte aligned; ld* in elements.
+ *                     read or written, its pointers may be NULL); N, K >= 1.  A, B, C: device pointers,
+ *                     16-byte aligned; ld* in elements, multiples of 16 bytes (ldc: of 8 elements).
  *                     gemm_select_grouped / gemm_cfg_at_grouped read M, N, K only.
  *   gemm_select_grouped  arg-min over the variants that are legal for every non-empty group (no
  *                     split-K, no Stream-K).  Model: Algorithm 4 counts the tiles of all groups
@@ -252,7 +258,7 @@ int gemm_run_grouped(const gemm_cfg *cfg, int n_groups, const gemm_group_rec *ho
 /*
  * Enqueue C = alpha * A * B + beta * C on hip_stream (a hipStream_t; NULL = the default stream) with
  * the kernel cfg names; returns without synchronising.  A, B, C: device pointers,
- * 16-byte aligned.  When cfg->split_k > 1 or cfg->stream_k = 1 a workspace of
+ * 16-byte aligned; lda, ldb multiples of 16 bytes, ldc a multiple of 8 elements (else GEMM_ERR_ALIGN).  When cfg->split_k > 1 or cfg->stream_k = 1 a workspace of
  * gemm_workspace_bytes(cfg) must have been registered with gemm_set_workspace for the
  * current device.
  */
@@ -274,7 +280,7 @@ int gemm_run(const gemm_cfg *cfg, const void *A, const void *B, void *C, void *h
 #define GEMM_NOALLOC_WORKSPACE_BYTES (64u << 20)
 int gemm_run_noalloc(const gemm_cfg *cfg, const void *A, const void *B, void *C, void *hip_stream);
 
-/* fp32 partial sums: batch * split_k * M * N * 4 bytes when split_k > 1; 2 * sk_workers * block_m *
+/* fp32 partial sums: batch * split_k * M * ceil(N / 8) * 8 * 4 bytes when split_k > 1; 2 * sk_workers * block_m *
  * block_n * 4 bytes (two partial tiles per stream-K workgroup) when stream_k = 1; else 0. */
 size_t gemm_workspace_bytes(const gemm_cfg *cfg);
 

@@ -35,7 +35,12 @@ def _ensure_workspace(cfg, device):
     idx = device.index if device.index is not None else torch.cuda.current_device()
     cur = _workspace.get(idx)
     if cur is None or cur.numel() * 4 < need:
-        # runs on one device are stream-ordered by the caller; a larger buffer replaces the old one
+        # A larger buffer replaces the old one.  Launches enqueued earlier -- on whatever stream the caller
+        # gave them -- may still be using the old one, and the allocator only knows about torch's current
+        # stream: wait for the device before the old buffer can be handed out again.  (Rare: the buffer
+        # only ever grows.)
+        if cur is not None:
+            torch.cuda.synchronize(device)
         cur = _workspace[idx] = torch.empty((need + 3) // 4, dtype=torch.float32, device=device)
     g.gemm_set_workspace(cur)
 
@@ -58,7 +63,8 @@ def matmul(A, B, out=None, alpha=1.0, beta=0.0, b_k_contiguous=False, stream=Non
     if out is None:
         if beta != 0.0:
             raise ValueError("beta != 0 needs out")
-        out = torch.empty((M, N), dtype=out_dtype, device=A.device)
+        # rows of C start on 16-byte boundaries: a ragged N gets a padded row stride (the result is a view)
+        out = torch.empty((M, -(-N // 8) * 8), dtype=out_dtype, device=A.device)[:, :N]
     elif out.shape != (M, N) or out.dtype != out_dtype or out.stride(1) != 1 or out.device != A.device:
         raise ValueError("out must be a (%d, %d) %s tensor with contiguous rows" % (M, N, out_dtype))
     layout = g.GEMM_B_K_CONTIGUOUS if b_k_contiguous else g.GEMM_B_ROW_MAJOR

@@ -20,10 +20,7 @@ int check_problem(int64_t M, int64_t N, int64_t K, int dtype)
     const int64_t lim = (int64_t)1 << 30;
     if (M > lim || N > lim || K > lim)
         return GEMM_ERR_SHAPE;
-    const int per16 = 16 / elem_bytes(dtype);   // elements per 16-byte chunk
-    if (N % per16 || K % per16)
-        return GEMM_ERR_ALIGN;
-    return GEMM_OK;
+    return GEMM_OK;   // N and K need not be whole 16-byte chunks: such shapes run the trimming instantiation
 }
 
 // The stream-K plan a cfg describes, or false when its fields do not make one.
@@ -84,7 +81,7 @@ int check_group_rec(const gemm_cfg *cfg, const gemm_group_rec *r, int64_t slot_s
     const int64_t lim = (int64_t)1 << 31;
     const int64_t b_window = cfg->b_layout ? (int64_t)v.block_n * r->ldb * es
                                            : (k_per_split(v, r->K, 1) + (int64_t)v.stages * v.block_k) * r->ldb * es;
-    if ((int64_t)v.block_m * r->lda * es >= lim || b_window >= lim)
+    if ((int64_t)v.block_m * r->lda * es >= lim || b_window >= lim || (int64_t)r->tiles_m * r->tiles_n >= lim)
         return GEMM_ERR_SHAPE;
     return GEMM_OK;
 }
@@ -269,7 +266,7 @@ const char *gemm_strerror(int status)
     case GEMM_ERR_SHAPE: return "bad shape";
     case GEMM_ERR_DTYPE: return "unknown dtype";
     case GEMM_ERR_CFG_ILLEGAL: return "configuration is not legal for this problem";
-    case GEMM_ERR_ALIGN: return "pointer, leading dimension, N or K not aligned to 16 bytes";
+    case GEMM_ERR_ALIGN: return "pointer, leading dimension or batch stride not aligned to 16 bytes";
     case GEMM_ERR_WORKSPACE: return "split-K workspace missing or too small";
     case GEMM_ERR_ABI: return "ABI version mismatch";
     case GEMM_ERR_HIP: return "HIP launch failed";
@@ -399,7 +396,7 @@ int gemm_grouped_locate(const gemm_cfg *cfg, int n_groups, const gemm_group_rec 
         rc = check_group_rec(cfg, &table[i], slots);
         if (rc)
             return rc;
-        slots += group_slots(table[i].tiles_m * table[i].tiles_n, X);
+        slots += group_slots((int64_t)table[i].tiles_m * table[i].tiles_n, X);
     }
     if (workgroup < 0 || workgroup >= slots * X)
         return GEMM_ERR_INDEX;
@@ -487,7 +484,8 @@ size_t gemm_workspace_bytes(const gemm_cfg *cfg)
         return (size_t)2 * cfg->sk_workers * cfg->block_m * cfg->block_n * sizeof(float);
     if (cfg->split_k <= 1)
         return 0;
-    return (size_t)(cfg->batch > 1 ? cfg->batch : 1) * cfg->split_k * (size_t)cfg->M * (size_t)cfg->N * sizeof(float);
+    // slab rows are N rounded up to 8 floats apart
+    return (size_t)(cfg->batch > 1 ? cfg->batch : 1) * cfg->split_k * (size_t)cfg->M * (size_t)((cfg->N + 7) / 8 * 8) * sizeof(float);
 }
 
 int gemm_stream_k_plan(const gemm_cfg *cfg, int32_t plan4[4])

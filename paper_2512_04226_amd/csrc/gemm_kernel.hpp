@@ -85,10 +85,17 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // few per MFMA over the first half of its MFMAs, so that a read has half a k-step to land (the
 // compiler alone issues reads next to their uses, which costs most with one wave per SIMD).
 // Building with -DG355_FORCE_LOOP_FORM=k gives every variant form k (how the forms are compared).
-template <int ES_, int BM_, int BN_, int BK_, int WM_, int WN_, int MI_, int NS_, int BL_, int FT_ = 0, int LF_ = 0>
+// RG_: 1 = the instantiation for shapes whose N or K is not a whole number of 16-byte chunks.  A chunk that
+// holds the end of a row of a K-contiguous operand then also holds bytes that are not part of the matrix
+// (padding up to the leading dimension, which may be anything, NaN included), so slabs go through registers,
+// where those elements are cleared, and are written to LDS with ds_write_b128 (a plain two-stage loop: the
+// next slab's global loads fly during the current slab's MFMAs); results at the ragged edge of C are stored
+// element by element.  Everything else -- LDS layout, fragments, MFMAs, staged epilogue -- is shared.
+template <int ES_, int BM_, int BN_, int BK_, int WM_, int WN_, int MI_, int NS_, int BL_, int FT_ = 0, int LF_ = 0, int RG_ = 0>
 struct Tile {
     static constexpr int ES = ES_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MI = MI_, NS = NS_, BL = BL_;
     static constexpr int FT = FT_;
+    static constexpr int RG = RG_;
 #ifdef G355_FORCE_LOOP_FORM
     static constexpr int LF = G355_FORCE_LOOP_FORM;
 #else
@@ -308,11 +315,16 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                                : (const uint8_t *)pB + (bz * args.stride_b + (size_t)n0 * pldb + k_begin) * ES;
     const int a_rows_valid = (pM - m0 < BM) ? (pM - m0) : BM;
     const int b_rows_valid = (pN - n0 < BN) ? (pN - n0) : BN;      // K-contiguous B only
+    // (ragged instantiation: the window ends with the chunk that holds the last valid element, so that this
+    // chunk is fetched whole and trimmed in registers; rows are a whole number of chunks apart, so it lies
+    // inside the last row's leading-dimension span)
+    constexpr int EPC = 16 / ES;                                   // elements per 16-byte chunk
+    const int k_len_w = T::RG ? (k_len + EPC - 1) / EPC * EPC : k_len;
     const __amdgpu_buffer_rsrc_t rsA =
-        make_rsrc(Abase, (unsigned)((a_rows_valid - 1) * plda + k_len) * ES);
+        make_rsrc(Abase, (unsigned)((a_rows_valid - 1) * plda + k_len_w) * ES);
     const __amdgpu_buffer_rsrc_t rsB =
         make_rsrc(Bbase, (T::BL == 0) ? (unsigned)(k_len * pldb) * ES
-                                      : (unsigned)((b_rows_valid - 1) * pldb + k_len) * ES);
+                                      : (unsigned)((b_rows_valid - 1) * pldb + k_len_w) * ES);
 
     unsigned a_voff[T::A_LOADS], b_voff[T::B_LOADS];
     int a_kcol[T::A_LOADS], b_kcol[T::B_LOADS];
@@ -362,6 +374,58 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         }
     };
     constexpr int NL = T::A_LOADS + T::B_LOADS;   // load instructions per wave and slab
+
+    // Ragged instantiation: the same requests into registers (`fetch`), elements of a K-contiguous operand
+    // beyond the end of the K range cleared there, then written to the lane's LDS slot (`commit`).
+    i32x4 staged[T::RG ? NL : 1];
+    auto trim = [&](i32x4 v, int valid) {          // keep the first `valid` (< EPC) elements of a chunk
+        constexpr int EPD = 4 / ES;                // elements per dword
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int keep = valid - d * EPD;
+            const unsigned mask = keep >= EPD ? 0xffffffffu : keep <= 0 ? 0u : ((1u << (keep * 8 * ES)) - 1u);
+            v[d] = (int)((unsigned)v[d] & mask);
+        }
+        return v;
+    };
+    auto fetch = [&](int slab) {
+        const int kk = slab * BK;
+#pragma unroll
+        for (int l = 0; l < NL; ++l) {
+            if (l < T::A_LOADS) {
+                const int i = l, u = i * T::NW + wave;
+                if (T::A_UNITS % T::NW == 0 || u < T::A_UNITS) {
+                    const int valid = k_len - (a_kcol[i] + kk);
+                    const unsigned off = (valid > 0) ? a_voff[i] + (unsigned)(kk * ES) : OOB_OFFSET;
+                    i32x4 v = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsA, off, 0, 0));
+                    staged[T::RG ? l : 0] = (valid < EPC) ? trim(v, valid) : v;
+                }
+            } else {
+                const int i = l - T::A_LOADS, u = i * T::NW + wave;
+                if (T::B_UNITS % T::NW == 0 || u < T::B_UNITS) {
+                    if constexpr (T::BL == 0) {
+                        // rows beyond the K range lie beyond the window; columns beyond N only feed outputs that are not stored
+                        const unsigned off = b_voff[i] + (unsigned)kk * (unsigned)(pldb * ES);
+                        staged[T::RG ? l : 0] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsB, off, 0, 0));
+                    } else {
+                        const int valid = k_len - (b_kcol[i] + kk);
+                        const unsigned off = (valid > 0) ? b_voff[i] + (unsigned)(kk * ES) : OOB_OFFSET;
+                        i32x4 v = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsB, off, 0, 0));
+                        staged[T::RG ? l : 0] = (valid < EPC) ? trim(v, valid) : v;
+                    }
+                }
+            }
+        }
+    };
+    auto commit = [&](G355_LDS uint8_t *sbase) {
+#pragma unroll
+        for (int l = 0; l < NL; ++l) {
+            const bool is_a = l < T::A_LOADS;
+            const int i = is_a ? l : l - T::A_LOADS, u = i * T::NW + wave;
+            if (is_a ? (T::A_UNITS % T::NW == 0 || u < T::A_UNITS) : (T::B_UNITS % T::NW == 0 || u < T::B_UNITS))
+                *(G355_LDS i32x4 *)(sbase + (is_a ? 0 : T::A_BYTES) + u * 1024 + lane * 16) = staged[T::RG ? l : 0];
+        }
+    };
 
     // ---- fragment addressing (per lane, constant over the K loop) ----
     // column operand (from A): lane holds row m = lane % MI, k in [kg*KL, kg*KL + KL)
@@ -553,7 +617,34 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             until_barrier(next);
     };
 
-    if (kt_count > 0) {
+    if constexpr (T::RG) {
+        if (kt_count > 0) {
+            fetch(0);
+            commit(lds);
+            __syncthreads();
+            for (int kt = 0; kt < kt_count; ++kt) {
+                const G355_LDS uint8_t *cur = lds + (kt & 1) * T::STAGE;
+                if (kt + 1 < kt_count)
+                    fetch(kt + 1);                   // in flight during this slab's MFMAs
+#pragma unroll
+                for (int u = 0; u < NF; ++u)
+                    load_frag(cur, 0, 0, u);
+#pragma unroll
+                for (int kstep = 0; kstep < T::KSTEPS; ++kstep) {
+                    if (kstep + 1 < T::KSTEPS) {
+#pragma unroll
+                        for (int u = 0; u < NF; ++u)
+                            load_frag(cur, kstep + 1, (kstep + 1) & 1, u);
+                    }
+                    mma_kstep(kstep & 1);
+                }
+                // the other stage was last read in the previous iteration, which every wave has left
+                if (kt + 1 < kt_count)
+                    commit(lds + ((kt + 1) & 1) * T::STAGE);
+                __syncthreads();
+            }
+        }
+    } else if (kt_count > 0) {
 #pragma unroll
         for (int s = 0; s < T::NS; ++s)
 #pragma unroll
@@ -618,8 +709,10 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             const G355_LDS uint8_t *src = stg + (c / ST_CPR) * ST_ROW + (c % ST_CPR) * 32;
             const f32x4 lo = *(const G355_LDS f32x4 *)src, hi = *(const G355_LDS f32x4 *)(src + 16);
             if (out_mode != 0) {
+                // split-K slabs have rows of N rounded up to 8 floats (whole 32-byte stores also at a ragged edge)
+                const size_t nw = (size_t)(pN + 7) / 8 * 8;
                 float *dst = (out_mode == 1)
-                                 ? args.ws + ((bz * args.split_k + ks) * pM + m) * pN + n
+                                 ? args.ws + ((bz * args.split_k + ks) * pM + m) * nw + n
                                  : args.ws + ((size_t)(2 * blockIdx.x + seg) * BM + (m - m0)) * BN + (n - n0);
                 *(f32x4 *)dst = lo;
                 *(f32x4 *)(dst + 4) = hi;
@@ -640,7 +733,15 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                         o[r + 4] = (out_t)(hi[r] * alpha);
                     }
                 }
-                *(out8_t *)dst = o;
+                if (!T::RG || n + 8 <= pN) {
+                    *(out8_t *)dst = o;
+                } else {
+                    // ragged edge of C: nothing beyond column N - 1 is written
+#pragma unroll
+                    for (int r = 0; r < 8; ++r)
+                        if (n + r < pN)
+                            dst[r] = o[r];
+                }
             }
         }
     }

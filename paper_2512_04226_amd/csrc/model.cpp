@@ -540,9 +540,11 @@ void fill_cfg(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, 
     c->M = M;
     c->N = N;
     c->K = K;
-    c->lda = K;
-    c->ldb = b_layout ? K : N;
-    c->ldc = N;
+    // the smallest legal leading dimensions: rows start on 16-byte boundaries (C: 8 elements)
+    const int64_t per16 = 16 / elem_bytes(dtype);
+    c->lda = cdiv(K, per16) * per16;
+    c->ldb = cdiv(b_layout ? K : N, per16) * per16;
+    c->ldc = cdiv(N, 8) * 8;
     c->kernel_id = kernel_id;
     c->block_m = (uint16_t)v.block_m;
     c->block_n = (uint16_t)v.block_n;

@@ -1,6 +1,7 @@
 // gemm_run and the split-K workspace: the only entry points that touch the GPU.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstddef>
 #include <cstring>
 #include <mutex>
@@ -16,22 +17,38 @@ namespace g355 {
 // Sum the split-K slabs in slice order (deterministic), scale, round to bf16.
 // Scale four sums, add beta * C when beta != 0 (C is read before it is overwritten), round to
 // the 16-bit output format (f16 != 0: IEEE fp16, else bf16) and store.
-__device__ inline void scale_round_store(f32x4 s, float alpha, float beta, void *dst, int f16)
+__device__ inline void scale_round_store(f32x4 s, float alpha, float beta, void *dst, int f16, int count = 4)
 {
+    // count < 4: the ragged right edge of C -- only the first `count` outputs exist; C is read (beta != 0)
+    // as a whole quad all the same, which stays inside the row's leading dimension
     if (f16) {
         f16x4 o;
         const f16x4 c = (beta != 0.f) ? *(const f16x4 *)dst : f16x4{0, 0, 0, 0};
 #pragma unroll
         for (int r = 0; r < 4; ++r)
             o[r] = (beta != 0.f) ? (_Float16)__builtin_fmaf(beta, (float)c[r], s[r] * alpha) : (_Float16)(s[r] * alpha);
-        *(f16x4 *)dst = o;
+        if (count >= 4) {
+            *(f16x4 *)dst = o;
+        } else {
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+                if (r < count)
+                    ((_Float16 *)dst)[r] = o[r];
+        }
     } else {
         bf16x4 o;
         const bf16x4 c = (beta != 0.f) ? *(const bf16x4 *)dst : bf16x4{0, 0, 0, 0};
 #pragma unroll
         for (int r = 0; r < 4; ++r)
             o[r] = (beta != 0.f) ? (__bf16)__builtin_fmaf(beta, (float)c[r], s[r] * alpha) : (__bf16)(s[r] * alpha);
-        *(bf16x4 *)dst = o;
+        if (count >= 4) {
+            *(bf16x4 *)dst = o;
+        } else {
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+                if (r < count)
+                    ((__bf16 *)dst)[r] = o[r];
+        }
     }
 }
 
@@ -39,19 +56,23 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
                                                             int split_k, float alpha, float beta, int f16,
                                                             long long stride_c)
 {
-    ws += (size_t)blockIdx.y * split_k * M * N;     // problem of the batch
+    // slab rows are N rounded up to 8 floats apart (the kernels store whole 32-byte pieces also at a ragged edge)
+    const size_t nw = (size_t)(N + 7) / 8 * 8;
+    ws += (size_t)blockIdx.y * split_k * M * nw;     // problem of the batch
     C += (size_t)blockIdx.y * stride_c;
-    const size_t quads = (size_t)M * (N / 4);
-    const size_t slab = (size_t)M * N;
+    const size_t qpr = (size_t)(N + 3) / 4;          // quads per row, the last one possibly partial
+    const size_t quads = (size_t)M * qpr;
+    const size_t slab = (size_t)M * nw;
     for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += (size_t)gridDim.x * blockDim.x) {
-        const size_t m = q / (N / 4), n = (q % (N / 4)) * 4;
-        const float *p = ws + m * N + n;
+        const size_t m = q / qpr, n = (q % qpr) * 4;
+        const float *p = ws + m * nw + n;
         f32x4 s = *(const f32x4 *)p;
         for (int k = 1; k < split_k; ++k) {
             f32x4 t = *(const f32x4 *)(p + k * slab);
             s += t;
         }
-        scale_round_store(s, alpha, beta, C + m * ldc + n, f16);
+        const int count = (int)((size_t)N - n < 4 ? (size_t)N - n : 4);
+        scale_round_store(s, alpha, beta, C + m * ldc + n, f16, count);
     }
 }
 
@@ -106,7 +127,7 @@ __global__ __launch_bounds__(256) void streamk_sum_kernel(const float *__restric
         s = part[0][quad];
     }
     if (r == 0 && live)
-        scale_round_store(s, alpha, beta, C + (size_t)m * ldc + n, f16);
+        scale_round_store(s, alpha, beta, C + (size_t)m * ldc + n, f16, N - n < 4 ? N - n : 4);
 }
 
 }  // namespace g355
@@ -150,7 +171,7 @@ int scratch_of_current_device(void **out)
     return GEMM_OK;
 }
 
-const VariantFns &launcher_of(int dtype, int id, int bl)
+const VariantFns &launcher_of(int dtype, int id, int bl, int ragged)
 {
 #define G355_COUNT(...) +1
     constexpr int n_b0 = 0 G355_VARIANTS_BF16_0(G355_COUNT);
@@ -162,33 +183,33 @@ const VariantFns &launcher_of(int dtype, int id, int bl)
 #undef G355_COUNT
     if (dtype == GEMM_FP16) {
         if (id < n_b0)
-            return kLaunchFp16_0(id, bl);
+            return kLaunchFp16_0(id, bl, ragged);
         if (id < n_b0 + n_b1)
-            return kLaunchFp16_1(id - n_b0, bl);
+            return kLaunchFp16_1(id - n_b0, bl, ragged);
         if (id < n_b0 + n_b1 + n_b2)
-            return kLaunchFp16_2(id - n_b0 - n_b1, bl);
+            return kLaunchFp16_2(id - n_b0 - n_b1, bl, ragged);
         if (id < n_b0 + n_b1 + n_b2 + n_b3)
-            return kLaunchFp16_3(id - n_b0 - n_b1 - n_b2, bl);
+            return kLaunchFp16_3(id - n_b0 - n_b1 - n_b2, bl, ragged);
         if (id < n_b0 + n_b1 + n_b2 + n_b3 + n_b4)
-            return kLaunchFp16_4(id - n_b0 - n_b1 - n_b2 - n_b3, bl);
-        return kLaunchFp16_5(id - n_b0 - n_b1 - n_b2 - n_b3 - n_b4, bl);
+            return kLaunchFp16_4(id - n_b0 - n_b1 - n_b2 - n_b3, bl, ragged);
+        return kLaunchFp16_5(id - n_b0 - n_b1 - n_b2 - n_b3 - n_b4, bl, ragged);
     }
     if (dtype == GEMM_BF16) {
         if (id < n_b0)
-            return kLaunchBf16_0(id, bl);
+            return kLaunchBf16_0(id, bl, ragged);
         if (id < n_b0 + n_b1)
-            return kLaunchBf16_1(id - n_b0, bl);
+            return kLaunchBf16_1(id - n_b0, bl, ragged);
         if (id < n_b0 + n_b1 + n_b2)
-            return kLaunchBf16_2(id - n_b0 - n_b1, bl);
+            return kLaunchBf16_2(id - n_b0 - n_b1, bl, ragged);
         if (id < n_b0 + n_b1 + n_b2 + n_b3)
-            return kLaunchBf16_3(id - n_b0 - n_b1 - n_b2, bl);
+            return kLaunchBf16_3(id - n_b0 - n_b1 - n_b2, bl, ragged);
         if (id < n_b0 + n_b1 + n_b2 + n_b3 + n_b4)
-            return kLaunchBf16_4(id - n_b0 - n_b1 - n_b2 - n_b3, bl);
-        return kLaunchBf16_5(id - n_b0 - n_b1 - n_b2 - n_b3 - n_b4, bl);
+            return kLaunchBf16_4(id - n_b0 - n_b1 - n_b2 - n_b3, bl, ragged);
+        return kLaunchBf16_5(id - n_b0 - n_b1 - n_b2 - n_b3 - n_b4, bl, ragged);
     }
     if (id < n_f0)
-        return kLaunchFp8_0(id, bl);
-    return kLaunchFp8_1(id - n_f0, bl);
+        return kLaunchFp8_0(id, bl, ragged);
+    return kLaunchFp8_1(id - n_f0, bl, ragged);
 }
 
 inline int64_t cdiv64(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -308,7 +329,7 @@ static int run_impl(const gemm_cfg *cfg, const void *A, const void *B, void *C, 
     a.tiles_n = (int)tiles_n;
     a.split_k = cfg->split_k;
     a.k_per_split = (int)kps;
-    a.group_m = cfg->group_m;
+    a.group_m = (int)std::min<int64_t>(cfg->group_m, tiles_m);   // a band taller than the grid is the whole grid
     a.xcd_remap = cfg->xcd_remap ? 1 : 0;
     a.n_xcd = hw.n_xcd;
     a.sk = sk;   // workers == 0 unless stream-K
@@ -321,7 +342,9 @@ static int run_impl(const gemm_cfg *cfg, const void *A, const void *B, void *C, 
 
     hipStream_t stream = (hipStream_t)hip_stream;
     const int f16 = (dtype == GEMM_FP16) ? 1 : 0;
-    if (launcher_of(dtype, cfg->kernel_id, cfg->b_layout).launch(a, stream) != hipSuccess) {
+    // an N or K that is not a whole number of 16-byte chunks runs the instantiation that trims in registers
+    const int ragged = (cfg->N % per16 || cfg->K % per16) ? 1 : 0;
+    if (launcher_of(dtype, cfg->kernel_id, cfg->b_layout, ragged).launch(a, stream) != hipSuccess) {
         (void)hipGetLastError();
         return GEMM_ERR_HIP;
     }
@@ -346,7 +369,7 @@ static int run_impl(const gemm_cfg *cfg, const void *A, const void *B, void *C, 
         if (hipGetLastError() != hipSuccess)
             return GEMM_ERR_HIP;
     } else if (cfg->split_k > 1) {
-        const size_t quads = (size_t)cfg->M * (size_t)(cfg->N / 4);
+        const size_t quads = (size_t)cfg->M * (size_t)((cfg->N + 3) / 4);
         size_t blocks = (quads + 255) / 256;
         if (blocks > 256 * 8)
             blocks = 256 * 8;
@@ -389,7 +412,7 @@ extern "C" int gemm_variant_occupancy(int dtype, int variant, int b_layout, int 
     if (b_layout != GEMM_B_ROW_MAJOR && b_layout != GEMM_B_K_CONTIGUOUS)
         return GEMM_ERR_CFG_ILLEGAL;
     (void)hipGetLastError();
-    if (launcher_of(dtype, variant, b_layout).occupancy(blocks_per_cu) != hipSuccess) {
+    if (launcher_of(dtype, variant, b_layout, 0).occupancy(blocks_per_cu) != hipSuccess) {
         (void)hipGetLastError();
         return GEMM_ERR_HIP;
     }
@@ -413,13 +436,17 @@ extern "C" int gemm_run_grouped(const gemm_cfg *cfg, int n_groups, const gemm_gr
         return GEMM_ERR_ALIGN;
     const int X = grouped_xcds(cfg);
     int64_t slots = 0;
+    int ragged = 0;   // one group with a ragged N or K sends the whole launch through the trimming instantiation
+    const int per16 = 16 / elem_bytes(cfg->dtype);
     for (int i = 0; i < n_groups; ++i) {
         rc = check_group_rec(cfg, &host_table[i], slots);
         if (rc)
             return rc;
-        slots += group_slots(host_table[i].tiles_m * host_table[i].tiles_n, X);
+        slots += group_slots((int64_t)host_table[i].tiles_m * host_table[i].tiles_n, X);
         if (slots * X >= ((int64_t)1 << 31))
             return GEMM_ERR_SHAPE;
+        if (host_table[i].M > 0 && (host_table[i].N % per16 || host_table[i].K % per16))
+            ragged = 1;
     }
     if (slots == 0)
         return GEMM_OK;   // every group is empty
@@ -438,7 +465,7 @@ extern "C" int gemm_run_grouped(const gemm_cfg *cfg, int n_groups, const gemm_gr
     a.batch = 1;
     a.groups = (const GroupRec *)dev_table;
     a.n_groups = n_groups;
-    if (launcher_of(cfg->dtype, cfg->kernel_id, cfg->b_layout).launch(a, (hipStream_t)hip_stream) != hipSuccess) {
+    if (launcher_of(cfg->dtype, cfg->kernel_id, cfg->b_layout, ragged).launch(a, (hipStream_t)hip_stream) != hipSuccess) {
         (void)hipGetLastError();
         return GEMM_ERR_HIP;
     }

@@ -64,9 +64,13 @@ def test_select_argument_errors():
     assert f(0, 512, 512, 0, ctypes.byref(cfg)) == -2          # shape
     assert f(512, -1, 512, 0, ctypes.byref(cfg)) == -2
     assert f(512, 512, 512, 7, ctypes.byref(cfg)) == -3        # dtype
-    assert f(512, 516, 512, 0, ctypes.byref(cfg)) == -5        # N not a multiple of 8 (bf16)
-    assert f(512, 512, 520, 1, ctypes.byref(cfg)) == -5        # K not a multiple of 16 (fp8)
-    assert f(1, 8, 8, 0, ctypes.byref(cfg)) == 0               # smallest legal problem
+    # selection is total on M, N, K >= 1; the default leading dimensions are rounded up to 16 bytes
+    assert f(512, 516, 512, 0, ctypes.byref(cfg)) == 0 and (cfg.lda, cfg.ldb, cfg.ldc) == (512, 520, 520)
+    assert f(512, 512, 520, 1, ctypes.byref(cfg)) == 0 and (cfg.lda, cfg.ldb, cfg.ldc) == (528, 512, 512)
+    assert f(1, 8, 8, 0, ctypes.byref(cfg)) == 0
+    assert f(1, 1, 1, 0, ctypes.byref(cfg)) == 0 and (cfg.lda, cfg.ldb, cfg.ldc) == (8, 8, 8)   # smallest problem
+    assert f(5, 1, 7, 1, ctypes.byref(cfg)) == 0 and (cfg.lda, cfg.ldb, cfg.ldc) == (16, 16, 8)
+    assert g._lib.gemm_select_ex(33, 1001, 72, 0, 1, ctypes.byref(cfg)) == 0 and (cfg.lda, cfg.ldb, cfg.ldc) == (72, 72, 1008)
     assert f(1 << 31, 512, 512, 0, ctypes.byref(cfg)) == -2
     for code in range(0, -10, -1):
         assert g.gemm_strerror(code) != "unknown status"

@@ -128,8 +128,8 @@ def test_grouped_argument_errors():
     assert f(5000, probs, 0, 0, ctypes.byref(cfg)) == -2
     assert f(2, probs, 9, 0, ctypes.byref(cfg)) == -3
     assert f(2, probs, 0, 3, ctypes.byref(cfg)) == -4
-    bad = probs_with_fake_pointers([(300, 1020, 512), (40, 512, 1024)])
-    assert f(2, bad, 0, 0, ctypes.byref(cfg)) == -5             # N not a multiple of 8
+    ragged = probs_with_fake_pointers([(300, 1020, 512), (40, 512, 1023)])
+    assert f(2, ragged, 0, 0, ctypes.byref(cfg)) == 0           # N and K need not be whole 16-byte chunks
     neg = probs_with_fake_pointers([(-1, 1024, 512), (40, 512, 1024)])
     assert f(2, neg, 0, 0, ctypes.byref(cfg)) == -2
     empty = probs_with_fake_pointers([(0, 1024, 512), (0, 512, 1024)])
