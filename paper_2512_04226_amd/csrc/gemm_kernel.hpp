@@ -84,6 +84,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // barrier the refill two loads per MFMA, then in each k-step the fragment reads of the next one a
 // few per MFMA over the first half of its MFMAs, so that a read has half a k-step to land (the
 // compiler alone issues reads next to their uses, which costs most with one wave per SIMD).
+// 4: as 3, but the refill is spread evenly over ALL the MFMAs of the k-step after the barrier (one load every
+// MN / NL matrix instructions) instead of going out as a burst: the vector-memory path of a CU takes 64 bytes
+// per clock, a slab's loads are 16 clocks of it each, and a wave whose load finds that path's queue full
+// cannot issue the MFMAs behind it either.
 // Building with -DG355_FORCE_LOOP_FORM=k gives every variant form k (how the forms are compared).
 // RG_: 1 = the instantiation for shapes whose N or K is not a whole number of 16-byte chunks.  A chunk that
 // holds the end of a row of a K-contiguous operand then also holds bytes that are not part of the matrix
@@ -101,7 +105,7 @@ struct Tile {
 #else
     static constexpr int LF = LF_;
 #endif
-    static_assert(LF >= 0 && LF <= 3, "unknown K-loop form");
+    static_assert(LF >= 0 && LF <= 4, "unknown K-loop form");
     static_assert(FT == 0 || ES == 2, "fp16 is a 16-bit input type");
     static constexpr int NW = WM * WN;
     static constexpr int NT = WM * WN * 64;
@@ -219,6 +223,24 @@ __device__ __forceinline__ void sched_fills_then_mfma()
         __builtin_amdgcn_sched_group_barrier(0x020, A, 0);
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         sched_fills_then_mfma<COUNT - 1, A>();
+    }
+}
+
+// K-loop form 4, the k-step after the barrier: MFMA number I of MN is preceded by its even share of the NL
+// refill loads and, in the first half, of the NFR fragment reads.
+template <int I, int MN, int NL, int NFR>
+__device__ __forceinline__ void sched_spread_fills()
+{
+    if constexpr (I < MN) {
+        constexpr int H = MN > 1 ? MN / 2 : 1;
+        constexpr int loads = (I + 1) * NL / MN - I * NL / MN;
+        constexpr int reads = I < H ? (I + 1) * NFR / H - I * NFR / H : 0;
+        if constexpr (loads > 0)
+            __builtin_amdgcn_sched_group_barrier(0x020, loads, 0);
+        if constexpr (reads > 0)
+            __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        sched_spread_fills<I + 1, MN, NL, NFR>();
     }
 }
 
@@ -566,7 +588,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             for (int u = 0; u < NF; ++u)
                 load_frag(cur, kstep + 1, (kstep + 1) & 1, u);
             mma_kstep(kstep & 1);
-            if constexpr (LF == 3) {
+            if constexpr (LF == 3 || LF == 4) {
                 sched_reads_then_mfma<RD_PAIRS, RD_A>();
                 if constexpr (RD_REM > 0) {
                     __builtin_amdgcn_sched_group_barrier(0x100, RD_REM, 0);
@@ -592,6 +614,8 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         for (int u = 0; u < NF; ++u)
             load_frag(next, 0, 0, u);
         mma_kstep((T::KSTEPS - 1) & 1);
+        if constexpr (LF == 4)
+            sched_spread_fills<0, MN, NL, NFR>();
         if constexpr (LF == 3) {
             // the refill two loads per MFMA, then the fragment reads as in the other k-steps
             constexpr int FP = (NL + 1) / 2 < MN / 2 ? (NL + 1) / 2 : MN / 2;     // MFMAs that carry fills
