@@ -103,13 +103,22 @@ def secondary(also, g, wl, np, torch, dev, sizes, timed_us, ensure_ws):
     also["fp16_%d_b_k_contiguous" % n_big] = {"tflops": 2.0 * n_big ** 3 / us * 1e-6, "picked": cfg_h.describe()}
     del Ah, Bh, dAh, dBh
     scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
-    also["mfma_only_bf16_tflops"] = g.gemm_probe_mfma(g.GEMM_BF16, 32, scratch)
+    # the matrix cores alone, settled (30 ms untimed, 20 ms timed): on constant operands and on per-lane different
+    # N(0,1)-like operands, for both bf16 instruction shapes -- the second is the ceiling the power limit leaves
+    # the benchmark's data
+    also["mfma_only_bf16_tflops"] = g.gemm_probe_mfma_ex(g.GEMM_BF16, 32, 0, scratch)
+    also["mfma_only_bf16_random_tflops"] = {"32x32x16": g.gemm_probe_mfma_ex(g.GEMM_BF16, 32, 1, scratch),
+                                            "16x16x32": g.gemm_probe_mfma_ex(g.GEMM_BF16, 16, 1, scratch)}
+    also["mfma_only_fp8_random_tflops"] = {"32x32x64": g.gemm_probe_mfma_ex(g.GEMM_FP8_E4M3, 32, 1, scratch),
+                                           "16x16x128": g.gemm_probe_mfma_ex(g.GEMM_FP8_E4M3, 16, 1, scratch)}
     n8 = 8192
     Aq, Bq, sa, sb = wl.config4(n8)
     cfg8 = g.gemm_select(n8, n8, n8, g.GEMM_FP8_E4M3)
     cfg8.alpha = float(sa) * float(sb)
     us = timed_us(cfg8, torch.from_numpy(Aq).cuda(), torch.from_numpy(Bq).cuda(), dev[n8][2])
     also["fp8_8192"] = {"tflops": 2.0 * n8 ** 3 / us * 1e-6, "frac_of_fp8_peak": 2.0 * n8 ** 3 / us * 1e-6 / PEAK_TFLOPS["fp8"],
+                        "frac_of_measured_ceiling": 2.0 * n8 ** 3 / us * 1e-6 / also["mfma_only_fp8_random_tflops"][
+                            "32x32x64" if cfg8.mfma == 32 else "16x16x128"],
                         "picked": cfg8.describe()}
     del Aq, Bq
     Ms, Ns, Ks = 16, 28672, 8192
@@ -281,6 +290,10 @@ def main():
         return settled_us(torch, lambda: g.gemm_run(cfg, dA, dB, dC))
 
     also = {}
+    # the same step in the chip's settled state (the driver's short default run sits in the throttling transient
+    # that follows an idle gap: `value` is what its flags time, this is the sustained rate)
+    also["settled_value"] = flops_step / settled_us(torch, step) * 1e-6
+    also["settled_8192_kernel_ms"] = settled_us(torch, lambda: g.gemm_run(cfg_big, *dev[big])) * 1e-3
     if not args.brief:
         secondary(also, g, wl, np, torch, dev, sizes, timed_us, ensure_ws)
 
@@ -297,6 +310,12 @@ def main():
                      "frac": achieved / PEAK_TFLOPS["bf16"], "kernel": "gemm_kernel<%s> on 8192^3" % cfg_big.describe(),
                      "avg_launch_ms": kern_ms, "traffic": read_traffic("gemm_bf16_8192_counters.txt")},
     }
+    ceiling = (also.get("mfma_only_bf16_random_tflops") or {}).get("16x16x32" if cfg_big.mfma == 16 else "32x32x16")
+    if ceiling:
+        # against what the matrix cores alone sustain on N(0,1)-like operands under this chip's power limit
+        out["roofline"]["measured_ceiling"] = ceiling
+        out["roofline"]["frac_of_measured_ceiling"] = achieved / ceiling
+        out["roofline"]["settled_frac"] = 2.0 * big ** 3 / (also["settled_8192_kernel_ms"] * 1e-3) * 1e-12 / PEAK_TFLOPS["bf16"]
     out["also"] = also
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(host[big][0], host[big][1], args.cpu_rows)

@@ -220,6 +220,49 @@ def compare_loop_forms(lib_paths, n=8192, passes=7):
               flush=True)
 
 
+def decompose(lib_paths, n=8192):
+    """Where a K slab's time goes: the large tiles of each datatype on n^3, timed in a normal build and in the
+    timing-only diagnostic builds without the refills, without the fragment reads, and without both
+    (LIB_FULL LIB_SKIP_FILL LIB_SKIP_FRAG LIB_SKIP_BOTH, all built with the same forced K-loop form), on
+    N(0,1)-like and on all-zero operands (the latter take the power limit out of the picture)."""
+    names = ("full", "no fill", "no fragment reads", "neither")
+    libs = [ctypes.CDLL(p) for p in lib_paths]
+    for lib in libs:
+        lib.gemm_run.restype = ctypes.c_int
+
+    def settled(lib, cfg, A, B, C):
+        def run():
+            if lib.gemm_run(ctypes.byref(cfg), g._ptr(A), g._ptr(B), g._ptr(C), ctypes.c_void_p(g._stream_handle(None))) != 0:
+                raise RuntimeError("gemm_run failed")
+        for _ in range(40):
+            run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(30):
+            run()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / 30
+
+    picks = {g.GEMM_BF16: ("256x256x64 w2x4 mfma16 s2 split1 ", "256x256x64 w2x4 mfma32 s2 split1 ", "256x256x32 w2x4 mfma32 s4 split1 ",
+                           "256x256x32 w2x4 mfma32 s5 split1 ", "256x128x64 w2x4 mfma16 s3 split1 ", "128x128x64 w2x4 mfma16 s2 split1 ",
+                           "128x128x64 w2x4 mfma16 s4 split1 "),
+             g.GEMM_FP8_E4M3: ("256x256x128 w2x4 mfma32 s2 split1 ", "128x128x128 w2x2 mfma32 s2 split1 ")}
+    for dtype, label in ((g.GEMM_BF16, "bf16"), (g.GEMM_FP8_E4M3, "fp8")):
+        for zeros in (False, True):
+            A, B, C = make_operands(n, n, n, dtype, normal=True)
+            if zeros:
+                A.zero_()
+                B.zero_()
+            for idx in range(g.gemm_cfg_count(dtype)):
+                c = g.gemm_cfg_at(idx, n, n, n, dtype)
+                if c is None or not c.describe().startswith(picks[dtype]):
+                    continue
+                us = [settled(lib, c, A, B, C) for lib in libs]
+                print("%-4s %-8s %-38s %s" % (label, "zeros" if zeros else "random", c.describe(), "   ".join(
+                    "%s %.0f us (%.0f TFLOP/s)" % (nm, t, 2.0 * n ** 3 / t * 1e-6) for nm, t in zip(names, us))), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--n", type=int, default=8192)
@@ -227,7 +270,12 @@ def main():
     ap.add_argument("--rates-only", action="store_true", help="run the probes, print the descriptor fields, stop")
     ap.add_argument("--loop-forms", nargs="+", metavar="LIB",
                     help="compare builds of the library (one per forced K-loop form) instead of calibrating")
+    ap.add_argument("--decompose", nargs=4, metavar="LIB",
+                    help="time the large tiles in four builds: normal, -DG355_DIAG_SKIP_FILL, -DG355_DIAG_SKIP_FRAG, both")
     args = ap.parse_args()
+    if args.decompose:
+        decompose(args.decompose, args.n)
+        return
     if args.loop_forms:
         compare_loop_forms(args.loop_forms, args.n)
         return

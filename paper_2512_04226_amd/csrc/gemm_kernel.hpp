@@ -89,6 +89,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // per clock, a slab's loads are 16 clocks of it each, and a wave whose load finds that path's queue full
 // cannot issue the MFMAs behind it either.
 // Building with -DG355_FORCE_LOOP_FORM=k gives every variant form k (how the forms are compared).
+// Timing-only diagnostic builds (their RESULTS ARE WRONG; every access stays in bounds and every wait ends):
+// -DG355_DIAG_SKIP_FILL leaves the refills out of the K loop (the ring keeps its first NS slabs),
+// -DG355_DIAG_SKIP_FRAG the fragment reads (the MFMAs reuse the first slab's fragments); timed against a
+// normal build they show what the fill and the LDS reads cost a slab (calibrate.py --decompose).
 // RG_: 1 = the instantiation for shapes whose N or K is not a whole number of 16-byte chunks.  A chunk that
 // holds the end of a row of a K-contiguous operand then also holds bytes that are not part of the matrix
 // (padding up to the leading dimension, which may be anything, NaN included), so slabs go through registers,
@@ -584,9 +588,11 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     auto until_barrier = [&](const G355_LDS uint8_t *cur) __attribute__((always_inline)) {
 #pragma unroll
         for (int kstep = 0; kstep < T::KSTEPS - 1; ++kstep) {
+#ifndef G355_DIAG_SKIP_FRAG
 #pragma unroll
             for (int u = 0; u < NF; ++u)
                 load_frag(cur, kstep + 1, (kstep + 1) & 1, u);
+#endif
             mma_kstep(kstep & 1);
             if constexpr (LF == 3 || LF == 4) {
                 sched_reads_then_mfma<RD_PAIRS, RD_A>();
@@ -603,16 +609,20 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     // from the barrier of slab kt to the barrier of slab kt + 1
     auto after_barrier = [&](G355_LDS uint8_t *__restrict__ freed, const G355_LDS uint8_t *__restrict__ next, int kt)
                              __attribute__((always_inline)) {
+#ifndef G355_DIAG_SKIP_FILL
 #pragma unroll
         for (int l = 0; l < NL; ++l)
             issue_one(l, kt + T::NS, freed);
+#endif
         // form 2: no memory instruction may be scheduled across this point (ALU and MFMA
         // instructions may), or the refill drifts down the iteration it has to land in
         if constexpr (LF == 2)
             __builtin_amdgcn_sched_barrier(0xF);
+#ifndef G355_DIAG_SKIP_FRAG
 #pragma unroll
         for (int u = 0; u < NF; ++u)
             load_frag(next, 0, 0, u);
+#endif
         mma_kstep((T::KSTEPS - 1) & 1);
         if constexpr (LF == 4)
             sched_spread_fills<0, MN, NL, NFR>();
@@ -678,6 +688,11 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
 #pragma unroll
         for (int u = 0; u < NF; ++u)
             load_frag(lds, 0, 0, u);
+#ifdef G355_DIAG_SKIP_FRAG
+#pragma unroll
+        for (int u = 0; u < NF; ++u)
+            load_frag(lds, 1, 1, u);      // both register buffers hold real fragments of the first slab
+#endif
         until_barrier(lds);
         int stage = 0;                         // stage of slab kt
         // forms 1 and 2 peel the last slab off (see Tile)
