@@ -749,7 +749,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             const f32x4 lo = *(const G355_LDS f32x4 *)src, hi = *(const G355_LDS f32x4 *)(src + 16);
             if (out_mode != 0) {
                 // split-K slabs have rows of N rounded up to 8 floats (whole 32-byte stores also at a ragged edge)
-                const size_t nw = (size_t)(pN + 7) / 8 * 8;
+                const size_t nw = T::RG ? (size_t)(pN + 7) / 8 * 8 : (size_t)pN;   // (N is a multiple of 8 otherwise)
                 float *dst = (out_mode == 1)
                                  ? args.ws + ((bz * args.split_k + ks) * pM + m) * nw + n
                                  : args.ws + ((size_t)(2 * blockIdx.x + seg) * BM + (m - m0)) * BN + (n - n0);
