@@ -67,6 +67,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define G355_LDS __attribute__((address_space(3)))
+// Cache-policy operand of the slab loads: 0 = default, 2 = the instruction's `nt` (non-temporal) modifier.
+#define G355_LOAD_DEFAULT 0
+#define G355_LOAD_STREAM 2
 
 // BL_: storage of B.  0: K x N row-major (N-contiguous).  1: N x K row-major (K-contiguous, the
 // layout of the paper's own runs, Section V): B is then staged and read exactly like A.
@@ -91,8 +94,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // Building with -DG355_FORCE_LOOP_FORM=k gives every variant form k (how the forms are compared).
 // Timing-only diagnostic builds (their RESULTS ARE WRONG; every access stays in bounds and every wait ends):
 // -DG355_DIAG_SKIP_FILL leaves the refills out of the K loop (the ring keeps its first NS slabs),
-// -DG355_DIAG_SKIP_FRAG the fragment reads (the MFMAs reuse the first slab's fragments); timed against a
-// normal build they show what the fill and the LDS reads cost a slab (calibrate.py --decompose).
+// -DG355_DIAG_SKIP_FRAG the fragment reads (the MFMAs reuse the first slab's fragments), -DG355_DIAG_SKIP_MFMA the
+// matrix instructions; timed against a normal build they show what the fill, the LDS reads and the MFMAs cost a
+// slab on their own and together (calibrate.py --decompose).
 // RG_: 1 = the instantiation for shapes whose N or K is not a whole number of 16-byte chunks.  A chunk that
 // holds the end of a row of a K-contiguous operand then also holds bytes that are not part of the matrix
 // (padding up to the leading dimension, which may be anything, NaN included), so slabs go through registers,
@@ -113,6 +117,12 @@ struct Tile {
     static_assert(FT == 0 || ES == 2, "fp16 is a 16-bit input type");
     static constexpr int NW = WM * WN;
     static constexpr int NT = WM * WN * 64;
+    // An operand that only ONE tile row (B) or tile column (A) of the grid reads is read once in all: its slab
+    // loads then carry the non-temporal hint, so that the stream does not push the other operand's panels (which
+    // every workgroup re-reads) out of the L2 (weight streaming at M <= BLOCK_M: 5-10 % on the HBM-bound shapes).
+    // Decided per launch (per group); compiled only into tiles of at most 128 rows / columns, so that the
+    // instruction streams of the large compute-bound tiles stay as they were tuned.
+    static constexpr bool STREAMABLE_B = BM <= 128, STREAMABLE_A = BN <= 128;
     static constexpr int WTM = BM / WM, WTN = BN / WN;      // wave tile
     static constexpr int TM = WTM / MI, TN = WTN / MI;      // MFMA tiles per wave
     static constexpr int KI = (ES == 2) ? (MI == 32 ? 16 : 32) : (MI == 32 ? 64 : 128);  // MI_K
@@ -268,11 +278,15 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     int pM = args.M, pN = args.N, pK = args.K, plda = args.lda, pldb = args.ldb, pldc = args.ldc;
     int g_tm = 0, g_tn = 0;
     const bool grouped = args.n_groups > 0;
+    // one tile row: B is read once; one tile column: A is read once (see Tile::STREAMABLE_*)
+    bool stream_a = args.tiles_n == 1, stream_b = args.tiles_m == 1;
     if (grouped) {
         const int X = args.xcd_remap ? args.n_xcd : 1;
         const int x = (int)blockIdx.x % X, q = (int)blockIdx.x / X;
         const GroupRec *r = args.groups + group_of(args.groups, args.n_groups, q);
         const int tiles_m = uniform_i32(r->tiles_m), tiles_n = uniform_i32(r->tiles_n);
+        stream_a = tiles_n == 1;
+        stream_b = tiles_m == 1;
         const int t = group_tile(tiles_m * tiles_n, X, x, q - uniform_i32(r->tile_start));
         if (t < 0)
             return;   // idle slot of this XCD (the whole workgroup leaves: nothing was started)
@@ -384,7 +398,10 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             const int i = l, u = i * T::NW + wave;
             if (T::A_UNITS % T::NW == 0 || u < T::A_UNITS) {
                 const unsigned off = (a_kcol[i] + kk < k_len) ? a_voff[i] + (unsigned)(kk * ES) : OOB_OFFSET;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (G355_LDS void *)(sbase + u * 1024), 16, off, 0, 0, 0);
+                if (T::STREAMABLE_A && stream_a)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (G355_LDS void *)(sbase + u * 1024), 16, off, 0, 0, G355_LOAD_STREAM);
+                else
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (G355_LDS void *)(sbase + u * 1024), 16, off, 0, 0, G355_LOAD_DEFAULT);
             }
         } else {
             const int i = l - T::A_LOADS, u = i * T::NW + wave;
@@ -394,8 +411,12 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                     off = b_voff[i] + (unsigned)kk * (unsigned)(pldb * ES);
                 else
                     off = (b_kcol[i] + kk < k_len) ? b_voff[i] + (unsigned)(kk * ES) : OOB_OFFSET;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (G355_LDS void *)(sbase + T::A_BYTES + u * 1024), 16, off,
-                                                         0, 0, 0);
+                if (T::STREAMABLE_B && stream_b)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (G355_LDS void *)(sbase + T::A_BYTES + u * 1024), 16, off,
+                                                             0, 0, G355_LOAD_STREAM);
+                else
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (G355_LDS void *)(sbase + T::A_BYTES + u * 1024), 16, off,
+                                                             0, 0, G355_LOAD_DEFAULT);
             }
         }
     };
@@ -579,9 +600,13 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     // overlap, and the waits that order refills against reads are the explicit ones of publish().
     G355_LDS uint8_t *const lds = (G355_LDS uint8_t *)smem;
     auto mma_kstep = [&](int buf) __attribute__((always_inline)) {
+#ifndef G355_DIAG_SKIP_MFMA
 #pragma unroll
         for (int m = 0; m < T::TM * T::TN; ++m)
             mma_one(buf, m / T::TM, m % T::TM);
+#else
+        (void)buf;
+#endif
     };
     // k-steps 0 .. KSTEPS-2 of the slab in `cur` (its first fragments are in registers), then the
     // slab's barrier
