@@ -51,7 +51,10 @@ int main()
     gemm_prediction p;
     long acc = 0, n_sk = 0;
     for (int it = 0; it < 1500; ++it) {
-        const long M = 1 + rnd(16384), N = 16 * (1 + rnd(1024)), K = 16 * (1 + rnd(1024));
+        // every fourth shape has N and K that are not whole 16-byte chunks
+        const bool ragged = it % 4 == 3;
+        const long M = 1 + rnd(16384), N = ragged ? 1 + rnd(16384) : 16 * (1 + rnd(1024)),
+                   K = ragged ? 1 + rnd(16384) : 16 * (1 + rnd(1024));
         const int dt = it % 3, bl = (it / 3) & 1;
         const long batch = (it % 5 == 0) ? 1 + rnd(64) : 1;
         if (gemm_select_batched(M, N, K, batch, dt, bl, &c) != GEMM_OK) {
@@ -154,6 +157,71 @@ int main()
             return 5;
         if (gemm_select(4096 + 256 * id, 4096, 4096, 0, &c) != GEMM_OK)
             return 6;
+        gemm_hw_reset();
+    }
+    // shapes at the documented limits: every answer is a status, and an accepted cfg predicts and plans
+    {
+        const long big = 1L << 30, dims[][3] = {{big, big, 1}, {big, 1, big}, {1, big, big}, {big, big, big}, {big, 16, 16},
+                                                {1, 1, 1}, {1, big, 1}, {big + 1, 16, 16}};
+        for (const auto &d : dims)
+            for (int dt = 0; dt < 3; ++dt)
+                for (int bl = 0; bl < 2; ++bl) {
+                    const int rc = gemm_select(d[0], d[1], d[2], dt, &c);
+                    if (d[0] > big ? rc != GEMM_ERR_SHAPE : (rc != GEMM_OK && rc != GEMM_ERR_SHAPE))
+                        return 30;
+                    if (rc == GEMM_OK && (gemm_predict(&c, &p) != GEMM_OK || !(p.total_us > 0)))
+                        return 31;
+                    for (int i = 0; i < gemm_cfg_count(dt); i += 7) {
+                        gemm_cfg e;
+                        const int r2 = gemm_cfg_at_batched(i, d[0], d[1], d[2], 1, dt, bl, &e);
+                        if (r2 == GEMM_OK && e.stream_k && check_stream_k(e))
+                            return 32;
+                        if (r2 == GEMM_OK)
+                            acc += (long)(gemm_workspace_bytes(&e) % 3);
+                    }
+                }
+        // a group whose tile count does not fit 31 bits is refused by the plan, not wrapped
+        gemm_problem one{};
+        one.M = one.N = big;
+        one.K = 64;
+        one.lda = 64;
+        one.ldb = one.ldc = big;
+        one.A = one.B = (const void *)(uintptr_t)0x1000;
+        one.C = (void *)(uintptr_t)0x1000;
+        gemm_group_rec rec;
+        int64_t total = 0;
+        const int rc = gemm_select_grouped(1, &one, 0, 0, &c);
+        if (rc == GEMM_OK && gemm_grouped_plan(&c, 1, &one, &rec, &total) == GEMM_OK)
+            return 33;
+    }
+    // device descriptions: counts beyond the documented bounds are refused; a highly composite CU
+    // count inside them (48 divisors) selects and plans without overrunning the factor search
+    {
+        gemm_hw h0, hx;
+        gemm_hw_get(&h0);
+        hx = h0;
+        hx.n_cu = 55440;
+        if (gemm_hw_set(&hx) != GEMM_ERR_SHAPE)
+            return 34;
+        hx = h0;
+        hx.simd_per_cu = 65;
+        if (gemm_hw_set(&hx) != GEMM_ERR_SHAPE)
+            return 35;
+        hx = h0;
+        hx.n_cu = 2520;
+        hx.n_xcd = 8;
+        if (gemm_hw_set(&hx) != GEMM_OK)
+            return 36;
+        for (int it = 0; it < 60; ++it) {
+            const long M = 1 + rnd(8192), N = 1 + rnd(8192), K = 1 + rnd(8192);
+            if (gemm_select(M, N, K, it % 3, &c) != GEMM_OK || gemm_predict(&c, &p) != GEMM_OK)
+                return 37;
+            for (int i = 0; i < gemm_cfg_count(it % 3); i += 3) {
+                gemm_cfg e;
+                if (gemm_cfg_at(i, M, N, K, it % 3, &e) == GEMM_OK && e.stream_k && check_stream_k(e))
+                    return 38;
+            }
+        }
         gemm_hw_reset();
     }
     gemm_hw h;
