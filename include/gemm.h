@@ -391,6 +391,21 @@ int gemm_probe_stream(const void *buf, size_t bytes, void *scratch4, void *hip_s
  *                        conflict-free: kind 0 ds_read_b128, 1 ds_read_b64, 2 ds_read_b64_tr_b16,
  *                        3 ds_read_b64_tr_b8.  -> GB/s over the whole device (divide by CUs and clock
  *                        for bytes per clock and CU).
+ *   gemm_probe_fill      the GEMM kernel's refill in isolation: one or two (`wgs_per_cu`) workgroups of 8
+ *                        waves per CU move 64 KiB slabs from buf towards LDS, 16 bytes per lane and
+ *                        request, two slabs in flight, with a workgroup barrier per slab when `sync` is
+ *                        non-zero.  kind 0: buffer loads that write LDS directly; 1: the same 4 bytes per
+ *                        lane; 2: loads into registers only; 3: loads into registers, then ds_write_b128.
+ *                        pattern 0: slabs of consecutive bytes inside the first `footprint` bytes of buf
+ *                        (a power of two, 64 KiB .. 2 GiB, <= bytes; its size decides the level that
+ *                        serves them); pattern 1: slabs of 512 rows of 128 bytes, 16 KiB apart (a K slab
+ *                        of a row-major bf16 operand with K = 8192), stepping along the first `footprint`
+ *                        bytes (128 .. 16384, a power of two) of the rows; bytes >= 8 MiB.  patterns 2
+ *                        and 3 (not with kind 1): slabs of 512 pieces of 128 bytes / 128 pieces of 512
+ *                        bytes of consecutive rows 16 KiB apart, walking the first `footprint` bytes of
+ *                        buf (a power of two, 8 MiB .. 2 GiB, <= bytes) so that every byte is read once
+ *                        before any is read again: the operand traffic of a large GEMM beyond the L2.
+ *                        buf is 128-byte aligned device memory, only read.  -> GB/s over the whole device.
  *   gemm_probe_latency   4096 dependent loads by one lane through buf[0, bytes) (device memory,
  *                        128-byte aligned, >= 1 MiB; OVERWRITTEN with the chain), every hop on another
  *                        128-byte line; the level that holds the chain follows from the size as for
@@ -402,6 +417,8 @@ int gemm_probe_mfma_ex(int dtype, int mfma, int operands, double warm_ms, double
                        void *hip_stream, double *tflops_out);
 int gemm_probe_read(const void *buf, size_t bytes, int passes, void *scratch4, void *hip_stream, double *gbps_out);
 int gemm_probe_lds(int kind, int waves_per_cu, void *scratch4, void *hip_stream, double *gbps_out);
+int gemm_probe_fill(int kind, int pattern, int wgs_per_cu, int sync, const void *buf, size_t bytes, size_t footprint,
+                    void *scratch4, void *hip_stream, double *gbps_out);
 int gemm_probe_latency(void *buf, size_t bytes, void *scratch4, void *hip_stream, double *ns_out);
 
 #ifdef __cplusplus

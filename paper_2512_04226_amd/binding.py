@@ -152,6 +152,9 @@ _lib.gemm_probe_read.restype = _int
 _lib.gemm_probe_read.argtypes = [_vp, ctypes.c_size_t, _int, _vp, _vp, ctypes.POINTER(ctypes.c_double)]
 _lib.gemm_probe_lds.restype = _int
 _lib.gemm_probe_lds.argtypes = [_int, _int, _vp, _vp, ctypes.POINTER(ctypes.c_double)]
+_lib.gemm_probe_fill.restype = _int
+_lib.gemm_probe_fill.argtypes = [_int, _int, _int, _int, _vp, ctypes.c_size_t, ctypes.c_size_t, _vp, _vp,
+                                 ctypes.POINTER(ctypes.c_double)]
 _lib.gemm_probe_latency.restype = _int
 _lib.gemm_probe_latency.argtypes = [_vp, ctypes.c_size_t, _vp, _vp, ctypes.POINTER(ctypes.c_double)]
 
@@ -178,6 +181,17 @@ def gemm_probe_lds(kind, waves_per_cu, scratch, stream=None):
     out = ctypes.c_double()
     _check(_lib.gemm_probe_lds(kind, waves_per_cu, _ptr(scratch), ctypes.c_void_p(_stream_handle(stream)),
                                ctypes.byref(out)), "gemm_probe_lds")
+    return out.value
+
+
+def gemm_probe_fill(kind, pattern, buf, footprint, scratch, wgs_per_cu=1, sync=0, stream=None):
+    """Device-wide GB/s of 8-wave workgroups moving 64 KiB slabs from the tensor towards LDS (kind 0 direct
+    to LDS 16 B per lane, 1 direct 4 B per lane, 2 into registers, 3 registers then ds_write; pattern 0
+    consecutive bytes inside `footprint`, 1 rows of 128 B 16 KiB apart)."""
+    out = ctypes.c_double()
+    _check(_lib.gemm_probe_fill(kind, pattern, wgs_per_cu, sync, _ptr(buf), buf.numel() * buf.element_size(), footprint,
+                                _ptr(scratch), ctypes.c_void_p(_stream_handle(stream)), ctypes.byref(out)),
+           "gemm_probe_fill")
     return out.value
 
 

@@ -80,6 +80,11 @@ def measure_rates():
         for w, x in by_waves.items():
             out["%s_%dwaves_gbps" % (name, w)] = x
         out[name + "_gbps"] = max(by_waves.values())
+    # the refill path by itself: 64 KiB slabs towards LDS from data that the L2s, the MALL or HBM hold
+    for kind, kname in ((0, "direct"), (2, "registers"), (3, "registers_ds_write")):
+        out["fill_%s_l2_gbps" % kname] = g.gemm_probe_fill(kind, 1, buf, 2048, scratch, sync=1)
+        out["fill_%s_mall_gbps" % kname] = g.gemm_probe_fill(kind, 2, buf, 128 << 20, scratch, sync=1)
+        out["fill_%s_hbm_gbps" % kname] = g.gemm_probe_fill(kind, 2, buf, 1 << 30, scratch, sync=1)
     out["lat_l2_ns"] = g.gemm_probe_latency(buf[:2 << 20], scratch)
     out["lat_mall_ns"] = g.gemm_probe_latency(buf[:128 << 20], scratch)
     out["lat_hbm_ns"] = g.gemm_probe_latency(buf, scratch)
@@ -263,6 +268,43 @@ def decompose(lib_paths, n=8192):
                     "%s %.0f us (%.0f TFLOP/s)" % (nm, t, 2.0 * n ** 3 / t * 1e-6) for nm, t in zip(names, us))), flush=True)
 
 
+def compare_builds(named_libs, n=8192):
+    """The large tiles of each datatype on n^3 in several builds of the library (NAME=PATH each; the
+    timing-only diagnostic builds of gemm_kernel.hpp among them), settled, N(0,1)-like operands."""
+    libs = []
+    for a in named_libs:
+        name, path = a.split("=", 1)
+        lib = ctypes.CDLL(path)
+        lib.gemm_run.restype = ctypes.c_int
+        libs.append((name, lib))
+
+    def settled(lib, cfg, A, B, C):
+        def run():
+            if lib.gemm_run(ctypes.byref(cfg), g._ptr(A), g._ptr(B), g._ptr(C), ctypes.c_void_p(g._stream_handle(None))) != 0:
+                raise RuntimeError("gemm_run failed")
+        for _ in range(30):
+            run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            run()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / 20
+
+    picks = {g.GEMM_BF16: ("256x256x64 w4x2 mfma16 s2 split1 ", "256x256x64 w2x4 mfma16 s2 split1 ", "256x256x32 w2x4 mfma32 s4 split1 ",
+                           "128x128x64 w2x4 mfma16 s2 split1 ", "128x128x64 w2x4 mfma16 s4 split1 ", "256x128x64 w2x4 mfma16 s3 split1 "),
+             g.GEMM_FP8_E4M3: ("256x256x128 w2x4 mfma32 s2 split1 ",)}
+    for dtype, label in ((g.GEMM_BF16, "bf16"), (g.GEMM_FP8_E4M3, "fp8")):
+        A, B, C = make_operands(n, n, n, dtype, normal=True)
+        for idx in range(g.gemm_cfg_count(dtype)):
+            c = g.gemm_cfg_at(idx, n, n, n, dtype)
+            if c is None or not c.describe().startswith(picks[dtype]):
+                continue
+            print("%-4s %-40s %s" % (label, c.describe(), "  ".join("%s %.0f us" % (nm, settled(l, c, A, B, C)) for nm, l in libs)),
+                  flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--n", type=int, default=8192)
@@ -272,7 +314,12 @@ def main():
                     help="compare builds of the library (one per forced K-loop form) instead of calibrating")
     ap.add_argument("--decompose", nargs=4, metavar="LIB",
                     help="time the large tiles in four builds: normal, -DG355_DIAG_SKIP_FILL, -DG355_DIAG_SKIP_FRAG, both")
+    ap.add_argument("--compare-builds", nargs="+", metavar="NAME=LIB",
+                    help="time the large tiles in each of several builds of the library (diagnostic builds among them)")
     args = ap.parse_args()
+    if args.compare_builds:
+        compare_builds(args.compare_builds, args.n)
+        return
     if args.decompose:
         decompose(args.decompose, args.n)
         return

@@ -96,7 +96,11 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // -DG355_DIAG_SKIP_FILL leaves the refills out of the K loop (the ring keeps its first NS slabs),
 // -DG355_DIAG_SKIP_FRAG the fragment reads (the MFMAs reuse the first slab's fragments), -DG355_DIAG_SKIP_MFMA the
 // matrix instructions; timed against a normal build they show what the fill, the LDS reads and the MFMAs cost a
-// slab on their own and together (calibrate.py --decompose).
+// slab on their own and together (calibrate.py --decompose).  -DG355_DIAG_PANEL=b lets every workgroup read the
+// A rows of tile row 0 (bit 0) and the B columns of tile column 0 (bit 1; with bit 2: of tile row / column
+// blockIdx % 8), so that every request hits in the L2; -DG355_DIAG_FILL_MODE=1 sends the refill into registers
+// that nothing reads (no LDS writes), =2 issues the same requests 4 bytes per lane instead of 16
+// (calibrate.py --compare-builds; run them on shapes that are whole tiles and whole slabs only).
 // RG_: 1 = the instantiation for shapes whose N or K is not a whole number of 16-byte chunks.  A chunk that
 // holds the end of a row of a K-contiguous operand then also holds bytes that are not part of the matrix
 // (padding up to the leading dimension, which may be anything, NaN included), so slabs go through registers,
@@ -349,10 +353,18 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     // outside the buffer window and arrive as zero; chunk columns past the edge (A: k >= k_len,
     // B: n >= N) are sent outside the window by replacing the offset.
     const size_t bz = blockIdx.y;     // problem of the batch
-    const uint8_t *Abase = (const uint8_t *)pA + (bz * args.stride_a + (size_t)m0 * plda + k_begin) * ES;
+#ifdef G355_DIAG_PANEL
+    // timing-only builds: every workgroup (bit 0: of an XCD, with bit 2) reads the A rows of tile row 0,
+    // (bit 1) the B columns of tile column 0 -- the results are wrong, the request stream keeps its shape
+    const int m0_ld = (G355_DIAG_PANEL & 1) ? ((G355_DIAG_PANEL & 4) ? (int)(blockIdx.x % 8) * BM : 0) : m0;
+    const int n0_ld = (G355_DIAG_PANEL & 2) ? ((G355_DIAG_PANEL & 4) ? (int)(blockIdx.x % 8) * BN : 0) : n0;
+#else
+    const int m0_ld = m0, n0_ld = n0;
+#endif
+    const uint8_t *Abase = (const uint8_t *)pA + (bz * args.stride_a + (size_t)m0_ld * plda + k_begin) * ES;
     const uint8_t *Bbase = (T::BL == 0)
-                               ? (const uint8_t *)pB + (bz * args.stride_b + (size_t)k_begin * pldb + n0) * ES
-                               : (const uint8_t *)pB + (bz * args.stride_b + (size_t)n0 * pldb + k_begin) * ES;
+                               ? (const uint8_t *)pB + (bz * args.stride_b + (size_t)k_begin * pldb + n0_ld) * ES
+                               : (const uint8_t *)pB + (bz * args.stride_b + (size_t)n0_ld * pldb + k_begin) * ES;
     const int a_rows_valid = (pM - m0 < BM) ? (pM - m0) : BM;
     const int b_rows_valid = (pN - n0 < BN) ? (pN - n0) : BN;      // K-contiguous B only
     // (ragged instantiation: the window ends with the chunk that holds the last valid element, so that this
@@ -392,16 +404,30 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     }
     // Load instruction l of a slab request (A units first, then B units): asynchronous,
     // completion is counted by vmcnt.
+#if defined(G355_DIAG_FILL_MODE) && G355_DIAG_FILL_MODE == 2
+#define G355_FILL_BYTES 4      // timing-only: the same requests a quarter as wide
+#else
+#define G355_FILL_BYTES 16
+#endif
+#if defined(G355_DIAG_FILL_MODE) && G355_DIAG_FILL_MODE == 1
+    // timing-only: the refill goes into registers that nothing reads (no LDS writes); they stay live until
+    // the barrier the LDS data would have been needed at
+    i32x4 diag_regs[T::A_LOADS + T::B_LOADS];
+#endif
     auto issue_one = [&](int l, int slab, G355_LDS uint8_t *sbase) {
         const int kk = slab * BK;
         if (l < T::A_LOADS) {
             const int i = l, u = i * T::NW + wave;
             if (T::A_UNITS % T::NW == 0 || u < T::A_UNITS) {
                 const unsigned off = (a_kcol[i] + kk < k_len) ? a_voff[i] + (unsigned)(kk * ES) : OOB_OFFSET;
+#if defined(G355_DIAG_FILL_MODE) && G355_DIAG_FILL_MODE == 1
+                diag_regs[l] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsA, off, 0, 0));
+                return;
+#endif
                 if (T::STREAMABLE_A && stream_a)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (G355_LDS void *)(sbase + u * 1024), 16, off, 0, 0, G355_LOAD_STREAM);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (G355_LDS void *)(sbase + u * 1024), G355_FILL_BYTES, off, 0, 0, G355_LOAD_STREAM);
                 else
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (G355_LDS void *)(sbase + u * 1024), 16, off, 0, 0, G355_LOAD_DEFAULT);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (G355_LDS void *)(sbase + u * 1024), G355_FILL_BYTES, off, 0, 0, G355_LOAD_DEFAULT);
             }
         } else {
             const int i = l - T::A_LOADS, u = i * T::NW + wave;
@@ -411,11 +437,15 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                     off = b_voff[i] + (unsigned)kk * (unsigned)(pldb * ES);
                 else
                     off = (b_kcol[i] + kk < k_len) ? b_voff[i] + (unsigned)(kk * ES) : OOB_OFFSET;
+#if defined(G355_DIAG_FILL_MODE) && G355_DIAG_FILL_MODE == 1
+                diag_regs[l] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsB, off, 0, 0));
+                return;
+#endif
                 if (T::STREAMABLE_B && stream_b)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (G355_LDS void *)(sbase + T::A_BYTES + u * 1024), 16, off,
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (G355_LDS void *)(sbase + T::A_BYTES + u * 1024), G355_FILL_BYTES, off,
                                                              0, 0, G355_LOAD_STREAM);
                 else
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (G355_LDS void *)(sbase + T::A_BYTES + u * 1024), 16, off,
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (G355_LDS void *)(sbase + T::A_BYTES + u * 1024), G355_FILL_BYTES, off,
                                                              0, 0, G355_LOAD_DEFAULT);
             }
         }
@@ -590,7 +620,14 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     constexpr int NFR = T::TM * (ES == 2 ? 1 : 2) + T::TN * (T::BL == 1 ? (ES == 2 ? 1 : 2) : (ES == 2 ? 2 : 4));
     constexpr int RD_A = (NFR + (MN > 1 ? MN / 2 : 1) - 1) / (MN > 1 ? MN / 2 : 1);
     constexpr int RD_PAIRS = NFR / RD_A, RD_REM = NFR - RD_PAIRS * RD_A;
-    auto publish = [&]() { asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(ALLOW) : "memory"); };
+    auto publish = [&]() {
+#if defined(G355_DIAG_FILL_MODE) && G355_DIAG_FILL_MODE == 1
+#pragma unroll
+        for (int l = 0; l < NL; ++l)
+            asm volatile("" ::"v"(diag_regs[l]));
+#endif
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(ALLOW) : "memory");
+    };
 
     // The compiler cannot tell which LDS bytes a direct-to-LDS load will write, and before an LDS
     // read that might touch them it waits for every such load in flight (vmcnt(0)), which would

@@ -7,6 +7,8 @@
 //   gemm_probe_read         repeated reads of a buffer whose size decides which level serves them
 //                           -> R_1 (L2), R_2 (MALL), R_MEM
 //   gemm_probe_lds          LDS fragment-read loops -> the LDS term's rates (plain and transpose reads)
+//   gemm_probe_fill         64 KB slabs moved from global memory into LDS by 8-wave workgroups -> the
+//                           per-CU rate of the kernel's refill path
 //   gemm_probe_latency      dependent loads through a buffer -> L_lat of Algorithm 7
 // All run synchronously on the given stream and time themselves with HIP events; none is part
 // of gemm_select or gemm_run.
@@ -222,6 +224,103 @@ __global__ __launch_bounds__(512) void lds_read_loop(uint32_t *out, int iters)
         out[0] = (uint32_t)acc;
 }
 
+// ---- slab fill: workgroups of 8 waves move 64 KB "slabs" from global memory towards LDS ----
+// Every wave issues the requests of 8 of a slab's 64 one-KB units (16 bytes per lane), as the GEMM
+// kernel's refill does, with at most two slabs' requests in flight.
+//   KIND 0  buffer loads that write LDS directly, 16 bytes per lane
+//   KIND 1  the same path 4 bytes per lane (four times the instructions)
+//   KIND 2  buffer loads into registers (the data goes nowhere)
+//   KIND 3  buffer loads into registers, then ds_write_b128 into the lane's LDS slot
+//   PAT 0   a slab is 64 KB of consecutive bytes; workgroups start 17 slabs apart inside the window
+//   PAT 1   a slab is 512 rows of 128 bytes, rows 16 KB apart (a K slab of a row-major bf16 operand
+//           with K = 8192); successive slabs step 128 bytes along the rows inside `span` bytes
+//   PAT 2/3 a slab is 512 pieces of 128 bytes / 128 pieces of 512 bytes of consecutive rows 16 KB apart;
+//           successive slabs take the next block of rows of the window, then the next piece of the rows:
+//           every byte of the window is read once before any is read again
+typedef unsigned u32x4p __attribute__((ext_vector_type(4)));
+template <int KIND, int PAT>
+__global__ __launch_bounds__(512) void fill_loop(const uint8_t *buf, unsigned window, unsigned span, int iters, int sync,
+                                                 uint32_t *out)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[64 * 1024];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(buf), 0, window, 0x00020000);
+    PROBE_LDS uint8_t *lds = (PROBE_LDS uint8_t *)smem;
+    // byte offset of this lane's 16 bytes of unit u in slab `it`; always below `window`
+    auto offset_of = [&](int it, int u, int sub) -> unsigned {
+        const unsigned unit = (unsigned)(u * 8 + wave);
+        if constexpr (PAT == 0) {
+            const unsigned base = ((blockIdx.x * 17u + (unsigned)it) * 65536u + unit * 1024u) & (window - 1);
+            return KIND == 1 ? base + sub * 256u + lane * 4u : base + lane * 16u;
+        } else if constexpr (PAT == 1) {
+            const unsigned kofs = ((unsigned)it * 128u) & (span - 1);
+            if constexpr (KIND == 1)
+                return (unit * 8u + sub * 2u + (lane >> 5)) * 16384u + kofs + (lane & 31) * 4u;
+            return (unit * 8u + (lane >> 3)) * 16384u + kofs + (lane & 7) * 16u;
+        } else {
+            // slab j of the launch: block of 65536 / PIECE rows j mod (row blocks), piece (j / row blocks) of the rows
+            constexpr unsigned PIECE = PAT == 2 ? 128u : 512u, ROWS = 65536u / PIECE, LPP = PIECE / 16u;
+            const unsigned j = blockIdx.x * 17u + (unsigned)it, blocks = (window >> 14) / ROWS;
+            const unsigned rb = j % blocks, kofs = ((j / blocks) * PIECE) & 16383u;
+            return (rb * ROWS + unit * (64u / LPP) + lane / LPP) * 16384u + kofs + (lane % LPP) * 16u;
+        }
+    };
+    if constexpr (KIND <= 1) {
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if constexpr (KIND == 0) {
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass does not know the 16-byte form and drops the launch stub
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (PROBE_LDS void *)(lds + (u * 8 + wave) * 1024), 16,
+                                                             offset_of(it, u, 0), 0, 0, 0);
+#endif
+                } else {
+#pragma unroll
+                    for (int sub = 0; sub < 4; ++sub)
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (PROBE_LDS void *)(lds + (u * 8 + wave) * 1024 + sub * 256), 4,
+                                                                 offset_of(it, u, sub), 0, 0, 0);
+                }
+            }
+            if constexpr (KIND == 0)
+                asm volatile("s_waitcnt vmcnt(8)" ::: "memory");     // the previous slab has landed
+            else
+                asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+            if (sync)
+                __builtin_amdgcn_s_barrier();   // the bare barrier: outstanding loads stay in flight across it
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+        u32x4p cur[8], nxt[8];
+        unsigned acc = 0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            cur[u] = __builtin_amdgcn_raw_buffer_load_b128(rs, offset_of(0, u, 0), 0, 0);
+        for (int it = 1; it <= iters; ++it) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                nxt[u] = __builtin_amdgcn_raw_buffer_load_b128(rs, offset_of(it < iters ? it : 0, u, 0), 0, 0);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if constexpr (KIND == 2)
+                    asm volatile("" ::"v"(cur[u]));
+                else
+                    *(PROBE_LDS u32x4p *)(lds + (u * 8 + wave) * 1024 + lane * 16) = cur[u];
+                cur[u] = nxt[u];
+            }
+            if (sync)
+                __builtin_amdgcn_s_barrier();   // the bare barrier: outstanding loads stay in flight across it
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            acc ^= cur[u][0];
+        if (acc == 0x9E3779B9u && out)   // practically never
+            out[1] = acc;
+    }
+    __syncthreads();
+    if (((PROBE_LDS uint32_t *)smem)[tid] == 0x9E3779B9u && iters < 0)   // never: keeps the LDS writes alive
+        out[0] = 1;
+}
+
 // ---- dependent loads: one lane follows a chain of line indices through the buffer ----
 // Line i (128 bytes apart) of the first `chain` lines holds the index of line (i + step) mod chain; step is
 // odd and chain a power of two, so the chain visits every one of them before it repeats.  All `lines` lines
@@ -424,6 +523,56 @@ extern "C" int gemm_probe_lds(int kind, int waves_per_cu, void *scratch4, void *
     if (rc)
         return rc;
     *gbps_out = bytes / (ms * 1e-3) * 1e-9;
+    return GEMM_OK;
+}
+
+extern "C" int gemm_probe_fill(int kind, int pattern, int wgs_per_cu, int sync, const void *buf, size_t bytes,
+                               size_t footprint, void *scratch4, void *hip_stream, double *gbps_out)
+{
+    if (!buf || !scratch4 || !gbps_out)
+        return GEMM_ERR_NULL;
+    if (kind < 0 || kind > 3 || pattern < 0 || pattern > 3 || wgs_per_cu < 1 || wgs_per_cu > 2 || (pattern >= 2 && kind == 1))
+        return GEMM_ERR_CFG_ILLEGAL;
+    if ((uintptr_t)buf & 127)
+        return GEMM_ERR_ALIGN;
+    // patterns 0, 2, 3: the window is `footprint` bytes (a power of two, 64 KiB (8 MiB) .. 2 GiB); pattern 1: 512 rows 16 KiB
+    // apart (an 8 MiB window) of which the first `footprint` bytes (128 .. 16384, a power of two) are read
+    unsigned window, span = 128;
+    if (footprint & (footprint - 1))
+        return GEMM_ERR_ALIGN;
+    if (pattern == 0 || pattern >= 2) {
+        if (footprint < (pattern ? (size_t)8 << 20 : 65536) || footprint > ((size_t)1 << 31) || footprint > bytes)
+            return GEMM_ERR_ALIGN;
+        window = (unsigned)footprint;
+    } else {
+        if (footprint < 128 || footprint > 16384 || bytes < ((size_t)8 << 20))
+            return GEMM_ERR_ALIGN;
+        window = 8u << 20;
+        span = (unsigned)footprint;
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        cus < 1) {
+        (void)hipGetLastError();
+        return GEMM_ERR_HIP;
+    }
+    const int blocks = cus * wgs_per_cu, iters = 2048 / wgs_per_cu;
+    const double moved = (double)blocks * iters * 65536.0;
+    const uint8_t *p = (const uint8_t *)buf;
+    uint32_t *out = (uint32_t *)scratch4;
+    double ms = 0;
+    (void)hipGetLastError();
+#define FILL_CASE(K, P)                                                                                                       \
+    if (kind == K && pattern == P)                                                                                            \
+        rc = timed(s, [&] { hipLaunchKernelGGL((fill_loop<K, P>), dim3(blocks), dim3(512), 0, s, p, window, span, iters, sync, out); }, &ms);
+    int rc = GEMM_ERR_CFG_ILLEGAL;
+    FILL_CASE(0, 0) FILL_CASE(1, 0) FILL_CASE(2, 0) FILL_CASE(3, 0) FILL_CASE(0, 1) FILL_CASE(1, 1) FILL_CASE(2, 1) FILL_CASE(3, 1)
+    FILL_CASE(0, 2) FILL_CASE(2, 2) FILL_CASE(3, 2) FILL_CASE(0, 3) FILL_CASE(2, 3) FILL_CASE(3, 3)
+#undef FILL_CASE
+    if (rc)
+        return rc;
+    *gbps_out = moved / (ms * 1e-3) * 1e-9;
     return GEMM_OK;
 }
 

@@ -87,6 +87,29 @@ def test_latency_probe_orders_the_memory_levels(g, scratch):
     assert math.isfinite(l2) and math.isfinite(hbm) and 50.0 <= l2 <= hbm <= 5000.0
 
 
+def test_fill_probe_orders_the_memory_levels_and_paths(g, scratch):
+    """Slabs moved towards LDS by 8-wave workgroups: from L2-resident rows every path runs near the 64 bytes
+    per clock a CU's vector memory path delivers, HBM-resident rows arrive at the streaming rate, and writing
+    LDS directly is not slower than going through registers and ds_write."""
+    hw = g.gemm_hw_get()
+    buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    cap = 64.0 * hw.n_cu * 2.6            # GB/s at a generous clock
+    l2 = {k: g.gemm_probe_fill(k, 1, buf, 2048, scratch, sync=1) for k in (0, 1, 2, 3)}
+    hbm = {k: g.gemm_probe_fill(k, 2, buf, 1 << 30, scratch, sync=1) for k in (0, 2, 3)}
+    wide = g.gemm_probe_fill(0, 3, buf, 1 << 30, scratch)
+    stream = g.gemm_probe_stream(buf, scratch)
+    print("fill probe GB/s: L2 %s, HBM %s (512-byte pieces %.0f, stream %.0f)" % (
+        {k: round(v) for k, v in l2.items()}, {k: round(v) for k, v in hbm.items()}, wide, stream))
+    for v in list(l2.values()) + list(hbm.values()) + [wide]:
+        assert math.isfinite(v) and v > 0
+    for k in l2:
+        assert 0.4 * cap <= l2[k] <= cap, l2
+    for k in hbm:
+        assert 0.5 * PEAK_HBM_GBPS <= hbm[k] <= 1.0 * PEAK_HBM_GBPS and hbm[k] <= l2[k], (hbm, l2)
+    assert l2[0] >= 0.9 * l2[3]
+    assert abs(hbm[0] - stream) <= 0.25 * stream
+
+
 def test_probe_argument_checks(g, scratch):
     small = torch.empty(1024, dtype=torch.uint8, device="cuda")
     with pytest.raises(g.GemmError):
@@ -99,3 +122,10 @@ def test_probe_argument_checks(g, scratch):
         g.gemm_probe_lds(9, 8, scratch)
     with pytest.raises(g.GemmError):
         g.gemm_probe_latency(small, scratch)
+    big = torch.empty(16 << 20, dtype=torch.uint8, device="cuda")
+    for bad in ((4, 0, 1 << 20), (0, 4, 1 << 20), (1, 2, 8 << 20), (0, 0, 3 << 20), (0, 0, 32 << 20), (0, 1, 64),
+                (0, 2, 1 << 20)):
+        with pytest.raises(g.GemmError):
+            g.gemm_probe_fill(bad[0], bad[1], big, bad[2], scratch)
+    with pytest.raises(g.GemmError):
+        g.gemm_probe_fill(0, 1, small, 2048, scratch)
