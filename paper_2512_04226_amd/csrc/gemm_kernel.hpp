@@ -124,9 +124,11 @@ struct Tile {
     // An operand that only ONE tile row (B) or tile column (A) of the grid reads is read once in all: its slab
     // loads then carry the non-temporal hint, so that the stream does not push the other operand's panels (which
     // every workgroup re-reads) out of the L2 (weight streaming at M <= BLOCK_M: 5-10 % on the HBM-bound shapes).
-    // Decided per launch (per group); compiled only into tiles of at most 128 rows / columns, so that the
-    // instruction streams of the large compute-bound tiles stay as they were tuned.
-    static constexpr bool STREAMABLE_B = BM <= 128, STREAMABLE_A = BN <= 128;
+    // Decided per launch (per group), outside the K loop: a streaming tile carries a second copy of the loop.
+    // Compiled only into the tiles of at most 32 rows, the ones the selector gives weight-streaming shapes
+    // (M <= 32): with a second or third copy of the loop the compiler keeps more values live across all of
+    // them, and the 64- to 128-row tiles then lose a resident workgroup (128x128x64: 120 -> 148 registers).
+    static constexpr bool STREAMABLE_B = BM <= 32, STREAMABLE_A = false;
     static constexpr int WTM = BM / WM, WTN = BN / WN;      // wave tile
     static constexpr int TM = WTM / MI, TN = WTN / MI;      // MFMA tiles per wave
     static constexpr int KI = (ES == 2) ? (MI == 32 ? 16 : 32) : (MI == 32 ? 64 : 128);  // MI_K
@@ -414,7 +416,11 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     // the barrier the LDS data would have been needed at
     i32x4 diag_regs[T::A_LOADS + T::B_LOADS];
 #endif
-    auto issue_one = [&](int l, int slab, G355_LDS uint8_t *sbase) {
+    // `mode` (a std::integral_constant): 0 default cache policy, 1 the B loads stream (one tile row), 2 the A loads
+    // stream (one tile column).  A compile-time constant, chosen once outside the K loop: a run-time choice per
+    // load would put every load into a basic block of its own and take the loop's schedule apart.
+    auto issue_one = [&](auto mode, int l, int slab, G355_LDS uint8_t *sbase) {
+        constexpr int MODE = decltype(mode)::value;
         const int kk = slab * BK;
         if (l < T::A_LOADS) {
             const int i = l, u = i * T::NW + wave;
@@ -424,10 +430,8 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                 diag_regs[l] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsA, off, 0, 0));
                 return;
 #endif
-                if (T::STREAMABLE_A && stream_a)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (G355_LDS void *)(sbase + u * 1024), G355_FILL_BYTES, off, 0, 0, G355_LOAD_STREAM);
-                else
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (G355_LDS void *)(sbase + u * 1024), G355_FILL_BYTES, off, 0, 0, G355_LOAD_DEFAULT);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (G355_LDS void *)(sbase + u * 1024), G355_FILL_BYTES, off, 0, 0,
+                                                         MODE == 2 ? G355_LOAD_STREAM : G355_LOAD_DEFAULT);
             }
         } else {
             const int i = l - T::A_LOADS, u = i * T::NW + wave;
@@ -441,12 +445,8 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                 diag_regs[l] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsB, off, 0, 0));
                 return;
 #endif
-                if (T::STREAMABLE_B && stream_b)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (G355_LDS void *)(sbase + T::A_BYTES + u * 1024), G355_FILL_BYTES, off,
-                                                             0, 0, G355_LOAD_STREAM);
-                else
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (G355_LDS void *)(sbase + T::A_BYTES + u * 1024), G355_FILL_BYTES, off,
-                                                             0, 0, G355_LOAD_DEFAULT);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (G355_LDS void *)(sbase + T::A_BYTES + u * 1024), G355_FILL_BYTES, off,
+                                                         0, 0, MODE == 1 ? G355_LOAD_STREAM : G355_LOAD_DEFAULT);
             }
         }
     };
@@ -669,12 +669,12 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         publish();
     };
     // from the barrier of slab kt to the barrier of slab kt + 1
-    auto after_barrier = [&](G355_LDS uint8_t *__restrict__ freed, const G355_LDS uint8_t *__restrict__ next, int kt)
+    auto after_barrier = [&](auto mode, G355_LDS uint8_t *__restrict__ freed, const G355_LDS uint8_t *__restrict__ next, int kt)
                              __attribute__((always_inline)) {
 #ifndef G355_DIAG_SKIP_FILL
 #pragma unroll
         for (int l = 0; l < NL; ++l)
-            issue_one(l, kt + T::NS, freed);
+            issue_one(mode, l, kt + T::NS, freed);
 #endif
         // form 2: no memory instruction may be scheduled across this point (ALU and MFMA
         // instructions may), or the refill drifts down the iteration it has to land in
@@ -741,11 +741,12 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             }
         }
     } else if (kt_count > 0) {
+      auto pipeline = [&](auto mode) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < T::NS; ++s)
 #pragma unroll
             for (int l = 0; l < NL; ++l)
-                issue_one(l, s, lds + s * T::STAGE);
+                issue_one(mode, l, s, lds + s * T::STAGE);
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((T::NS - 1) * FULL) : "memory");
 #pragma unroll
         for (int u = 0; u < NF; ++u)
@@ -760,11 +761,28 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         // forms 1 and 2 peel the last slab off (see Tile)
         for (int kt = 0; kt + (LF != 0) < kt_count; ++kt) {
             const int next = (stage + 1 == T::NS) ? 0 : stage + 1;
-            after_barrier(lds + stage * T::STAGE, lds + next * T::STAGE, kt);
+            after_barrier(mode, lds + stage * T::STAGE, lds + next * T::STAGE, kt);
             stage = next;
         }
         if constexpr (LF != 0)
             mma_kstep((T::KSTEPS - 1) & 1);
+      };
+      // one tile row: B is read once and streams; else one tile column: A streams (see Tile::STREAMABLE_*)
+      bool done = false;
+      if constexpr (T::STREAMABLE_B) {
+          if (stream_b) {
+              pipeline(std::integral_constant<int, 1>{});
+              done = true;
+          }
+      }
+      if constexpr (T::STREAMABLE_A) {
+          if (!done && stream_a) {
+              pipeline(std::integral_constant<int, 2>{});
+              done = true;
+          }
+      }
+      if (!done)
+          pipeline(std::integral_constant<int, 0>{});
     }
     // nothing may still be in flight towards LDS when the workgroup ends
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
