@@ -419,13 +419,14 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     // `mode` (a std::integral_constant): 0 default cache policy, 1 the B loads stream (one tile row), 2 the A loads
     // stream (one tile column).  A compile-time constant, chosen once outside the K loop: a run-time choice per
     // load would put every load into a basic block of its own and take the loop's schedule apart.
-    auto issue_one = [&](auto mode, int l, int slab, G355_LDS uint8_t *sbase) {
+    auto issue_one = [&](auto mode, auto tail, int l, int slab, G355_LDS uint8_t *sbase) {
         constexpr int MODE = decltype(mode)::value;
+        constexpr bool TAIL = decltype(tail)::value;     // false: the slab lies wholly inside the K range
         const int kk = slab * BK;
         if (l < T::A_LOADS) {
             const int i = l, u = i * T::NW + wave;
             if (T::A_UNITS % T::NW == 0 || u < T::A_UNITS) {
-                const unsigned off = (a_kcol[i] + kk < k_len) ? a_voff[i] + (unsigned)(kk * ES) : OOB_OFFSET;
+                const unsigned off = (!TAIL || a_kcol[i] + kk < k_len) ? a_voff[i] + (unsigned)(kk * ES) : OOB_OFFSET;
 #if defined(G355_DIAG_FILL_MODE) && G355_DIAG_FILL_MODE == 1
                 diag_regs[l] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsA, off, 0, 0));
                 return;
@@ -440,7 +441,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                 if constexpr (T::BL == 0)
                     off = b_voff[i] + (unsigned)kk * (unsigned)(pldb * ES);
                 else
-                    off = (b_kcol[i] + kk < k_len) ? b_voff[i] + (unsigned)(kk * ES) : OOB_OFFSET;
+                    off = (!TAIL || b_kcol[i] + kk < k_len) ? b_voff[i] + (unsigned)(kk * ES) : OOB_OFFSET;
 #if defined(G355_DIAG_FILL_MODE) && G355_DIAG_FILL_MODE == 1
                 diag_regs[l] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsB, off, 0, 0));
                 return;
@@ -669,12 +670,12 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         publish();
     };
     // from the barrier of slab kt to the barrier of slab kt + 1
-    auto after_barrier = [&](auto mode, G355_LDS uint8_t *__restrict__ freed, const G355_LDS uint8_t *__restrict__ next, int kt)
+    auto after_barrier = [&](auto mode, auto tail, G355_LDS uint8_t *__restrict__ freed, const G355_LDS uint8_t *__restrict__ next, int kt)
                              __attribute__((always_inline)) {
 #ifndef G355_DIAG_SKIP_FILL
 #pragma unroll
         for (int l = 0; l < NL; ++l)
-            issue_one(mode, l, kt + T::NS, freed);
+            issue_one(mode, tail, l, kt + T::NS, freed);
 #endif
         // form 2: no memory instruction may be scheduled across this point (ALU and MFMA
         // instructions may), or the refill drifts down the iteration it has to land in
@@ -746,7 +747,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         for (int s = 0; s < T::NS; ++s)
 #pragma unroll
             for (int l = 0; l < NL; ++l)
-                issue_one(mode, l, s, lds + s * T::STAGE);
+                issue_one(mode, std::true_type{}, l, s, lds + s * T::STAGE);
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((T::NS - 1) * FULL) : "memory");
 #pragma unroll
         for (int u = 0; u < NF; ++u)
@@ -759,9 +760,21 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         until_barrier(lds);
         int stage = 0;                         // stage of slab kt
         // forms 1 and 2 peel the last slab off (see Tile)
-        for (int kt = 0; kt + (LF != 0) < kt_count; ++kt) {
+        const int kt_end = kt_count - (LF != 0);
+        int kt = 0;
+        // Iterations whose refill (slab kt + NS) lies wholly inside the K range run a copy of the loop without the
+        // per-chunk test against the end of K (three vector ALU instructions and a register per load of a
+        // K-contiguous operand; with them the 256x256 tiles on K-contiguous B spilled); the last NS + 1 do test.
+        int kt_main = k_len / BK - T::NS;
+        kt_main = kt_main < kt_end ? kt_main : kt_end;
+        for (; kt < kt_main; ++kt) {
             const int next = (stage + 1 == T::NS) ? 0 : stage + 1;
-            after_barrier(mode, lds + stage * T::STAGE, lds + next * T::STAGE, kt);
+            after_barrier(mode, std::false_type{}, lds + stage * T::STAGE, lds + next * T::STAGE, kt);
+            stage = next;
+        }
+        for (; kt < kt_end; ++kt) {
+            const int next = (stage + 1 == T::NS) ? 0 : stage + 1;
+            after_barrier(mode, std::true_type{}, lds + stage * T::STAGE, lds + next * T::STAGE, kt);
             stage = next;
         }
         if constexpr (LF != 0)

@@ -72,7 +72,7 @@
 
 // fp8 e4m3: MFMA 32 -> v_mfma_f32_32x32x64_f8f6f4, 16 -> v_mfma_f32_16x16x128_f8f6f4
 #define G355_VARIANTS_FP8_0(X)     \
-    X(256, 256, 128, 2, 4, 32, 2, 2, 3) \
+    X(256, 256, 128, 2, 4, 32, 2, 2, 2) \
     X(256, 256, 128, 2, 2, 32, 2, 3, 4) \
     X(256, 128, 128, 2, 4, 32, 3, 1, 1) \
     X(128, 256, 128, 2, 4, 32, 3, 4, 4) \
