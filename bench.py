@@ -21,6 +21,10 @@ PEAK_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0}   # MI355X dense MFMA, published
 PEAK_HBM_GBPS = 8000.0
 
 
+def ms_per_step_of(tflops, flops_step):
+    return flops_step / (tflops * 1e12) * 1e3
+
+
 def read_traffic(name):
     """HBM bytes per launch of the dominant kernel from the committed counter summary
     (profiles/<name>: a line `traffic_bytes_per_launch: <number>`), or None."""
@@ -294,6 +298,11 @@ def main():
     # that follows an idle gap: `value` is what its flags time, this is the sustained rate)
     also["settled_value"] = flops_step / settled_us(torch, step) * 1e-6
     also["settled_8192_kernel_ms"] = settled_us(torch, lambda: g.gemm_run(cfg_big, *dev[big])) * 1e-3
+    # GPU time of the warm-up steps: after an idle gap the chip needs 15-20 ms of work to settle under its power
+    # limit; a timed region that starts earlier reads the transient
+    warm_gpu_ms = args.warmup * ms_per_step_of(also["settled_value"], flops_step)
+    also["warmup_gpu_ms"] = warm_gpu_ms
+    also["value_measured_in_transient"] = bool(warm_gpu_ms < 20.0)
     if not args.brief:
         secondary(also, g, wl, np, torch, dev, sizes, timed_us, ensure_ws)
 
