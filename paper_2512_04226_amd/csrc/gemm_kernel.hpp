@@ -75,7 +75,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // layout of the paper's own runs, Section V): B is then staged and read exactly like A.
 // FT_ (16-bit inputs only): 0 bf16 in / bf16 out, 1 IEEE fp16 in / fp16 out (the precision of the
 // paper's runs); the data path is the same, only the MFMA instruction and the output rounding differ.
-// LF_: form of the K loop, one of four source arrangements of the same work between which the
+// LF_: form of the K loop, one of six source arrangements of the same work between which the
 // compiler's instruction schedule, and with it the time per slab, differs by up to 15 % either
 // way; which one a variant uses is measured (8192^3, the forms interleaved) and recorded
 // in the variant table.  0: one loop over all slabs, the part up to the next barrier under a
@@ -91,6 +91,11 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // MN / NL matrix instructions) instead of going out as a burst: the vector-memory path of a CU takes 64 bytes
 // per clock, a slab's loads are 16 clocks of it each, and a wave whose load finds that path's queue full
 // cannot issue the MFMAs behind it either.
+// 5: the order written out in the source instead of prescribed to the scheduler: every MFMA of a k-step is preceded
+// by its share of the refill loads (after the barrier) and of the next k-step's fragment reads (first half of the
+// MFMAs), and a scheduling fence after each MFMA keeps the compiler from moving anything across it.  Both fragment
+// buffers are then live through every k-step: the four-wave tiles and several medium tiles gain 3-13 %, the 256x256
+// eight-wave tiles on a 4x2 grid would spill.
 // Building with -DG355_FORCE_LOOP_FORM=k gives every variant form k (how the forms are compared).
 // Timing-only diagnostic builds (their RESULTS ARE WRONG; every access stays in bounds and every wait ends):
 // -DG355_DIAG_SKIP_FILL leaves the refills out of the K loop (the ring keeps its first NS slabs),
@@ -117,7 +122,7 @@ struct Tile {
 #else
     static constexpr int LF = LF_;
 #endif
-    static_assert(LF >= 0 && LF <= 4, "unknown K-loop form");
+    static_assert(LF >= 0 && LF <= 5, "unknown K-loop form");
     static_assert(FT == 0 || ES == 2, "fp16 is a 16-bit input type");
     static constexpr int NW = WM * WN;
     static constexpr int NT = WM * WN * 64;
@@ -651,6 +656,21 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     auto until_barrier = [&](const G355_LDS uint8_t *cur) __attribute__((always_inline)) {
 #pragma unroll
         for (int kstep = 0; kstep < T::KSTEPS - 1; ++kstep) {
+            if constexpr (LF == 5) {
+                // form 5: the order is written out -- MFMA m of the k-step is preceded by its share of the next
+                // k-step's fragment reads (spread over the first half of the MFMAs), and nothing may move
+                // across the fence after it
+#pragma unroll
+                for (int m = 0; m < MN; ++m) {
+#pragma unroll
+                    for (int u = 0; u < NF; ++u)
+                        if (u * (MN / 2 > 0 ? MN / 2 : 1) / NF == m)
+                            load_frag(cur, kstep + 1, (kstep + 1) & 1, u);
+                    mma_one(kstep & 1, m / T::TM, m % T::TM);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                continue;
+            }
 #ifndef G355_DIAG_SKIP_FRAG
 #pragma unroll
             for (int u = 0; u < NF; ++u)
@@ -672,6 +692,24 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     // from the barrier of slab kt to the barrier of slab kt + 1
     auto after_barrier = [&](auto mode, auto tail, G355_LDS uint8_t *__restrict__ freed, const G355_LDS uint8_t *__restrict__ next, int kt)
                              __attribute__((always_inline)) {
+        if constexpr (LF == 5) {
+            // form 5: refill loads one every MN / NL MFMAs, the next slab's first fragments over the first half
+#pragma unroll
+            for (int m = 0; m < MN; ++m) {
+#pragma unroll
+                for (int l = 0; l < NL; ++l)
+                    if (l * MN / NL == m)
+                        issue_one(mode, tail, l, kt + T::NS, freed);
+#pragma unroll
+                for (int u = 0; u < NF; ++u)
+                    if (u * (MN / 2 > 0 ? MN / 2 : 1) / NF == m)
+                        load_frag(next, 0, 0, u);
+                mma_one((T::KSTEPS - 1) & 1, m / T::TM, m % T::TM);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            until_barrier(next);
+            return;
+        }
 #ifndef G355_DIAG_SKIP_FILL
 #pragma unroll
         for (int l = 0; l < NL; ++l)

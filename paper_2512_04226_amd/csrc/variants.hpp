@@ -14,19 +14,19 @@
 // bf16: BLOCK_K in elements; MFMA 32 -> v_mfma_f32_32x32x16_bf16, 16 -> v_mfma_f32_16x16x32_bf16
 #define G355_VARIANTS_BF16_0(X)    \
     X(256, 256, 64, 2, 4, 32, 2, 3, 3) \
-    X(256, 256, 64, 2, 2, 32, 2, 3, 4) \
+    X(256, 256, 64, 2, 2, 32, 2, 5, 4) \
     X(256, 256, 32, 2, 4, 32, 4, 3, 3) \
     X(256, 256, 32, 2, 2, 32, 4, 4, 4) \
     X(256, 256, 32, 2, 4, 32, 5, 3, 3) \
-    X(256, 128, 64, 2, 4, 32, 3, 3, 3) \
-    X(256, 128, 64, 2, 2, 32, 3, 3, 4) \
+    X(256, 128, 64, 2, 4, 32, 3, 3, 5) \
+    X(256, 128, 64, 2, 2, 32, 3, 5, 5) \
     X(128, 256, 64, 2, 4, 32, 3, 3, 1)
 #define G355_VARIANTS_BF16_1(X)    \
-    X(128, 256, 64, 2, 2, 32, 3, 3, 3) \
+    X(128, 256, 64, 2, 2, 32, 3, 5, 5) \
     X(128, 128, 64, 2, 2, 32, 2, 0, 0) \
-    X(128, 128, 64, 2, 2, 32, 3, 3, 4) \
+    X(128, 128, 64, 2, 2, 32, 3, 5, 5) \
     X(64, 256, 64, 1, 4, 32, 2, 1, 0) \
-    X(128, 64, 64, 2, 2, 32, 3, 0, 3) \
+    X(128, 64, 64, 2, 2, 32, 3, 5, 3) \
     X(64, 128, 64, 2, 2, 32, 3, 1, 3)
 #define G355_VARIANTS_BF16_2(X)    \
     X(64, 64, 64, 2, 2, 32, 3, 3, 0) \
@@ -37,9 +37,9 @@
     X(32, 128, 128, 1, 4, 32, 2, 0, 0) \
     X(32, 64, 128, 1, 2, 32, 3, 3, 1)
 #define G355_VARIANTS_BF16_3(X)    \
-    X(16, 256, 64, 1, 4, 16, 4, 4, 4) \
+    X(16, 256, 64, 1, 4, 16, 4, 5, 4) \
     X(16, 256, 128, 1, 4, 16, 2, 0, 3) \
-    X(16, 128, 128, 1, 4, 16, 4, 3, 3) \
+    X(16, 128, 128, 1, 4, 16, 4, 3, 5) \
     X(16, 128, 256, 1, 4, 16, 2, 3, 3) \
     X(16, 64, 128, 1, 4, 16, 4, 0, 0) \
     X(16, 64, 256, 1, 4, 16, 3, 3, 1) \
@@ -66,32 +66,32 @@
 // deeper LDS rings of tiles that win latency- and bandwidth-bound shapes (a request has NS-1 whole slabs
 // of time to land); of eight such candidates these three were sweep-best on 10-20 % of the irregular shapes
 #define G355_VARIANTS_BF16_5(X)    \
-    X(64, 128, 64, 2, 4, 16, 4, 2, 2) \
+    X(64, 128, 64, 2, 4, 16, 4, 2, 5) \
     X(128, 128, 64, 2, 4, 16, 3, 4, 1) \
     X(128, 128, 64, 2, 4, 16, 4, 3, 1)
 
 // fp8 e4m3: MFMA 32 -> v_mfma_f32_32x32x64_f8f6f4, 16 -> v_mfma_f32_16x16x128_f8f6f4
 #define G355_VARIANTS_FP8_0(X)     \
+    X(256, 256, 128, 2, 2, 32, 2, 5, 5) \
     X(256, 256, 128, 2, 4, 32, 2, 2, 2) \
-    X(256, 256, 128, 2, 2, 32, 2, 3, 4) \
-    X(256, 128, 128, 2, 4, 32, 3, 1, 1) \
+    X(256, 128, 128, 2, 4, 32, 3, 1, 5) \
     X(128, 256, 128, 2, 4, 32, 3, 4, 4) \
-    X(128, 128, 128, 2, 2, 32, 2, 0, 0) \
-    X(128, 128, 128, 2, 2, 32, 3, 3, 4) \
-    X(128, 128, 256, 2, 2, 32, 2, 3, 0) \
+    X(128, 128, 128, 2, 2, 32, 2, 5, 5) \
+    X(128, 128, 128, 2, 2, 32, 3, 5, 5) \
+    X(128, 128, 256, 2, 2, 32, 2, 3, 5) \
     X(128, 64, 128, 2, 2, 32, 3, 0, 4) \
     X(64, 128, 128, 2, 2, 32, 3, 0, 2)
 #define G355_VARIANTS_FP8_1(X)     \
-    X(64, 128, 256, 2, 2, 32, 3, 3, 3) \
+    X(64, 128, 256, 2, 2, 32, 3, 5, 5) \
     X(64, 64, 128, 2, 2, 32, 3, 0, 1) \
     X(64, 64, 256, 2, 2, 32, 2, 0, 3) \
-    X(64, 256, 128, 1, 4, 32, 2, 0, 0) \
+    X(64, 256, 128, 1, 4, 32, 2, 0, 5) \
     X(32, 256, 128, 1, 4, 32, 2, 0, 0) \
     X(32, 128, 256, 1, 4, 32, 2, 0, 3) \
     X(32, 32, 256, 1, 1, 32, 3, 0, 4) \
-    X(16, 256, 256, 1, 4, 16, 2, 1, 4) \
-    X(16, 128, 256, 1, 4, 16, 4, 4, 3) \
-    X(16, 64, 256, 1, 4, 16, 4, 0, 1) \
+    X(16, 256, 256, 1, 4, 16, 2, 1, 5) \
+    X(16, 128, 256, 1, 4, 16, 4, 5, 3) \
+    X(16, 64, 256, 1, 4, 16, 4, 0, 5) \
     X(16, 16, 256, 1, 1, 16, 4, 0, 4)
 
 #define G355_VARIANTS_BF16(X) \
