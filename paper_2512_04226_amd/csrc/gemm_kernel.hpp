@@ -67,6 +67,18 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define G355_LDS __attribute__((address_space(3)))
+// K-loop form 5's scheduling fence after MFMA m of a k-step
+#ifndef G355_LF5_EVERY
+#define G355_LF5_EVERY 1
+#endif
+#ifndef G355_LF5_MASK
+#define G355_LF5_MASK 0
+#endif
+#define G355_LF5_FENCE(m)                                      \
+    do {                                                       \
+        if ((m) % G355_LF5_EVERY == G355_LF5_EVERY - 1)        \
+            __builtin_amdgcn_sched_barrier(G355_LF5_MASK);     \
+    } while (0)
 // Cache-policy operand of the slab loads: 0 = default, 2 = the instruction's `nt` (non-temporal) modifier.
 #define G355_LOAD_DEFAULT 0
 #define G355_LOAD_STREAM 2
@@ -623,6 +635,10 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     constexpr int LF = T::LF;
     // form 3: LDS read instructions per k-step and how they are spread over its MN MFMAs
     constexpr int MN = T::TM * T::TN;
+#ifndef G355_LF5_SPREAD4
+#define G355_LF5_SPREAD4 2      // quarters of a k-step's MFMAs over which the next fragments' reads are spread
+#endif
+    constexpr int H5 = MN * G355_LF5_SPREAD4 / 4 > 0 ? MN * G355_LF5_SPREAD4 / 4 : 1;   // form 5: MFMAs of a k-step that carry the next k-step's fragment reads
     constexpr int NFR = T::TM * (ES == 2 ? 1 : 2) + T::TN * (T::BL == 1 ? (ES == 2 ? 1 : 2) : (ES == 2 ? 2 : 4));
     constexpr int RD_A = (NFR + (MN > 1 ? MN / 2 : 1) - 1) / (MN > 1 ? MN / 2 : 1);
     constexpr int RD_PAIRS = NFR / RD_A, RD_REM = NFR - RD_PAIRS * RD_A;
@@ -662,12 +678,12 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                 // across the fence after it
 #pragma unroll
                 for (int m = 0; m < MN; ++m) {
+                    // fragments u with floor(u * H5 / NF) == m
 #pragma unroll
-                    for (int u = 0; u < NF; ++u)
-                        if (u * (MN / 2 > 0 ? MN / 2 : 1) / NF == m)
-                            load_frag(cur, kstep + 1, (kstep + 1) & 1, u);
+                    for (int u = (m * NF + H5 - 1) / H5; u < ((m + 1) * NF + H5 - 1) / H5 && u < NF; ++u)
+                        load_frag(cur, kstep + 1, (kstep + 1) & 1, u);
                     mma_one(kstep & 1, m / T::TM, m % T::TM);
-                    __builtin_amdgcn_sched_barrier(0);
+                    G355_LF5_FENCE(m);
                 }
                 continue;
             }
@@ -696,16 +712,15 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             // form 5: refill loads one every MN / NL MFMAs, the next slab's first fragments over the first half
 #pragma unroll
             for (int m = 0; m < MN; ++m) {
+                // loads l with floor(l * MN / NL) == m, fragments u with floor(u * H5 / NF) == m
 #pragma unroll
-                for (int l = 0; l < NL; ++l)
-                    if (l * MN / NL == m)
-                        issue_one(mode, tail, l, kt + T::NS, freed);
+                for (int l = (m * NL + MN - 1) / MN; l < ((m + 1) * NL + MN - 1) / MN && l < NL; ++l)
+                    issue_one(mode, tail, l, kt + T::NS, freed);
 #pragma unroll
-                for (int u = 0; u < NF; ++u)
-                    if (u * (MN / 2 > 0 ? MN / 2 : 1) / NF == m)
-                        load_frag(next, 0, 0, u);
+                for (int u = (m * NF + H5 - 1) / H5; u < ((m + 1) * NF + H5 - 1) / H5 && u < NF; ++u)
+                    load_frag(next, 0, 0, u);
                 mma_one((T::KSTEPS - 1) & 1, m / T::TM, m % T::TM);
-                __builtin_amdgcn_sched_barrier(0);
+                G355_LF5_FENCE(m);
             }
             until_barrier(next);
             return;

@@ -48,6 +48,9 @@
 // 16x16x32 MFMA on the larger tiles, eight waves: fewer accumulator register bytes per flop than
 // 32x32x16, which is what counts once the chip is power-limited.  The model prices the 4x2 and the 2x4 wave grid of
 // the 256x256x64 tile alike; the 4x2 one measures 3-4 % faster on 8192^3 and is listed first (earlier wins a tie).
+// (A four-wave grid of this tile -- 128x128 wave tiles, accumulators in AGPRs, K-loop form 5 -- is level with the
+// 4x2 grid on 8192^3 with row-major B and 3-4 % ahead with K-contiguous B, but 3-5 % behind on the irregular shapes
+// that pick this tile: not listed.)
 #define G355_VARIANTS_BF16_4(X)    \
     X(256, 256, 64, 4, 2, 16, 2, 4, 2) \
     X(256, 256, 64, 2, 4, 16, 2, 2, 2) \
