@@ -1,7 +1,7 @@
 """Build the gfx950 shared library in-tree (hipcc for the kernels, g++ for the host-only
 selector).  Usage: python -m paper_2512_04226_amd.build [-f]
 With --out LIB [-DNAME=VALUE ...] it builds a second library with extra kernel defines
-somewhere else, e.g. the three builds `calibrate.py --loop-forms` compares:
+somewhere else, e.g. the builds `calibrate.py --loop-forms` compares:
   python -m paper_2512_04226_amd.build --out /tmp/lf0.so -DG355_FORCE_LOOP_FORM=0"""
 import os
 import subprocess
