@@ -173,7 +173,8 @@ int gemm_select_grouped(int n_groups, const gemm_problem *problems, int dtype, i
     const gemm_hw &hw = hw_current();
     int best_id = -1, best_label = 0;
     double best = 0.0;
-    // fixed enumeration order and a strict '<': the first of equal predictions wins
+    // fixed enumeration order and a strict '<': the first of equal predictions wins (on K-contiguous B one
+    // listed variant goes before the entry it ties with, see variant_wins_tie_on_kc)
     for (int id = 0; id < variant_count(dtype); ++id) {
         double l_total;
         int label;
@@ -347,7 +348,10 @@ int gemm_select_batched(int64_t M, int64_t N, int64_t K, int64_t batch, int dtyp
             gemm_prediction p;
             int gm, gn;
             predict(hw, dtype, b_layout, M, N, K, v, split_k_of(s), stream_k_of(s), &p, &gm, &gn, batch, nullptr, &pairs);
-            if (best_id < 0 || p.l_total < best) {
+            const bool tie_kc = best_id >= 0 && b_layout == GEMM_B_K_CONTIGUOUS && dtype != GEMM_FP8_E4M3 &&
+                                p.l_total == best && s == best_mode && variant_wins_tie_on_kc(v) &&
+                                !variant_wins_tie_on_kc(variant_at(dtype, best_id));
+            if (best_id < 0 || p.l_total < best || tie_kc) {
                 best = p.l_total;
                 best_id = id;
                 best_mode = s;

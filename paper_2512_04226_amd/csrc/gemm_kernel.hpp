@@ -130,11 +130,11 @@ struct Tile {
     static constexpr int FT = FT_;
     static constexpr int RG = RG_;
 #ifdef G355_FORCE_LOOP_FORM
-    static constexpr int LF = G355_FORCE_LOOP_FORM;
+    static constexpr int LF_ASKED = G355_FORCE_LOOP_FORM;
 #else
-    static constexpr int LF = LF_;
+    static constexpr int LF_ASKED = LF_;
 #endif
-    static_assert(LF >= 0 && LF <= 5, "unknown K-loop form");
+    static_assert(LF_ASKED >= 0 && LF_ASKED <= 6, "unknown K-loop form");
     static_assert(FT == 0 || ES == 2, "fp16 is a 16-bit input type");
     static constexpr int NW = WM * WN;
     static constexpr int NT = WM * WN * 64;
@@ -152,6 +152,9 @@ struct Tile {
     static constexpr int KG = 64 / MI;                      // lane groups along k
     static constexpr int KL = KI / KG;                      // k elements held by one lane
     static constexpr int KSTEPS = BK / KI;
+    // form 6 needs at least three B fragments per k-step and a whole number of four-slot ring turns per slab;
+    // a tile that has neither runs form 0 when form 6 is forced on every tile
+    static constexpr int LF = (LF_ASKED == 6 && !(TN >= 3 && (KSTEPS * TN) % 4 == 0 && KSTEPS >= 2)) ? 0 : LF_ASKED;
     static constexpr int RA = BK * ES;                      // bytes per A row in LDS
     static constexpr int RB = (BL == 0) ? BN * ES : BK * ES; // bytes per B row in LDS (a k row, or an n row when K-contiguous)
     static constexpr int A_BYTES = BM * RA, B_BYTES = BK * BN * ES;
@@ -554,7 +557,8 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
 
     // Fragment `u` of k-step `kstep` of LDS stage `stage` into register buffer `buf`:
     // u < TM is the A fragment of MFMA tile row u, otherwise the B fragment of tile column u-TM.
-    auto load_frag = [&](const G355_LDS uint8_t *sA, int kstep, int buf, int u) {
+    // (`dslot` >= 0: a B fragment goes to slot dslot of the flat B register array instead of [buf][j]: K-loop form 6)
+    auto load_frag = [&](const G355_LDS uint8_t *sA, int kstep, int buf, int u, int dslot = -1) {
         const G355_LDS uint8_t *sB = sA + T::A_BYTES;
         const int k0 = kstep * T::KI;
         if (u < T::TM) {
@@ -570,14 +574,15 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             }
         } else {
             const int j = u - T::TM;
+            frag_t &dst = dslot < 0 ? bfr[buf][j] : bfr[dslot / T::TN][dslot % T::TN];
             if constexpr (T::BL == 1 && ES == 2) {
                 const int chunk = (k0 + a_kg * T::KL) / 8;
-                bfr[buf][j] = *(const G355_LDS bf16x8 *)(sB + T::a_off(bk_row + j * MI, chunk));
+                dst = *(const G355_LDS bf16x8 *)(sB + T::a_off(bk_row + j * MI, chunk));
             } else if constexpr (T::BL == 1) {
                 const int chunk = (k0 + a_kg * T::KL) / 16;
                 i32x4 lo = *(const G355_LDS i32x4 *)(sB + T::a_off(bk_row + j * MI, chunk));
                 i32x4 hi = *(const G355_LDS i32x4 *)(sB + T::a_off(bk_row + j * MI, chunk + 1));
-                bfr[buf][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                dst = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             } else if constexpr (ES == 2) {
                 short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                     (G355_LDS short4_t *)(sB + T::b_off(k0 + b_krow_l, (b_ncol + j * MI) * 2)));
@@ -585,7 +590,7 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                     (G355_LDS short4_t *)(sB + T::b_off(k0 + b_krow_l + TRK, (b_ncol + j * MI) * 2)));
                 typedef short short8_t __attribute__((ext_vector_type(8)));
                 short8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                bfr[buf][j] = __builtin_bit_cast(bf16x8, v);
+                dst = __builtin_bit_cast(bf16x8, v);
             } else {
                 int2_t q[4];
 #pragma unroll
@@ -594,27 +599,31 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
                         (G355_LDS int2_t *)(sB + T::b_off(k0 + b_krow_l + h * TRK, b_ncol + j * MI)));
                 i32x4 lo = __builtin_shufflevector(q[0], q[1], 0, 1, 2, 3);
                 i32x4 hi = __builtin_shufflevector(q[2], q[3], 0, 1, 2, 3);
-                bfr[buf][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                dst = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
         }
     };
     constexpr int NF = T::TM + T::TN;     // fragments per k-step
-    auto mma_one = [&](int buf, int j, int i) {
+    // acc[j][i] += B fragment in flat slot `bslot` x A fragment af[abuf][i]
+    auto mma_ops = [&](int bslot, int abuf, int j, int i) {
+        const frag_t &bf_ = bfr[bslot / T::TN][bslot % T::TN];
+        const frag_t &af_ = af[abuf][i];
         if constexpr (ES == 2 && T::FT == 1 && MI == 32)
-            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, bfr[buf][j]),
-                                                               __builtin_bit_cast(f16x8, af[buf][i]), acc[j][i], 0, 0, 0);
+            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, bf_),
+                                                               __builtin_bit_cast(f16x8, af_), acc[j][i], 0, 0, 0);
         else if constexpr (ES == 2 && T::FT == 1)
-            acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, bfr[buf][j]),
-                                                               __builtin_bit_cast(f16x8, af[buf][i]), acc[j][i], 0, 0, 0);
+            acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, bf_),
+                                                               __builtin_bit_cast(f16x8, af_), acc[j][i], 0, 0, 0);
         else if constexpr (ES == 2 && MI == 32)
-            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[buf][j], af[buf][i], acc[j][i], 0, 0, 0);
+            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf_, af_, acc[j][i], 0, 0, 0);
         else if constexpr (ES == 2)
-            acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[buf][j], af[buf][i], acc[j][i], 0, 0, 0);
+            acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf_, af_, acc[j][i], 0, 0, 0);
         else if constexpr (MI == 32)
-            acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bfr[buf][j], af[buf][i], acc[j][i], 0, 0, 0, 0, 0, 0);
+            acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bf_, af_, acc[j][i], 0, 0, 0, 0, 0, 0);
         else
-            acc[j][i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bfr[buf][j], af[buf][i], acc[j][i], 0, 0, 0, 0, 0, 0);
+            acc[j][i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf_, af_, acc[j][i], 0, 0, 0, 0, 0, 0);
     };
+    auto mma_one = [&](int buf, int j, int i) { mma_ops(buf * T::TN + j, buf, j, i); };
 
     // ---- pipeline: prologue, main K loop, epilogue (Algorithm 8's three phases) ----
     // Ring of NS LDS stages; slab kt lives in stage kt % NS.  One barrier per slab, placed
@@ -802,6 +811,80 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
             for (int l = 0; l < NL; ++l)
                 issue_one(mode, std::true_type{}, l, s, lds + s * T::STAGE);
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((T::NS - 1) * FULL) : "memory");
+        if constexpr (LF == 6) {
+            // Form 6: B fragments are not double-buffered per k-step but pass through a ring of R6 register
+            // slots, each read D6 blocks ahead of its use (a block = the TM MFMAs that share one B fragment; a
+            // slab has NB of them).  Only the A fragments keep two buffers.  That is 48 fewer registers in the
+            // 256x256 eight-wave tiles, whose loop then fits without the compiler folding the buffers together.
+            // The current stage is read until block NB-1-D6 has issued its prefetch, so the slab's barrier sits
+            // there; the refill and the next slab's first fragments go out in the D6 blocks after it.
+            constexpr int NB = T::KSTEPS * T::TN, D6 = 3, R6 = 4, TM_ = T::TM, TN_ = T::TN;
+            static_assert(TN_ >= D6 && NB % R6 == 0 && 2 * TN_ >= R6 && T::KSTEPS >= 2, "tile does not fit K-loop form 6");
+            auto mfmas = [&](int f) __attribute__((always_inline)) {
+#pragma unroll
+                for (int i = 0; i < TM_; ++i)
+                    mma_ops(f % R6, (f / TN_) & 1, f % TN_, i);
+            };
+            // blocks 0 .. NB-D6-1 of the slab in `st`, then its barrier
+            auto head = [&](const G355_LDS uint8_t *st) __attribute__((always_inline)) {
+#pragma unroll
+                for (int f = 0; f < NB - D6; ++f) {
+                    const int g = f + D6, kstep = f / TN_, j = f % TN_;
+                    load_frag(st, g / TN_, 0, TM_ + g % TN_, g % R6);
+                    if (kstep + 1 < T::KSTEPS) {
+#pragma unroll
+                        for (int i = (j * TM_ + TN_ - 1) / TN_; i < ((j + 1) * TM_ + TN_ - 1) / TN_ && i < TM_; ++i)
+                            load_frag(st, kstep + 1, (kstep + 1) & 1, i);
+                    }
+                    mfmas(f);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                publish();
+            };
+            // from the barrier of slab kt to the barrier of slab kt + 1
+            auto span = [&](auto tail, G355_LDS uint8_t *__restrict__ freed, const G355_LDS uint8_t *__restrict__ next, int kt)
+                            __attribute__((always_inline)) {
+#pragma unroll
+                for (int t = 0; t < D6; ++t) {
+                    const int f = NB - D6 + t;
+#pragma unroll
+                    for (int l = (t * NL + D6 - 1) / D6; l < ((t + 1) * NL + D6 - 1) / D6 && l < NL; ++l)
+                        issue_one(mode, tail, l, kt + T::NS, freed);
+                    load_frag(next, 0, 0, TM_ + t, (f + D6) % R6);
+#pragma unroll
+                    for (int i = (t * TM_ + D6 - 1) / D6; i < ((t + 1) * TM_ + D6 - 1) / D6 && i < TM_; ++i)
+                        load_frag(next, 0, 0, i);
+                    mfmas(f);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                head(next);
+            };
+#pragma unroll
+            for (int i = 0; i < TM_; ++i)
+                load_frag(lds, 0, 0, i);
+#pragma unroll
+            for (int g = 0; g < D6; ++g)
+                load_frag(lds, 0, 0, TM_ + g, g % R6);
+            head(lds);
+            int stage6 = 0, kt6 = 0;
+            const int end6 = kt_count - 1;
+            int main6 = k_len / BK - T::NS;
+            main6 = main6 < end6 ? main6 : end6;
+            for (; kt6 < main6; ++kt6) {
+                const int next = (stage6 + 1 == T::NS) ? 0 : stage6 + 1;
+                span(std::false_type{}, lds + stage6 * T::STAGE, lds + next * T::STAGE, kt6);
+                stage6 = next;
+            }
+            for (; kt6 < end6; ++kt6) {
+                const int next = (stage6 + 1 == T::NS) ? 0 : stage6 + 1;
+                span(std::true_type{}, lds + stage6 * T::STAGE, lds + next * T::STAGE, kt6);
+                stage6 = next;
+            }
+#pragma unroll
+            for (int f = NB - D6; f < NB; ++f)
+                mfmas(f);
+            return;
+        }
 #pragma unroll
         for (int u = 0; u < NF; ++u)
             load_frag(lds, 0, 0, u);

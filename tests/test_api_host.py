@@ -57,7 +57,7 @@ def test_variant_table_loop_form_columns_cover_every_compiled_variant():
             if c is not None:
                 seen.add((sect, c.block_m, c.block_n, c.block_k, c.waves_m, c.waves_n, c.mfma, c.stages))
         assert seen == set(rows)
-    assert all(lf in range(6) and lf_kc in range(6) for lf, lf_kc in forms.values())
+    assert all(lf in range(7) and lf_kc in range(7) for lf, lf_kc in forms.values())
 
 
 def test_uniform128_shapes_follow_the_papers_recipe():
