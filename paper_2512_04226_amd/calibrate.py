@@ -13,11 +13,12 @@ Prints the descriptor fields the probes give and one line per variant (B row-maj
 
     python -m paper_2512_04226_amd.calibrate [--n 8192]
 
-The K-loop form of each variant (LOOP / LOOP_KC columns) is chosen from a comparison of three
-builds of the library, each with one form forced on every variant:
+The K-loop form of each variant (LOOP / LOOP_KC columns) is chosen from a comparison of
+builds of the library, one per form (0 .. 6), each with that form forced on every variant (a tile that
+does not fit form 6 runs form 0 in that build):
 
-    for k in 0 1 2 3 4 5: python -m paper_2512_04226_amd.build --out /tmp/lf$k.so -DG355_FORCE_LOOP_FORM=$k
-    python -m paper_2512_04226_amd.calibrate --loop-forms /tmp/lf0.so /tmp/lf1.so /tmp/lf2.so /tmp/lf3.so /tmp/lf4.so /tmp/lf5.so
+    for k in 0 1 2 3 4 5 6: python -m paper_2512_04226_amd.build --out /tmp/lf$k.so -DG355_FORCE_LOOP_FORM=$k
+    python -m paper_2512_04226_amd.calibrate --loop-forms /tmp/lf0.so /tmp/lf1.so /tmp/lf2.so /tmp/lf3.so /tmp/lf4.so /tmp/lf5.so /tmp/lf6.so
 
 which ends with the table rows carrying the chosen forms.
 """

@@ -168,6 +168,36 @@ def test_pick_is_the_oracle_argmin():
         assert (pick.kernel_id, pick.split_k, pick.stream_k) == best[1:], (M, N, K, pick.describe())
 
 
+@pytest.mark.parametrize("dtype", [0, 2])
+def test_pick_on_k_contiguous_b_is_the_oracle_argmin_up_to_the_one_listed_tie(dtype):
+    """On K-contiguous B the pick has the oracle's minimum latency; it is the first such entry in enumeration order unless
+    that entry is the 4x2 wave grid of the 16-bit 256x256x64 tile (16x16x32 MFMA, two stages), whose exact tie with the 2x4
+    grid of the same tile goes to the 2x4 grid on this layout (same split / Stream-K mode)."""
+    from paper_2512_04226_amd import binding as g
+    hw = _hw_dict(g)
+    n_exception = 0
+    for (M, N, K) in SHAPES:
+        rows = []
+        for idx in range(g.gemm_cfg_count(dtype)):
+            c = g.gemm_cfg_at_ex(idx, M, N, K, dtype, 1)
+            if c is None:
+                continue
+            t = sm.predict(hw, dtype, M, N, K, _variant_dict(c), c.split_k, 1, c.stream_k)["l_total"]
+            rows.append((t, c))
+        t_min = min(t for t, _ in rows)
+        first = next(c for t, c in rows if t <= t_min * (1 + 1e-12))
+        pick = g.gemm_select_ex(M, N, K, dtype, 1)
+        t_pick = sm.predict(hw, dtype, M, N, K, _variant_dict(pick), pick.split_k, 1, pick.stream_k)["l_total"]
+        assert t_pick == pytest.approx(t_min, rel=1e-12), (M, N, K, pick.describe())
+        key = lambda c: (c.kernel_id, c.split_k, c.stream_k)
+        if key(pick) != key(first):
+            tile = lambda c: (c.block_m, c.block_n, c.block_k, c.mfma, c.stages, c.split_k, c.stream_k)
+            assert tile(pick) == tile(first) == (256, 256, 64, 16, 2, first.split_k, first.stream_k), (M, N, K, pick.describe())
+            assert (first.waves_m, first.waves_n) == (4, 2) and (pick.waves_m, pick.waves_n) == (2, 4)
+            n_exception += 1
+    assert n_exception >= 1      # 8192^3 and 4096^3 take the 2x4 grid
+
+
 def test_retargeting_to_a_304_cu_table_changes_waves_cache_tiles_and_candidates():
     """Section I / V: the selector is ported by swapping the hardware table.  Under the 304-CU table
     Algorithm 4 must count waves of 304 tiles and Algorithm 6 must factor 38 CUs per L2; every
