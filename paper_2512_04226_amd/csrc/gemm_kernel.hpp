@@ -814,8 +814,8 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         if constexpr (LF == 6) {
             // Form 6: B fragments are not double-buffered per k-step but pass through a ring of R6 register
             // slots, each read D6 blocks ahead of its use (a block = the TM MFMAs that share one B fragment; a
-            // slab has NB of them).  Only the A fragments keep two buffers.  That is 48 fewer registers in the
-            // 256x256 eight-wave tiles, whose loop then fits without the compiler folding the buffers together.
+            // slab has NB of them).  Only the A fragments keep two buffers.  That is 16 (2x4 wave grid) or 48 (4x2) fewer registers in
+            // the 256x256x64 eight-wave tiles, whose loop then fits without the compiler folding the buffers together.
             // The current stage is read until block NB-1-D6 has issued its prefetch, so the slab's barrier sits
             // there; the refill and the next slab's first fragments go out in the D6 blocks after it.
             constexpr int NB = T::KSTEPS * T::TN, D6 = 3, R6 = 4, TM_ = T::TM, TN_ = T::TN;
