@@ -87,7 +87,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // layout of the paper's own runs, Section V): B is then staged and read exactly like A.
 // FT_ (16-bit inputs only): 0 bf16 in / bf16 out, 1 IEEE fp16 in / fp16 out (the precision of the
 // paper's runs); the data path is the same, only the MFMA instruction and the output rounding differ.
-// LF_: form of the K loop, one of six source arrangements of the same work between which the
+// LF_: form of the K loop, one of seven source arrangements of the same work between which the
 // compiler's instruction schedule, and with it the time per slab, differs by up to 15 % either
 // way; which one a variant uses is measured (8192^3, the forms interleaved) and recorded
 // in the variant table.  0: one loop over all slabs, the part up to the next barrier under a
@@ -108,6 +108,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // MFMAs), and a scheduling fence after each MFMA keeps the compiler from moving anything across it.  Both fragment
 // buffers are then live through every k-step: the four-wave tiles and several medium tiles gain 3-13 %, the 256x256
 // eight-wave tiles on a 4x2 grid would spill.
+// 6: only the A fragments are double-buffered; the B fragments pass through a ring of four register slots that is
+// read three (k-step, column) blocks ahead of the MFMAs, and the slab's barrier follows the last fragment read of
+// the stage, not its last MFMA.  Fewer live registers than form 5 (the eight-wave 256x256x64 tiles keep no spills);
+// needs three or more column blocks per wave and a multiple of four blocks per slab, else the tile runs form 0.
 // Building with -DG355_FORCE_LOOP_FORM=k gives every variant form k (how the forms are compared).
 // Timing-only diagnostic builds (their RESULTS ARE WRONG; every access stays in bounds and every wait ends):
 // -DG355_DIAG_SKIP_FILL leaves the refills out of the K loop (the ring keeps its first NS slabs),

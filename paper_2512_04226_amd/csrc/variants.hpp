@@ -2,9 +2,10 @@
 // the paper speaks of 75 searched configurations; Section V-E of 50-150 valid tiles per
 // datatype).  One line per instantiation of gemm_kernel<>:
 //   X(BLOCK_M, BLOCK_N, BLOCK_K, WAVES_M, WAVES_N, MFMA, LDS_STAGES, LOOP, LOOP_KC)
-// LOOP / LOOP_KC: the K-loop form (0 to 4, see Tile in gemm_kernel.hpp) the instantiation for
-// row-major / K-contiguous B is compiled with: the fastest of the five on 8192^3 where one is
-// at least 1.5 % faster than form 0 (bf16 and fp16 timings together for the 16-bit list), else 0.
+// LOOP / LOOP_KC: the K-loop form (0 to 6, see Tile in gemm_kernel.hpp) the instantiation for
+// row-major / K-contiguous B is compiled with: the fastest of forms 0 to 4 on 8192^3 where one is
+// at least 1.5 % faster than form 0 (bf16 and fp16 timings together for the 16-bit list), else 0;
+// form 5 or 6 where it beat that choice by 3 % (form 6: 2 %) or more.
 // The table holds no timing: the selector prices a variant from its shape and the hardware
 // descriptor alone (Algorithm 3's instruction count times the measured issue interval, plus the
 // slab's fill and synchronisation cost).
