@@ -32,7 +32,6 @@
 #define G355_VARIANTS_BF16_2(X)    \
     X(64, 64, 64, 2, 2, 32, 3, 3, 0) \
     X(64, 64, 128, 2, 2, 32, 2, 4, 0) \
-    X(128, 32, 64, 4, 1, 32, 3, 0, 0) \
     X(32, 256, 64, 1, 4, 32, 2, 2, 0) \
     X(32, 128, 64, 1, 4, 32, 3, 0, 0) \
     X(32, 128, 128, 1, 4, 32, 2, 0, 0) \
@@ -60,7 +59,6 @@
     X(256, 128, 64, 2, 4, 16, 3, 3, 3) \
     X(128, 256, 64, 2, 4, 16, 3, 4, 3) \
     X(128, 128, 64, 2, 4, 16, 2, 2, 0) \
-    X(128, 64, 64, 2, 4, 16, 3, 4, 0) \
     X(64, 128, 64, 2, 4, 16, 3, 4, 1) \
     X(128, 64, 64, 2, 4, 16, 2, 0, 1) \
     X(64, 128, 64, 2, 4, 16, 2, 0, 0) \
@@ -84,7 +82,6 @@
     X(128, 256, 128, 2, 4, 32, 3, 4, 4) \
     X(128, 128, 128, 2, 2, 32, 2, 5, 5) \
     X(128, 128, 128, 2, 2, 32, 3, 5, 5) \
-    X(128, 128, 256, 2, 2, 32, 2, 3, 5) \
     X(128, 64, 128, 2, 2, 32, 3, 0, 4) \
     X(64, 128, 128, 2, 2, 32, 3, 0, 2)
 #define G355_VARIANTS_FP8_1(X)     \
