@@ -136,6 +136,14 @@ def secondary(also, g, wl, np, torch, dev, sizes, timed_us, ensure_ws):
                                             "frac_of_hbm_peak": sk_bytes / us * 1e-3 / PEAK_HBM_GBPS,
                                             "picked": cfgs.describe()}
     also["hbm_stream_gbps"] = g.gemm_probe_stream(dBs, scratch)
+    # the same weights stored N x K (K-contiguous, a row pitch of 16 KiB): the tiles walk K in a rotated order
+    dBk = dBs.t().contiguous()
+    cfgk = g.gemm_select_ex(Ms, Ns, Ks, g.GEMM_BF16, g.GEMM_B_K_CONTIGUOUS)
+    us = timed_us(cfgk, torch.from_numpy(As.view(np.int16)).cuda(), dBk, torch.empty((Ms, Ns), dtype=torch.int16, device="cuda"))
+    also["skinny_bf16_M16_N28672_K8192_b_k_contiguous"] = {"us": us, "gbps": sk_bytes / us * 1e-3,
+                                                           "frac_of_hbm_peak": sk_bytes / us * 1e-3 / PEAK_HBM_GBPS,
+                                                           "picked": cfgk.describe()}
+    del dBk
     # the same weight against 256 rows: still on the HBM side of the ridge (61 us of bytes, 48 us of flops at the peaks)
     Mw = 256
     dAw = torch.randn((Mw, Ks), device="cuda", generator=torch.Generator(device="cuda").manual_seed(2)).to(torch.bfloat16)

@@ -443,10 +443,25 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     // `mode` (a std::integral_constant): 0 default cache policy, 1 the B loads stream (one tile row), 2 the A loads
     // stream (one tile column).  A compile-time constant, chosen once outside the K loop: a run-time choice per
     // load would put every load into a basic block of its own and take the loop's schedule apart.
+    // Weight streaming (mode 1) from K-contiguous weights whose row pitch is a power of two (K = 4096, 8192, ...)
+    // walks the K range in a rotated order, workgroup tn starting tn slabs in.  The workgroups of a one-row grid
+    // advance through K in step, and with such a pitch the rows of every workgroup's slab fall into the same few
+    // memory channels at any one time (M = 16, N = 28672, K = 8192 bf16: 83 us, 68 with the pitch padded by 256 bytes,
+    // 69 rotated; fp8 40 -> 35).  Started at different slabs they spread over all channels.  Other pitches gain
+    // nothing (K = 28672: +-2 %), and row-major B loses 1-20 % (there the workgroups' simultaneous reads of adjacent
+    // pieces of the same rows are what keeps DRAM pages open): both keep the plain order.  Only for whole slabs (K
+    // range a multiple of BLOCK_K), so that no slab of the rotated order needs the test against the end of K.
+    int rot = 0;
     auto issue_one = [&](auto mode, auto tail, int l, int slab, G355_LDS uint8_t *sbase) {
         constexpr int MODE = decltype(mode)::value;
         constexpr bool TAIL = decltype(tail)::value;     // false: the slab lies wholly inside the K range
-        const int kk = slab * BK;
+        int kk = slab * BK;
+        if constexpr (MODE == 1 && T::BL == 1) {
+            // logical slab -> position in K; slabs requested past the last one stay outside the range
+            int p = slab + rot;
+            p = p >= kt_count ? p - kt_count : p;
+            kk = (!TAIL || slab < kt_count) ? p * BK : kt_count * BK;
+        }
         if (l < T::A_LOADS) {
             const int i = l, u = i * T::NW + wave;
             if (T::A_UNITS % T::NW == 0 || u < T::A_UNITS) {
@@ -809,6 +824,10 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         }
     } else if (kt_count > 0) {
       auto pipeline = [&](auto mode) __attribute__((always_inline)) {
+        if constexpr (decltype(mode)::value == 1 && T::BL == 1) {
+            const unsigned pitch = (unsigned)pldb * ES;
+            rot = (k_len % BK == 0 && pitch >= 8192 && (pitch & (pitch - 1)) == 0) ? tn % kt_count : 0;
+        }
 #pragma unroll
         for (int s = 0; s < T::NS; ++s)
 #pragma unroll

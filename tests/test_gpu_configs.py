@@ -283,6 +283,38 @@ def test_k_contiguous_b_fp8_and_padded_ldb(g, oracle):
         assert np.array_equal(out, ref16), (c.describe(), int((out != ref16).sum()))
 
 
+@pytest.mark.parametrize("M", [1, 16, 32])
+def test_k_contiguous_weights_with_a_power_of_two_pitch(g, oracle, M):
+    """One tile row over K-contiguous weights whose row pitch is a power of two (K = 4096 bf16, 8192 fp8): the tiles of
+    at most 32 rows then walk K in an order rotated by their tile column (whole slabs; also inside every K split).
+    Integer operands: any order of the K sum is exact, so every configuration must match the oracle bit for bit.
+    A second K (a power-of-two pitch of the allocation, K itself not a whole number of slabs) takes the plain order."""
+    from gpu_util import run_cfg, to_dev
+    N = 1000
+    for dtype, K, ld in ((BF16, 4096, 4096), (BF16, 4000, 4096), (E4M3, 8192, 8192)):
+        if dtype == BF16:
+            A, B = wl.integer_bf16(M, N, K, seed=77, case=M + K)
+        else:
+            gen = np.random.default_rng(M + K)
+            vals = np.array([0, 1, 2, 3, 4, -1, -2, -3, -4], dtype=np.float64)
+            A = oracle.encode_e4m3(vals[gen.integers(0, 9, size=(M, K))])
+            B = oracle.encode_e4m3(vals[gen.integers(0, 9, size=(K, N))])
+        ref16, _ = oracle.gemm(A, B, dtype)
+        Bt = np.zeros((N, ld), B.dtype)
+        Bt[:, :K] = B.T
+        dA, dBt = to_dev(A), to_dev(Bt)
+        n_small = 0
+        for idx in range(g.gemm_cfg_count(dtype)):
+            c = g.gemm_cfg_at_ex(idx, M, N, K, dtype, g.GEMM_B_K_CONTIGUOUS)
+            if c is None:
+                continue
+            c.ldb = ld
+            out = run_cfg(c, dA, dBt, M, N)
+            assert np.array_equal(out, ref16), (c.describe(), K, int((out != ref16).sum()))
+            n_small += c.block_m <= 32
+        assert n_small >= 20
+
+
 def test_k_contiguous_b_square_4096(g, oracle):
     """All 4096 x 4096 outputs with B stored N x K."""
     n = 4096
