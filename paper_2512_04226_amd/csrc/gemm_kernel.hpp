@@ -149,7 +149,16 @@ struct Tile {
     // Compiled only into the tiles of at most 32 rows, the ones the selector gives weight-streaming shapes
     // (M <= 32): with a second or third copy of the loop the compiler keeps more values live across all of
     // them, and the 64- to 128-row tiles then lose a resident workgroup (128x128x64: 120 -> 148 registers).
-    static constexpr bool STREAMABLE_B = BM <= 32, STREAMABLE_A = false;
+    // (The 16-bit 64x128x64 four-stage tile, which one-row grids of 33 to 64 rows are given, carries the copy too: its
+    // four stages leave room for one workgroup per CU whatever its registers.)
+    static constexpr bool STREAMABLE_B = BM <= 32 || (ES == 2 && MI == 16 && BM == 64 && BN == 128 && BK == 64 && NS == 4),
+                          STREAMABLE_A = false;
+    // K-contiguous B: a one-row grid may walk K in a rotated order (see `rot` in gemm_kernel).  Compiled into the
+    // weight-streaming copy of the loop (see STREAMABLE_B) and, of the other tiles, into the one that one-row grids
+    // of 129 to 256 rows are given, whose K-loop form prescribes the instruction order (+-1 % on other shapes): the
+    // few scalar instructions per slab changed the compiler's schedule of the freely scheduled loops (128x128x64:
+    // 4-7 % slower on every shape, the 256x256 tiles 1-2 %, 64x128x64 with four stages 3-5 %).
+    static constexpr bool ROTATES_TALL = BL == 1 && ES == 2 && MI == 16 && BN == 128 && BK == 64 && BM == 256 && NS == 3;
     static constexpr int WTM = BM / WM, WTN = BN / WN;      // wave tile
     static constexpr int TM = WTM / MI, TN = WTN / MI;      // MFMA tiles per wave
     static constexpr int KI = (ES == 2) ? (MI == 32 ? 16 : 32) : (MI == 32 ? 64 : 128);  // MI_K
@@ -332,6 +341,11 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         logical_tile(tiles_m, tiles_n, uniform_i32(r->group_m), t, g_tm, g_tn);
     }
 
+    // Weights that fit the memory-side cache twice over are left to it: a caller that multiplies by the same weights
+    // again soon finds them there (M = 48, N = 14336, K = 4096 in a loop: 21 us cached, 31 us streamed), and the
+    // K order is only worth changing for what comes from HBM.
+    stream_b = stream_b && (size_t)pN * (size_t)pK * ES > ((size_t)128 << 20);
+
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept scalar
@@ -443,20 +457,22 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     // `mode` (a std::integral_constant): 0 default cache policy, 1 the B loads stream (one tile row), 2 the A loads
     // stream (one tile column).  A compile-time constant, chosen once outside the K loop: a run-time choice per
     // load would put every load into a basic block of its own and take the loop's schedule apart.
-    // Weight streaming (mode 1) from K-contiguous weights whose row pitch is a power of two (K = 4096, 8192, ...)
-    // walks the K range in a rotated order, workgroup tn starting tn slabs in.  The workgroups of a one-row grid
-    // advance through K in step, and with such a pitch the rows of every workgroup's slab fall into the same few
-    // memory channels at any one time (M = 16, N = 28672, K = 8192 bf16: 83 us, 68 with the pitch padded by 256 bytes,
-    // 69 rotated; fp8 40 -> 35).  Started at different slabs they spread over all channels.  Other pitches gain
-    // nothing (K = 28672: +-2 %), and row-major B loses 1-20 % (there the workgroups' simultaneous reads of adjacent
-    // pieces of the same rows are what keeps DRAM pages open): both keep the plain order.  Only for whole slabs (K
-    // range a multiple of BLOCK_K), so that no slab of the rotated order needs the test against the end of K.
+    // A one-row grid (M <= BLOCK_M: every byte of B is read once) over K-contiguous weights whose row pitch is a power
+    // of two of 16 KiB or more (bf16 K = 8192, ...; from 8 KiB for the tiles of at most 32 rows) walks the K range in
+    // a rotated order, workgroup tn starting tn slabs in.  The workgroups of such a grid advance through K in step, and with such a pitch the rows of every
+    // workgroup's slab fall into the same few memory channels at any one time (N = 28672, K = 8192 bf16: M = 16 83 us,
+    // 68 with the pitch padded by 256 bytes, 69 rotated; M = 64 103 -> 82, M = 256 151 -> 126).  Started at different
+    // slabs they spread over all channels.  Other pitches gain nothing (K = 28672: +-2 %; 8 KiB: fp8 K = 8192 at M = 16 39 -> 35 us
+    // with the small tiles, +2-4 % with the taller ones), and
+    // row-major B loses 1-20 % (there the workgroups' simultaneous reads of adjacent pieces of the same rows are what
+    // keeps DRAM pages open): both keep the plain order.  Only for whole slabs (K range a multiple of BLOCK_K), so
+    // that no slab of the rotated order needs the test against the end of K.
     int rot = 0;
     auto issue_one = [&](auto mode, auto tail, int l, int slab, G355_LDS uint8_t *sbase) {
         constexpr int MODE = decltype(mode)::value;
         constexpr bool TAIL = decltype(tail)::value;     // false: the slab lies wholly inside the K range
         int kk = slab * BK;
-        if constexpr (MODE == 1 && T::BL == 1) {
+        if constexpr (T::BL == 1 && (MODE == 1 || T::ROTATES_TALL)) {
             // logical slab -> position in K; slabs requested past the last one stay outside the range
             int p = slab + rot;
             p = p >= kt_count ? p - kt_count : p;
@@ -824,9 +840,10 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         }
     } else if (kt_count > 0) {
       auto pipeline = [&](auto mode) __attribute__((always_inline)) {
-        if constexpr (decltype(mode)::value == 1 && T::BL == 1) {
+        if constexpr (T::BL == 1 && (decltype(mode)::value == 1 || T::ROTATES_TALL)) {
             const unsigned pitch = (unsigned)pldb * ES;
-            rot = (k_len % BK == 0 && pitch >= 8192 && (pitch & (pitch - 1)) == 0) ? tn % kt_count : 0;
+            constexpr unsigned MIN_PITCH = BM <= 32 ? 8192 : 16384;
+            rot = (stream_b && k_len % BK == 0 && pitch >= MIN_PITCH && (pitch & (pitch - 1)) == 0) ? tn % kt_count : 0;
         }
 #pragma unroll
         for (int s = 0; s < T::NS; ++s)

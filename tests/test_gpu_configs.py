@@ -283,15 +283,20 @@ def test_k_contiguous_b_fp8_and_padded_ldb(g, oracle):
         assert np.array_equal(out, ref16), (c.describe(), int((out != ref16).sum()))
 
 
-@pytest.mark.parametrize("M", [1, 16, 32])
+@pytest.mark.parametrize("M", [1, 16, 100])
 def test_k_contiguous_weights_with_a_power_of_two_pitch(g, oracle, M):
-    """One tile row over K-contiguous weights whose row pitch is a power of two (K = 4096 bf16, 8192 fp8): the tiles of
-    at most 32 rows then walk K in an order rotated by their tile column (whole slabs; also inside every K split).
+    """One tile row over K-contiguous weights of more than 128 MiB whose row pitch is a power of two of at least 16 KiB
+    (K = 8192 bf16, 16384 fp8; from 8 KiB, K = 4096 bf16, for the tiles of at most 32 rows): the tiles that carry the
+    weight-streaming copy of the loop, and the 256x128x64 tile, then walk K in an order rotated by their tile column
+    (whole slabs; also inside every K split; at M = 100 the tiles of 64 rows have two tile rows and keep the plain order).
     Integer operands: any order of the K sum is exact, so every configuration must match the oracle bit for bit.
-    A second K (a power-of-two pitch of the allocation, K itself not a whole number of slabs) takes the plain order."""
+    A second K (the same pitch of the allocation, K itself not a whole number of slabs) takes the plain order."""
     from gpu_util import run_cfg, to_dev
-    N = 1000
-    for dtype, K, ld in ((BF16, 4096, 4096), (BF16, 4000, 4096), (E4M3, 8192, 8192)):
+    cases = [(BF16, 8600, 8192, 8192), (BF16, 8600, 8000, 8192), (BF16, 16400, 4096, 4096)]
+    if M <= 16:
+        cases.append((E4M3, 8600, 16384, 16384))
+    for dtype, N, K, ld in cases:
+        assert N * K * (2 if dtype == BF16 else 1) > 128 << 20
         if dtype == BF16:
             A, B = wl.integer_bf16(M, N, K, seed=77, case=M + K)
         else:
@@ -303,16 +308,17 @@ def test_k_contiguous_weights_with_a_power_of_two_pitch(g, oracle, M):
         Bt = np.zeros((N, ld), B.dtype)
         Bt[:, :K] = B.T
         dA, dBt = to_dev(A), to_dev(Bt)
-        n_small = 0
+        n_one_row = 0
         for idx in range(g.gemm_cfg_count(dtype)):
             c = g.gemm_cfg_at_ex(idx, M, N, K, dtype, g.GEMM_B_K_CONTIGUOUS)
-            if c is None:
+            if c is None or (c.split_k > 4 and not c.stream_k) or (c.block_m < M and c.split_k > 1):
                 continue
             c.ldb = ld
             out = run_cfg(c, dA, dBt, M, N)
             assert np.array_equal(out, ref16), (c.describe(), K, int((out != ref16).sum()))
-            n_small += c.block_m <= 32
-        assert n_small >= 20
+            n_one_row += c.block_m >= M
+        assert n_one_row >= 10
+        del dBt
 
 
 def test_k_contiguous_b_square_4096(g, oracle):
