@@ -168,7 +168,7 @@ def slab_compute(hw, v, dtype):
 
 
 def level_times(hw, v, es, b_layout, tiles_per_cu, active_cus, h_first, h_second, rows_valid, cols_valid,
-                tiles_per_cu_moving=None, hbm_share="neither"):
+                tiles_per_cu_moving=None, hbm_share="neither", one_tile_row=False):
     """Algorithm 7 in bytes and clocks for one K step, with these READINGS:
     * Ld_CU (undefined in the paper) is the slab of every tile a CU works on: the load INSTRUCTIONS cover the
       nominal (BM + BN) * BK elements, the BYTES that move only the valid rows and columns of the tile
@@ -179,7 +179,9 @@ def level_times(hw, v, es, b_layout, tiles_per_cu, active_cus, h_first, h_second
       the transpose-read rate unless it is stored K-contiguous;
     * the share of requested bytes that reaches HBM is what NEITHER cache holds, min(1 - H1, 1 - H2), because
       the two rates come from nested scopes (hbm_share="product" gives the printed (1 - H1)(1 - H2));
-    * each operand's HBM bytes are divided by its row-segment efficiency;
+    * each operand's HBM bytes are divided by its row-segment efficiency (K-contiguous B under a grid of one tile
+      row: every piece of a row is read once, by one workgroup, whose next slab continues the row, so the piece
+      counts twice);
     * the latency is shared by the slabs in flight: L_lat / max(1, tiles_per_cu * (stages - 1)).
     -> dict of the five terms and their maximum."""
     moving = tiles_per_cu if tiles_per_cu_moving is None else tiles_per_cu_moving
@@ -198,7 +200,7 @@ def level_times(hw, v, es, b_layout, tiles_per_cu, active_cus, h_first, h_second
     else:
         miss_both = min(1.0 - h_first, 1.0 - h_second)
     seg_a = segment_efficiency(hw, slab_k_bytes)
-    seg_b = segment_efficiency(hw, (v["block_k"] if b_layout else v["block_n"]) * es)
+    seg_b = segment_efficiency(hw, ((2 if one_tile_row else 1) * v["block_k"] if b_layout else v["block_n"]) * es)
     hbm = (miss_both * (a_moved / seg_a + b_moved / seg_b) * active_cus / hw["hbm_bytes_per_clk"]
            + hw["mem_latency_clk"] / max(1.0, tiles_per_cu * (v["stages"] - 1)))
     return {"l_issue": issue, "l_lds": lds, "l_l2": l2, "l_mall": mall, "l_hbm": hbm,
@@ -301,7 +303,8 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0, batch=1):
     out_bytes = 4.0 if split_k > 1 else 2.0
 
     def wave(tiles_per_cu, active_cus, moving=None, h_first=h1):
-        mem = level_times(hw, v, es, b_layout, tiles_per_cu, active_cus, h_first, h2, rows_valid, cols_valid, moving)
+        mem = level_times(hw, v, es, b_layout, tiles_per_cu, active_cus, h_first, h2, rows_valid, cols_valid, moving,
+                          one_tile_row=tiles_m == 1)
         return dict(mem, **tile_time(hw, v, slab_cost, occ, tiles_per_cu, active_cus, slabs, out_bytes, mem))
 
     full = wave(float(occ), float(hw["n_cu"]))
@@ -319,7 +322,8 @@ def predict(hw, dtype, M, N, K, v, split_k, b_layout=0, stream_k=0, batch=1):
     if stream_k:
         slots = hw["n_cu"] * occ
         whole, left, per_worker = stream_k_split(tiles, slots, slabs)
-        no_l2 = level_times(hw, v, es, b_layout, float(occ), float(hw["n_cu"]), 0.0, h2, rows_valid, cols_valid)
+        no_l2 = level_times(hw, v, es, b_layout, float(occ), float(hw["n_cu"]), 0.0, h2, rows_valid, cols_valid,
+                            one_tile_row=tiles_m == 1)
         l_sk = stream_k_phase(hw, v, occ, slots, left, per_worker, full["l_compute"], no_l2)
         l_sum = stream_k_sum(hw, v, slots, left)
         for name in ("l_compute", "l_issue", "l_lds", "l_l2", "l_mall", "l_hbm", "l_mem", "l_prologue", "l_epilogue",

@@ -375,8 +375,10 @@ void predict(const gemm_hw &hw, int dtype, int b_layout, int64_t M, int64_t N, i
     const double out_bytes = (split_k > 1) ? 4.0 : 2.0;
 
     const double fill_bytes = (double)(v.block_m + v.block_n) * v.block_k * es;   // one slab of one tile
+    // (K-contiguous B under a one-row grid: each piece of a row is read once, by one workgroup, whose next slab
+    // continues the row where this one ended -- twice the piece counts)
     const double ea = segment_efficiency(hw, (double)v.block_k * es);
-    const double eb = segment_efficiency(hw, (double)(b_layout ? v.block_k : v.block_n) * es);
+    const double eb = segment_efficiency(hw, (double)(b_layout ? (tiles_m == 1 ? 2 : 1) * v.block_k : v.block_n) * es);
     auto tile_latency = [&](double per_cu, double act, double per_cu_mem, MemTerms *mt_out, double *l_comp_out,
                             double *pro, double *epi, double *iter) {
         // Compute latency of one K slab of one tile: Algorithm 3's L_MT, plus what the slab's fill and

@@ -52,6 +52,11 @@ def test_checker_functions_reproduce_their_examples():
         assert _close(sm.stream_k_sum(hw, case["variant"], case["slots"], case["left"]), case["expect"]), case["why"]
     for case in f["wave_split"]:
         assert list(sm.wave_split(case["tiles"], case["n_cu"], case["occ"])) == case["expect"], case
+    for case in f["level_times_hbm"]:
+        got = sm.level_times(hw, case["variant"], case["es"], case["b_layout"], case["tiles_per_cu"], case["active_cus"],
+                             case["h_first"], case["h_second"], case["rows_valid"], case["cols_valid"],
+                             one_tile_row=case["one_tile_row"])["l_hbm"]
+        assert _close(got, case["expect"]), case["why"]
 
 
 # ------------------------------------------------------------------ (b) the library against the same literals
