@@ -176,7 +176,10 @@ const char *gemm_strerror(int status);
  * chunks (8 16-bit or 16 fp8 elements; ldc: 8 elements); the caller may overwrite them with larger
  * multiples of that.  N and K themselves need not be such multiples: gemm_run then runs the variant's
  * instantiation that trims the ragged ends in registers (slower than the direct-to-LDS one; the model
- * does not price the difference).  Whatever lies between a row's end and its leading dimension is never
+ * does not price the difference).  A grid of one tile row (M <= BLOCK_M) over weights larger than the hardware
+ * descriptor's mall_bytes runs the variant's weight-streaming instantiation: B's loads carry the non-temporal hint,
+ * and K-contiguous weights whose row pitch is a power of two of 16 KiB or more are walked in a K order rotated by
+ * tile column (the sum over K is then taken in another order than otherwise: still deterministic).  Whatever lies between a row's end and its leading dimension is never
  * used (NaN patterns there do not reach the result) and C's padding is never written; the library does
  * read, without using it, the rest of the 16-byte chunk that holds a row's last element.
  */

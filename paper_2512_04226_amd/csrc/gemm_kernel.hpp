@@ -128,11 +128,12 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // where those elements are cleared, and are written to LDS with ds_write_b128 (a plain two-stage loop: the
 // next slab's global loads fly during the current slab's MFMAs); results at the ragged edge of C are stored
 // element by element.  Everything else -- LDS layout, fragments, MFMAs, staged epilogue -- is shared.
-template <int ES_, int BM_, int BN_, int BK_, int WM_, int WN_, int MI_, int NS_, int BL_, int FT_ = 0, int LF_ = 0, int RG_ = 0>
+template <int ES_, int BM_, int BN_, int BK_, int WM_, int WN_, int MI_, int NS_, int BL_, int FT_ = 0, int LF_ = 0, int RG_ = 0, int ST_ = 0>
 struct Tile {
     static constexpr int ES = ES_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MI = MI_, NS = NS_, BL = BL_;
     static constexpr int FT = FT_;
     static constexpr int RG = RG_;
+    static constexpr int ST = ST_;
 #ifdef G355_FORCE_LOOP_FORM
     static constexpr int LF_ASKED = G355_FORCE_LOOP_FORM;
 #else
@@ -142,23 +143,15 @@ struct Tile {
     static_assert(FT == 0 || ES == 2, "fp16 is a 16-bit input type");
     static constexpr int NW = WM * WN;
     static constexpr int NT = WM * WN * 64;
-    // An operand that only ONE tile row (B) or tile column (A) of the grid reads is read once in all: its slab
-    // loads then carry the non-temporal hint, so that the stream does not push the other operand's panels (which
-    // every workgroup re-reads) out of the L2 (weight streaming at M <= BLOCK_M: 5-10 % on the HBM-bound shapes).
-    // Decided per launch (per group), outside the K loop: a streaming tile carries a second copy of the loop.
-    // Compiled only into the tiles of at most 32 rows, the ones the selector gives weight-streaming shapes
-    // (M <= 32): with a second or third copy of the loop the compiler keeps more values live across all of
-    // them, and the 64- to 128-row tiles then lose a resident workgroup (128x128x64: 120 -> 148 registers).
-    // (The 16-bit 64x128x64 four-stage tile, which one-row grids of 33 to 64 rows are given, carries the copy too: its
-    // four stages leave room for one workgroup per CU whatever its registers.)
-    static constexpr bool STREAMABLE_B = BM <= 32 || (ES == 2 && MI == 16 && BM == 64 && BN == 128 && BK == 64 && NS == 4),
-                          STREAMABLE_A = false;
-    // K-contiguous B: a one-row grid may walk K in a rotated order (see `rot` in gemm_kernel).  Compiled into the
-    // weight-streaming copy of the loop (see STREAMABLE_B) and, of the other tiles, into the one that one-row grids
-    // of 129 to 256 rows are given, whose K-loop form prescribes the instruction order (+-1 % on other shapes): the
-    // few scalar instructions per slab changed the compiler's schedule of the freely scheduled loops (128x128x64:
-    // 4-7 % slower on every shape, the 256x256 tiles 1-2 %, 64x128x64 with four stages 3-5 %).
-    static constexpr bool ROTATES_TALL = BL == 1 && ES == 2 && MI == 16 && BN == 128 && BK == 64 && BM == 256 && NS == 3;
+    // ST_ = 1: the weight-streaming instantiation, which the host launches for a grid of one tile row (M <= BLOCK_M)
+    // over weights of more than 128 MiB.  Every byte of B is then read once: its slab loads carry the non-temporal
+    // hint, so that the stream does not push A's panel, which every workgroup re-reads, out of the L2 (5-10 % on
+    // the HBM-bound shapes), and K-contiguous weights with a power-of-two row pitch are walked in a rotated order
+    // (see `rot` in gemm_kernel).  The cache policy is an immediate of the load instruction and the rotation a
+    // few scalar instructions per slab; as a second copy of the loop inside one kernel either cost the other copy
+    // registers or its schedule (128x128x64: a resident workgroup, or 2-12 % on every other shape), so the
+    // streaming loop is a kernel of its own.
+    static constexpr bool STREAMABLE_B = ST == 1, STREAMABLE_A = false;
     static constexpr int WTM = BM / WM, WTN = BN / WN;      // wave tile
     static constexpr int TM = WTM / MI, TN = WTN / MI;      // MFMA tiles per wave
     static constexpr int KI = (ES == 2) ? (MI == 32 ? 16 : 32) : (MI == 32 ? 64 : 128);  // MI_K
@@ -318,14 +311,13 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     int g_tm = 0, g_tn = 0;
     const bool grouped = args.n_groups > 0;
     // one tile row: B is read once; one tile column: A is read once (see Tile::STREAMABLE_*)
-    bool stream_a = args.tiles_n == 1, stream_b = args.tiles_m == 1;
+    bool stream_a = args.tiles_n == 1, stream_b = T::ST == 1;
     if (grouped) {
         const int X = args.xcd_remap ? args.n_xcd : 1;
         const int x = (int)blockIdx.x % X, q = (int)blockIdx.x / X;
         const GroupRec *r = args.groups + group_of(args.groups, args.n_groups, q);
         const int tiles_m = uniform_i32(r->tiles_m), tiles_n = uniform_i32(r->tiles_n);
         stream_a = tiles_n == 1;
-        stream_b = tiles_m == 1;
         const int t = group_tile(tiles_m * tiles_n, X, x, q - uniform_i32(r->tile_start));
         if (t < 0)
             return;   // idle slot of this XCD (the whole workgroup leaves: nothing was started)
@@ -340,11 +332,6 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         pldc = uniform_i32(r->ldc);
         logical_tile(tiles_m, tiles_n, uniform_i32(r->group_m), t, g_tm, g_tn);
     }
-
-    // Weights that fit the memory-side cache twice over are left to it: a caller that multiplies by the same weights
-    // again soon finds them there (M = 48, N = 14336, K = 4096 in a loop: 21 us cached, 31 us streamed), and the
-    // K order is only worth changing for what comes from HBM.
-    stream_b = stream_b && (size_t)pN * (size_t)pK * ES > ((size_t)128 << 20);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -457,22 +444,22 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
     // `mode` (a std::integral_constant): 0 default cache policy, 1 the B loads stream (one tile row), 2 the A loads
     // stream (one tile column).  A compile-time constant, chosen once outside the K loop: a run-time choice per
     // load would put every load into a basic block of its own and take the loop's schedule apart.
-    // A one-row grid (M <= BLOCK_M: every byte of B is read once) over K-contiguous weights whose row pitch is a power
-    // of two of 16 KiB or more (bf16 K = 8192, ...; from 8 KiB for the tiles of at most 32 rows) walks the K range in
-    // a rotated order, workgroup tn starting tn slabs in.  The workgroups of such a grid advance through K in step, and with such a pitch the rows of every
-    // workgroup's slab fall into the same few memory channels at any one time (N = 28672, K = 8192 bf16: M = 16 83 us,
-    // 68 with the pitch padded by 256 bytes, 69 rotated; M = 64 103 -> 82, M = 256 151 -> 126).  Started at different
-    // slabs they spread over all channels.  Other pitches gain nothing (K = 28672: +-2 %; 8 KiB: fp8 K = 8192 at M = 16 39 -> 35 us
-    // with the small tiles, +2-4 % with the taller ones), and
-    // row-major B loses 1-20 % (there the workgroups' simultaneous reads of adjacent pieces of the same rows are what
-    // keeps DRAM pages open): both keep the plain order.  Only for whole slabs (K range a multiple of BLOCK_K), so
-    // that no slab of the rotated order needs the test against the end of K.
+    // The streaming instantiation (a one-row grid: every byte of B is read once) over K-contiguous weights whose row
+    // pitch is a power of two of 16 KiB or more (bf16 K = 8192, ...; from 8 KiB for the tiles of at most 32 rows)
+    // walks the K range in a rotated order, workgroup tn starting tn slabs in.  The workgroups of such a grid advance
+    // through K in step, and with such a pitch the rows of every workgroup's slab fall into the same few memory
+    // channels at any one time (N = 28672, K = 8192 bf16: M = 16 83 us, 68 with the pitch padded by 256 bytes, 69
+    // rotated; M = 64 104 -> 71, M = 256 139 -> 127).  Started at different slabs they spread over all channels.
+    // Other pitches gain nothing (K = 28672: +-2 %; 8 KiB: fp8 K = 8192 at M = 16 39 -> 35 us with the small tiles,
+    // +2-4 % with the taller ones), and row-major B loses 1-20 % (there the workgroups' simultaneous reads of
+    // adjacent pieces of the same rows are what keeps DRAM pages open): both keep the plain order.  Only for whole
+    // slabs (K range a multiple of BLOCK_K), so that no slab of the rotated order needs the test against the end of K.
     int rot = 0;
     auto issue_one = [&](auto mode, auto tail, int l, int slab, G355_LDS uint8_t *sbase) {
         constexpr int MODE = decltype(mode)::value;
         constexpr bool TAIL = decltype(tail)::value;     // false: the slab lies wholly inside the K range
         int kk = slab * BK;
-        if constexpr (T::BL == 1 && (MODE == 1 || T::ROTATES_TALL)) {
+        if constexpr (T::BL == 1 && MODE == 1) {
             // logical slab -> position in K; slabs requested past the last one stay outside the range
             int p = slab + rot;
             p = p >= kt_count ? p - kt_count : p;
@@ -840,10 +827,10 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         }
     } else if (kt_count > 0) {
       auto pipeline = [&](auto mode) __attribute__((always_inline)) {
-        if constexpr (T::BL == 1 && (decltype(mode)::value == 1 || T::ROTATES_TALL)) {
+        if constexpr (T::BL == 1 && decltype(mode)::value == 1) {
             const unsigned pitch = (unsigned)pldb * ES;
             constexpr unsigned MIN_PITCH = BM <= 32 ? 8192 : 16384;
-            rot = (stream_b && k_len % BK == 0 && pitch >= MIN_PITCH && (pitch & (pitch - 1)) == 0) ? tn % kt_count : 0;
+            rot = (k_len % BK == 0 && pitch >= MIN_PITCH && (pitch & (pitch - 1)) == 0) ? tn % kt_count : 0;
         }
 #pragma unroll
         for (int s = 0; s < T::NS; ++s)
@@ -956,22 +943,17 @@ __global__ __launch_bounds__(T::NT) void gemm_kernel(const KernelArgs args)
         if constexpr (LF != 0)
             mma_kstep((T::KSTEPS - 1) & 1);
       };
-      // one tile row: B is read once and streams; else one tile column: A streams (see Tile::STREAMABLE_*)
-      bool done = false;
+      // the streaming instantiation: B is read once and streams (see Tile::STREAMABLE_B); a kernel has one copy of the loop
       if constexpr (T::STREAMABLE_B) {
-          if (stream_b) {
-              pipeline(std::integral_constant<int, 1>{});
-              done = true;
-          }
-      }
-      if constexpr (T::STREAMABLE_A) {
-          if (!done && stream_a) {
+          pipeline(std::integral_constant<int, 1>{});
+      } else if constexpr (T::STREAMABLE_A) {
+          if (stream_a)
               pipeline(std::integral_constant<int, 2>{});
-              done = true;
-          }
-      }
-      if (!done)
+          else
+              pipeline(std::integral_constant<int, 0>{});
+      } else {
           pipeline(std::integral_constant<int, 0>{});
+      }
     }
     // nothing may still be in flight towards LDS when the workgroup ends
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

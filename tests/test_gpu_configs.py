@@ -284,41 +284,51 @@ def test_k_contiguous_b_fp8_and_padded_ldb(g, oracle):
 
 
 @pytest.mark.parametrize("M", [1, 16, 100])
-def test_k_contiguous_weights_with_a_power_of_two_pitch(g, oracle, M):
-    """One tile row over K-contiguous weights of more than 128 MiB whose row pitch is a power of two of at least 16 KiB
-    (K = 8192 bf16, 16384 fp8; from 8 KiB, K = 4096 bf16, for the tiles of at most 32 rows): the tiles that carry the
-    weight-streaming copy of the loop, and the 256x128x64 tile, then walk K in an order rotated by their tile column
-    (whole slabs; also inside every K split; at M = 100 the tiles of 64 rows have two tile rows and keep the plain order).
-    Integer operands: any order of the K sum is exact, so every configuration must match the oracle bit for bit.
-    A second K (the same pitch of the allocation, K itself not a whole number of slabs) takes the plain order."""
+def test_weight_streaming_instantiation_and_rotated_k_order(g, oracle, M):
+    """A grid of one tile row over weights larger than the memory-side cache runs the weight-streaming instantiation;
+    over K-contiguous weights whose row pitch is a power of two of at least 16 KiB (K = 8192 bf16, 16384 fp8; from
+    8 KiB, K = 4096 bf16, for the tiles of at most 32 rows) it walks K in an order rotated by tile column (whole
+    slabs; also inside every K split).  The test shrinks the cache size in the hardware descriptor so that small
+    weights take that path.  Integer operands: any order of the K sum is exact, so every configuration, in both
+    layouts, must match the oracle bit for bit.  A second K (the same pitch of the allocation, K itself not a whole
+    number of slabs) takes the plain order; at M = 100 the tiles of 64 rows and fewer have several tile rows and run
+    the plain instantiation."""
     from gpu_util import run_cfg, to_dev
-    cases = [(BF16, 8600, 8192, 8192), (BF16, 8600, 8000, 8192), (BF16, 16400, 4096, 4096)]
+    hw = g.gemm_hw_get()
+    small = g.gemm_hw_get()
+    small.mall_bytes = 1 << 20
+    N = 1008           # whole 16-byte chunks in both datatypes (a ragged N runs the trimming instantiation instead)
+    cases = [(BF16, 8192, 8192), (BF16, 8000, 8192), (BF16, 4096, 4096)]
     if M <= 16:
-        cases.append((E4M3, 8600, 16384, 16384))
-    for dtype, N, K, ld in cases:
-        assert N * K * (2 if dtype == BF16 else 1) > 128 << 20
-        if dtype == BF16:
-            A, B = wl.integer_bf16(M, N, K, seed=77, case=M + K)
-        else:
-            gen = np.random.default_rng(M + K)
-            vals = np.array([0, 1, 2, 3, 4, -1, -2, -3, -4], dtype=np.float64)
-            A = oracle.encode_e4m3(vals[gen.integers(0, 9, size=(M, K))])
-            B = oracle.encode_e4m3(vals[gen.integers(0, 9, size=(K, N))])
-        ref16, _ = oracle.gemm(A, B, dtype)
-        Bt = np.zeros((N, ld), B.dtype)
-        Bt[:, :K] = B.T
-        dA, dBt = to_dev(A), to_dev(Bt)
-        n_one_row = 0
-        for idx in range(g.gemm_cfg_count(dtype)):
-            c = g.gemm_cfg_at_ex(idx, M, N, K, dtype, g.GEMM_B_K_CONTIGUOUS)
-            if c is None or (c.split_k > 4 and not c.stream_k) or (c.block_m < M and c.split_k > 1):
-                continue
-            c.ldb = ld
-            out = run_cfg(c, dA, dBt, M, N)
-            assert np.array_equal(out, ref16), (c.describe(), K, int((out != ref16).sum()))
-            n_one_row += c.block_m >= M
-        assert n_one_row >= 10
-        del dBt
+        cases.append((E4M3, 16384, 16384))
+    try:
+        g.gemm_hw_set(small)
+        for dtype, K, ld in cases:
+            if dtype == BF16:
+                A, B = wl.integer_bf16(M, N, K, seed=77, case=M + K)
+            else:
+                gen = np.random.default_rng(M + K)
+                vals = np.array([0, 1, 2, 3, 4, -1, -2, -3, -4], dtype=np.float64)
+                A = oracle.encode_e4m3(vals[gen.integers(0, 9, size=(M, K))])
+                B = oracle.encode_e4m3(vals[gen.integers(0, 9, size=(K, N))])
+            ref16, _ = oracle.gemm(A, B, dtype)
+            Bt = np.zeros((N, ld), B.dtype)
+            Bt[:, :K] = B.T
+            for b_layout, dB in ((g.GEMM_B_K_CONTIGUOUS, to_dev(Bt)), (0, to_dev(B))):
+                dA = to_dev(A)
+                n_one_row = 0
+                for idx in range(g.gemm_cfg_count(dtype)):
+                    c = g.gemm_cfg_at_ex(idx, M, N, K, dtype, b_layout)
+                    if c is None:
+                        continue
+                    if b_layout:
+                        c.ldb = ld
+                    out = run_cfg(c, dA, dB, M, N)
+                    assert np.array_equal(out, ref16), (c.describe(), K, int((out != ref16).sum()))
+                    n_one_row += c.block_m >= M
+                assert n_one_row >= 10
+    finally:
+        g.gemm_hw_set(hw)
 
 
 def test_k_contiguous_b_square_4096(g, oracle):

@@ -35,7 +35,7 @@ def _usage(src):
 
 def _tile(es, bm, bn, bk, wm, wn, mi, ns, bl, ft):
     """Regular expression for the whole-chunk instantiation of a tile, whatever K-loop form the table gives it."""
-    return "TileI" + "".join("Li%dE" % x for x in (es, bm, bn, bk, wm, wn, mi, ns, bl, ft)) + r"Li\d+ELi0EEEEE"
+    return "TileI" + "".join("Li%dE" % x for x in (es, bm, bn, bk, wm, wn, mi, ns, bl, ft)) + r"Li\d+ELi0ELi0EEEEE"
 
 
 @pytest.mark.skipif(shutil.which(HIPCC) is None and not os.path.exists(HIPCC), reason="needs hipcc")
