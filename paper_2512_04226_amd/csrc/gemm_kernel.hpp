@@ -128,6 +128,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // where those elements are cleared, and are written to LDS with ds_write_b128 (a plain two-stage loop: the
 // next slab's global loads fly during the current slab's MFMAs); results at the ragged edge of C are stored
 // element by element.  Everything else -- LDS layout, fragments, MFMAs, staged epilogue -- is shared.
+// ST_: 1 = the weight-streaming instantiation for grids of one tile row (see STREAMABLE_B in Tile).
 template <int ES_, int BM_, int BN_, int BK_, int WM_, int WN_, int MI_, int NS_, int BL_, int FT_ = 0, int LF_ = 0, int RG_ = 0, int ST_ = 0>
 struct Tile {
     static constexpr int ES = ES_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MI = MI_, NS = NS_, BL = BL_;
@@ -144,7 +145,7 @@ struct Tile {
     static constexpr int NW = WM * WN;
     static constexpr int NT = WM * WN * 64;
     // ST_ = 1: the weight-streaming instantiation, which the host launches for a grid of one tile row (M <= BLOCK_M)
-    // over weights of more than 128 MiB.  Every byte of B is then read once: its slab loads carry the non-temporal
+    // over weights larger than the memory-side cache.  Every byte of B is then read once: its slab loads carry the non-temporal
     // hint, so that the stream does not push A's panel, which every workgroup re-reads, out of the L2 (5-10 % on
     // the HBM-bound shapes), and K-contiguous weights with a power-of-two row pitch are walked in a rotated order
     // (see `rot` in gemm_kernel).  The cache policy is an immediate of the load instruction and the rotation a
